@@ -1,0 +1,168 @@
+/*
+ * tdq.h — C ABI of libtdq: the DSTG + DCRP W4A4 quantized linear path of COD-TDQ
+ * as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * Notation follows the paper: an activation tensor X[B, T, C] (B images, T tokens
+ * per image, C channels), a weight W[N, C] with per-output-channel scales s[N],
+ * q_max = 7, q_min = -8, step-to-dispersion bound tau, zero-bin mass bound zr.
+ *
+ * A quantization group here is (image b, token set S_j), j < G: every token of an
+ * image is put into one of G token sets by its range, and all C channels of all
+ * tokens of a set share one clip radius c[b, j] and one step Delta[b, j].
+ * G = 1 is per-image ("per-tensor") quantization.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    keeps no state, allocates nothing, launches asynchronously on `stream`
+ *    (a hipStream_t passed as void*, NULL = the default stream) and never
+ *    synchronises.
+ *  - Arguments are checked on the host before anything is launched; a bad
+ *    argument returns a negative tdq_status and launches nothing.  A HIP launch
+ *    error returns TDQ_ERR_HIP.  No C++ exception crosses the ABI.
+ *  - Row-major; leading dimensions (ld_*) are in ELEMENTS of the array they
+ *    belong to (bytes for the packed-code arrays).
+ *  - Packed int4 codes: two's-complement nibbles, element 2i in bits 0-3 and
+ *    element 2i+1 in bits 4-7 of byte i of the row; an odd C leaves the last high
+ *    nibble zero.  (The paper leaves packing to the implementation, Sec. 3.3
+ *    "Static Symmetric Weight Quantization".)
+ */
+#ifndef TDQ_H
+#define TDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TDQ_VERSION 100
+
+typedef enum { TDQ_F16 = 0, TDQ_F32 = 1 } tdq_dtype;
+
+typedef enum {
+  TDQ_OK = 0,
+  TDQ_ERR_NULL = -1,        /* a required pointer is NULL                        */
+  TDQ_ERR_SHAPE = -2,       /* B, T, C, N, K or a leading dimension is invalid   */
+  TDQ_ERR_PARAM = -3,       /* tdq_params out of range                           */
+  TDQ_ERR_WORKSPACE = -4,   /* workspace too small or misaligned                 */
+  TDQ_ERR_DTYPE = -5,       /* unknown tdq_dtype                                 */
+  TDQ_ERR_HIP = -6,         /* a HIP call failed                                 */
+  TDQ_ERR_UNSUPPORTED = -7, /* valid request that this build does not implement  */
+  TDQ_ERR_ALIGN = -8        /* pointer / leading dimension alignment             */
+} tdq_status;
+
+#define TDQ_FLAG_C1 1u /* constraint C1: Delta <= tau * sigma   (Eq. tau_constraint) */
+#define TDQ_FLAG_C2 2u /* constraint C2: Delta/2 <= Q_zr(|x|)   (Eq. zr_constraint)  */
+
+#define TDQ_MAX_GROUPS 256
+
+/* Hyper-parameters (Supp. "Default Hyperparameters": tau = 1.0, zr = 0.2). */
+typedef struct tdq_params {
+  int32_t n_groups;   /* G token sets per image, 1..TDQ_MAX_GROUPS                */
+  int32_t chan_group; /* channel block g; 0 = whole row (the only value built)    */
+  int32_t act_bits;   /* 4                                                        */
+  uint32_t flags;     /* TDQ_FLAG_C1 | TDQ_FLAG_C2 = DCRP; 0 = base radius only   */
+  double tau;         /* > 0                                                      */
+  double zr;          /* in (0,1); rank k = ceil(zr * n) in binary64              */
+  double base_pct;    /* 0 or 1 = max-abs base radius (the only value built)      */
+  float eps_scale;    /* floor of clip radius and step, 1e-8 (Supp. numerical conv.) */
+  float eps_std;      /* added to the population std, 1e-12                       */
+} tdq_params;
+
+/* What bound the projection c = min(c_base, c_tau, c_zr) of Eq. (dcrp). */
+enum { TDQ_BIND_BASE = 0, TDQ_BIND_C1 = 1, TDQ_BIND_C2 = 2, TDQ_BIND_EPS = 3, TDQ_BIND_EMPTY = 4 };
+
+/* Per-(image, token set) record written by tdq_calibrate_groups. */
+typedef struct tdq_group_stats {
+  int64_t n;      /* elements in the group = tokens * C                          */
+  int64_t k;      /* rank of the zr quantile, clamp(ceil(zr n), 1, n)             */
+  float c_base;   /* max |x|                              (Eq. DSTG_clip)          */
+  float sigma;    /* population std + eps_std                                     */
+  float thr;      /* k-th smallest |x| (an element of the data)                   */
+  float c_tau;    /* q_max * tau * sigma                  (Eq. tau_constraint)     */
+  float c_zr;     /* 2 * q_max * thr                      (Eq. zr_constraint)      */
+  float clip;     /* c   after projection and eps floor   (Eq. dcrp)               */
+  float scale;    /* Delta = max(c / q_max, eps_scale)    (Eq. clipx)              */
+  uint32_t bind;  /* TDQ_BIND_*                                                   */
+} tdq_group_stats;
+
+/* Bits of the device status word (first uint32 of the workspace after a call
+ * to tdq_calibrate_groups; read it back after synchronising the stream). */
+#define TDQ_DEV_NONFINITE 1u /* X holds an Inf or NaN: results undefined          */
+
+int tdq_version(void);
+const char* tdq_status_string(int status);
+
+/* Fills *p with the paper's defaults (G = 8, tau = 1, zr = 0.2, DCRP on). */
+void tdq_default_params(tdq_params* p);
+
+/* Bytes of device scratch tdq_calibrate_groups needs for this shape; 0 if the
+ * shape or params are invalid.  The workspace must be 256-byte aligned. */
+size_t tdq_workspace_bytes(int32_t B, int32_t T, int32_t C, tdq_dtype dt, const tdq_params* p);
+
+/*
+ * DSTG statistics + token-set assignment + DCRP projection.
+ *
+ *  1. per token: range r_t = max_c |x_tc| and the moments sum x, sum x^2
+ *     (Sec. 4.2: base radius and within-group dispersion);
+ *  2. per image: gid[t] in [0, G) from the bit pattern of r_t — G equal-width
+ *     bins between the image's smallest and largest key, the lower end raised to
+ *     at most 24 octaves below the top (integer arithmetic, exact);
+ *  3. per group: c_base = max r_t, sigma = population std + eps_std;
+ *     thr = the ceil(zr n)-th smallest |x| of the group (exact radix select on the
+ *     magnitude bit patterns with LDS histograms);
+ *  4. c = max(min(c_base, q_max tau sigma, 2 q_max thr), eps),
+ *     Delta = max(c / q_max, eps)                    (Eqs. dcrp, clipx; Lemma 1).
+ *
+ * X        [B*T, ld_x] of dt, ld_x >= C (elements)
+ * group_id [B*T] out, clip [B*G] out, scale [B*G] out, stats [B*G] out or NULL.
+ * An empty token set gets clip = scale = eps_scale.
+ */
+int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                         int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                         float* scale, tdq_group_stats* stats, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
+ * Quantize + pack (Eqs. clipx, dequant): for row t of image b with j = gid,
+ *   q = clamp(rint(clip(x, -c[b,j], c[b,j]) / Delta[b,j]), -8, 7)
+ * with a correctly rounded binary32 quotient and ties-to-even rounding, written as
+ * packed nibbles.  Qx [B*T, ld_q] bytes, ld_q >= ceil(C/2); bytes past ceil(C/2)
+ * of a row are not written.
+ */
+int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                     const tdq_params* p, const int32_t* group_id, const float* clip,
+                     const float* scale, uint8_t* Qx, int64_t ld_q, void* stream);
+
+/*
+ * W4A4 contraction with the dequantizing epilogue (Supp. Algorithm 1, step 10,
+ * written on the integer codes):
+ *   acc[m, n] = sum_i Qx[m, i] * Qw[n, i]                      (int32, exact)
+ *   Y[m, n]   = (float(acc) * Delta[b(m)*G + gid[m]]) * w_scale[n] (+ bias[n])
+ * each product rounded to binary32, no fused multiply-add.
+ *
+ * Qx [B*T, ld_q], Qw [N, ld_w] packed codes; both pointers 16-byte aligned and
+ * ld_q, ld_w multiples of 16 with ld >= 16*ceil(K/32) (rows are read in 16-byte
+ * pieces; bytes past ceil(K/2) are ignored).  Y [B*T, ld_y] of y_dt (fp32 or fp16).
+ * acc_dump [B*T, N] int32 or NULL.  bias [N] or NULL.  group_id may be NULL when
+ * G == 1.
+ */
+int tdq_w4a4_linear(const uint8_t* Qx, int64_t ld_q, const int32_t* group_id, const float* scale,
+                    int32_t B, int32_t T, int32_t K, int32_t N, int32_t G, const uint8_t* Qw,
+                    int64_t ld_w, const float* w_scale, const float* bias, void* Y,
+                    tdq_dtype y_dt, int64_t ld_y, int32_t* acc_dump, void* stream);
+
+/*
+ * Static symmetric per-output-channel weight quantization (Eq. weight_quant),
+ * done once offline:  s_o = max(max_i |W_oi|, 1e-8) / 7,
+ * Qw = clamp(rint(W / s_o), -8, 7) packed.  W [N, K] fp32 (device),
+ * Qw [N, ld_w] bytes (bytes from ceil(K/2) to ld_w are zeroed), w_scale [N].
+ */
+int tdq_quantize_weight(const float* W, int32_t N, int32_t K, int64_t ld_w_in, uint8_t* Qw,
+                        int64_t ld_w, float* w_scale, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TDQ_H */

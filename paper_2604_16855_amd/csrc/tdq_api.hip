@@ -1,0 +1,227 @@
+// C ABI of libtdq: argument validation on the host, workspace layout, and the
+// launch sequence of each entry point.  Nothing here computes on the data.
+#include <math.h>
+#include <string.h>
+
+#include "tdq_internal.hpp"
+
+namespace tdq {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+LevelPlan make_level_plan(tdq_dtype dt, int G) {
+  LevelPlan lp;
+  memset(&lp, 0, sizeof(lp));
+  lp.key_bits = dt == TDQ_F16 ? 15 : 31;
+  int max_bits = 0;
+  while ((G << (max_bits + 1)) <= kHistLdsWords && max_bits + 1 <= kMaxLevelBits) ++max_bits;
+  if (max_bits < 1) max_bits = 1;
+  const int n = (lp.key_bits + max_bits - 1) / max_bits;
+  lp.n_levels = n;
+  int left = lp.key_bits;
+  for (int l = 0; l < n; ++l) {
+    const int levels_left = n - l;
+    int b = (left + levels_left - 1) / levels_left;     // spread the bits evenly
+    lp.bits[l] = b;
+    left -= b;
+    lp.shift[l] = left;
+  }
+  return lp;
+}
+
+WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {
+  WorkspaceLayout w;
+  memset(&w, 0, sizeof(w));
+  const size_t M = (size_t)B * T, BG = (size_t)B * G;
+  size_t off = 0;
+  w.status = off;   off = align256(off + 64 * sizeof(unsigned));
+  w.img_flag = off; off = align256(off + (size_t)B * sizeof(unsigned));
+  w.r = off;        off = align256(off + M * sizeof(float));
+  w.s1 = off;       off = align256(off + M * sizeof(double));
+  w.s2 = off;       off = align256(off + M * sizeof(double));
+  w.grp = off;      off = align256(off + BG * sizeof(GroupWork));
+  w.hist = off;
+  for (int l = 0; l < lp.n_levels; ++l) {
+    w.hist_level[l] = off;
+    off += BG * ((size_t)1 << lp.bits[l]) * sizeof(unsigned);   // levels are contiguous
+  }
+  w.total = align256(off);
+  return w;
+}
+
+static int check_params(const tdq_params* p) {
+  if (!p) return TDQ_ERR_NULL;
+  if (p->n_groups < 1 || p->n_groups > TDQ_MAX_GROUPS) return TDQ_ERR_PARAM;
+  if (p->act_bits != 4) return p->act_bits == 8 ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
+  if (p->flags & ~(TDQ_FLAG_C1 | TDQ_FLAG_C2)) return TDQ_ERR_PARAM;
+  if (!(p->tau > 0.0) || !isfinite(p->tau)) return TDQ_ERR_PARAM;
+  if (!(p->zr > 0.0 && p->zr < 1.0)) return TDQ_ERR_PARAM;
+  if (!(p->eps_scale > 0.f) || !(p->eps_std >= 0.f)) return TDQ_ERR_PARAM;
+  if (p->chan_group != 0) return p->chan_group > 0 ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
+  if (p->base_pct != 0.0 && p->base_pct != 1.0)
+    return (p->base_pct > 0.0 && p->base_pct < 1.0) ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
+  return TDQ_OK;
+}
+
+static int check_shape(int32_t B, int32_t T, int32_t C, int64_t ld_x) {
+  if (B < 1 || T < 1 || C < 1) return TDQ_ERR_SHAPE;
+  if (ld_x < C) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
+  return TDQ_OK;
+}
+
+static Scalars make_scalars(const tdq_params* p) {
+  Scalars s;
+  s.qmax = (float)kQMax;
+  s.qmax_tau = (float)kQMax * (float)p->tau;   // binary32 product, as in the definition
+  s.two_qmax = 2.0f * (float)kQMax;
+  s.eps_scale = p->eps_scale;
+  s.eps_std = (double)p->eps_std;
+  s.zr = p->zr;
+  s.flags = p->flags;
+  return s;
+}
+
+}  // namespace tdq
+
+using namespace tdq;
+
+extern "C" {
+
+int tdq_version(void) { return TDQ_VERSION; }
+
+const char* tdq_status_string(int status) {
+  switch (status) {
+    case TDQ_OK: return "ok";
+    case TDQ_ERR_NULL: return "null pointer";
+    case TDQ_ERR_SHAPE: return "invalid shape or leading dimension";
+    case TDQ_ERR_PARAM: return "parameter out of range";
+    case TDQ_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case TDQ_ERR_DTYPE: return "unknown dtype";
+    case TDQ_ERR_HIP: return "HIP call failed";
+    case TDQ_ERR_UNSUPPORTED: return "not implemented in this build";
+    case TDQ_ERR_ALIGN: return "pointer or leading dimension misaligned";
+    default: return "unknown status";
+  }
+}
+
+void tdq_default_params(tdq_params* p) {
+  if (!p) return;
+  p->n_groups = 8;
+  p->chan_group = 0;
+  p->act_bits = 4;
+  p->flags = TDQ_FLAG_C1 | TDQ_FLAG_C2;
+  p->tau = 1.0;
+  p->zr = 0.2;
+  p->base_pct = 0.0;
+  p->eps_scale = 1e-8f;
+  p->eps_std = 1e-12f;
+}
+
+size_t tdq_workspace_bytes(int32_t B, int32_t T, int32_t C, tdq_dtype dt, const tdq_params* p) {
+  if (check_params(p) != TDQ_OK) return 0;
+  if (check_shape(B, T, C, C) != TDQ_OK) return 0;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return 0;
+  const LevelPlan lp = make_level_plan(dt, p->n_groups);
+  return make_layout(B, T, p->n_groups, lp).total;
+}
+
+int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                         int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                         float* scale, tdq_group_stats* stats, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (!X || !p || !group_id || !clip || !scale || !workspace) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  const int G = p->n_groups;
+  const LevelPlan lp = make_level_plan(dt, G);
+  const WorkspaceLayout wl = make_layout(B, T, G, lp);
+  if (workspace_bytes < wl.total) return TDQ_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return TDQ_ERR_WORKSPACE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  unsigned* status = reinterpret_cast<unsigned*>(ws + wl.status);
+  unsigned* img_flag = reinterpret_cast<unsigned*>(ws + wl.img_flag);
+  float* r = reinterpret_cast<float*>(ws + wl.r);
+  double* s1 = reinterpret_cast<double*>(ws + wl.s1);
+  double* s2 = reinterpret_cast<double*>(ws + wl.s2);
+  GroupWork* grp = reinterpret_cast<GroupWork*>(ws + wl.grp);
+  unsigned* hist = reinterpret_cast<unsigned*>(ws + wl.hist);
+  const Scalars sc = make_scalars(p);
+  const int M = B * T;
+
+  if (launch_token_stats(X, dt, M, C, ld_x, r, s1, s2, st) != hipSuccess) return TDQ_ERR_HIP;
+  if (launch_assign(r, s1, s2, B, T, C, G, sc, group_id, grp, hist, img_flag, lp, st) != hipSuccess)
+    return TDQ_ERR_HIP;
+  for (int l = 0; l < lp.n_levels; ++l) {
+    unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
+    if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], st) !=
+        hipSuccess)
+      return TDQ_ERR_HIP;
+    if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
+                      scale, stats, img_flag, status, st) != hipSuccess)
+      return TDQ_ERR_HIP;
+  }
+  return TDQ_OK;
+}
+
+int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                     const tdq_params* p, const int32_t* group_id, const float* clip,
+                     const float* scale, uint8_t* Qx, int64_t ld_q, void* stream) {
+  if (!X || !p || !clip || !scale || !Qx) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  if (!group_id && p->n_groups != 1) return TDQ_ERR_NULL;
+  if (ld_q < (C + 1) / 2) return TDQ_ERR_SHAPE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if (launch_quantize(X, dt, B, T, C, ld_x, p->n_groups, group_id, clip, scale, Qx, ld_q,
+                      static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+int tdq_w4a4_linear(const uint8_t* Qx, int64_t ld_q, const int32_t* group_id, const float* scale,
+                    int32_t B, int32_t T, int32_t K, int32_t N, int32_t G, const uint8_t* Qw,
+                    int64_t ld_w, const float* w_scale, const float* bias, void* Y,
+                    tdq_dtype y_dt, int64_t ld_y, int32_t* acc_dump, void* stream) {
+  if (!Qx || !scale || !Qw || !w_scale || !Y) return TDQ_ERR_NULL;
+  if (y_dt != TDQ_F16 && y_dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  if (B < 1 || T < 1 || K < 1 || N < 1) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
+  if (K > 131072) return TDQ_ERR_SHAPE;     // 256 * 64 * K must stay below 2^31
+  if (G < 1 || G > TDQ_MAX_GROUPS) return TDQ_ERR_PARAM;
+  if (!group_id && G != 1) return TDQ_ERR_NULL;
+  const int64_t row_bytes = 16 * (((int64_t)K + 31) / 32);
+  if (ld_q < row_bytes || ld_w < row_bytes || ld_y < N) return TDQ_ERR_SHAPE;
+  if (ld_q % 16 || ld_w % 16) return TDQ_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(Qx) & 15) || (reinterpret_cast<uintptr_t>(Qw) & 15))
+    return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(Y) % (y_dt == TDQ_F16 ? 2 : 4)) return TDQ_ERR_ALIGN;
+  if (launch_w4a4_gemm(Qx, ld_q, group_id, scale, B * T, T, K, N, G, Qw, ld_w, w_scale, bias, Y,
+                       y_dt, ld_y, acc_dump, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+int tdq_quantize_weight(const float* W, int32_t N, int32_t K, int64_t ld_w_in, uint8_t* Qw,
+                        int64_t ld_w, float* w_scale, void* stream) {
+  if (!W || !Qw || !w_scale) return TDQ_ERR_NULL;
+  if (N < 1 || K < 1 || ld_w_in < K || ld_w < (K + 1) / 2) return TDQ_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(W) & 3) return TDQ_ERR_ALIGN;
+  if (launch_quantize_weight(W, N, K, ld_w_in, Qw, ld_w, w_scale,
+                             static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,226 @@
+"""Thin binding over the C ABI of libtdq (include/tdq.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch is used for device memory and streams and nothing else.  The
+functions carry the names of the C entry points and fail loudly when the
+library is missing — there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch  # first: the library resolves libamdhip64 against the copy torch loaded
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtdq.so")
+
+TDQ_F16, TDQ_F32 = 0, 1
+FLAG_C1, FLAG_C2 = 1, 2
+DEV_NONFINITE = 1
+BIND_NAMES = ("base", "C1", "C2", "eps", "empty")
+
+ERR_NULL, ERR_SHAPE, ERR_PARAM, ERR_WORKSPACE = -1, -2, -3, -4
+ERR_DTYPE, ERR_HIP, ERR_UNSUPPORTED, ERR_ALIGN = -5, -6, -7, -8
+
+
+class Params(C.Structure):
+    """Mirror of tdq_params."""
+
+    _fields_ = [("n_groups", C.c_int32), ("chan_group", C.c_int32), ("act_bits", C.c_int32),
+                ("flags", C.c_uint32), ("tau", C.c_double), ("zr", C.c_double),
+                ("base_pct", C.c_double), ("eps_scale", C.c_float), ("eps_std", C.c_float)]
+
+
+class GroupStats(C.Structure):
+    """Mirror of tdq_group_stats (48 bytes)."""
+
+    _fields_ = [("n", C.c_int64), ("k", C.c_int64), ("c_base", C.c_float), ("sigma", C.c_float),
+                ("thr", C.c_float), ("c_tau", C.c_float), ("c_zr", C.c_float), ("clip", C.c_float),
+                ("scale", C.c_float), ("bind", C.c_uint32)]
+
+
+class TdqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libtdq.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2604_16855_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.tdq_version.restype = C.c_int
+    L.tdq_status_string.restype = C.c_char_p
+    L.tdq_status_string.argtypes = [C.c_int]
+    L.tdq_default_params.restype = None
+    L.tdq_default_params.argtypes = [C.POINTER(Params)]
+    L.tdq_workspace_bytes.restype = sz
+    L.tdq_workspace_bytes.argtypes = [i32, i32, i32, C.c_int, C.POINTER(Params)]
+    L.tdq_calibrate_groups.restype = C.c_int
+    L.tdq_calibrate_groups.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
+                                       vp, vp, vp, sz, vp]
+    L.tdq_quantize_act.restype = C.c_int
+    L.tdq_quantize_act.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp, vp,
+                                   vp, i64, vp]
+    L.tdq_w4a4_linear.restype = C.c_int
+    L.tdq_w4a4_linear.argtypes = [vp, i64, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp, vp, vp,
+                                  C.c_int, i64, vp, vp]
+    L.tdq_quantize_weight.restype = C.c_int
+    L.tdq_quantize_weight.argtypes = [vp, i32, i32, i64, vp, i64, vp, vp]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().tdq_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().tdq_version())
+
+
+def default_params(n_groups: int = 8, tau: float = 1.0, zr: float = 0.2,
+                   flags: int = FLAG_C1 | FLAG_C2) -> Params:
+    p = Params()
+    lib().tdq_default_params(C.byref(p))
+    p.n_groups, p.tau, p.zr, p.flags = n_groups, tau, zr, flags
+    return p
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return TDQ_F16
+    if t.dtype == torch.float32:
+        return TDQ_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise TdqError(rc, where)
+
+
+def _btc(X: torch.Tensor) -> Tuple[int, int, int, int]:
+    if (X.dim() != 3 or X.stride(2) != 1
+            or (X.shape[0] > 1 and X.stride(0) != X.shape[1] * X.stride(1))):
+        raise ValueError("X must be [B, T, C] with contiguous channels and uniform row stride")
+    return X.shape[0], X.shape[1], X.shape[2], X.stride(1)
+
+
+def workspace_bytes(B: int, T: int, C_: int, dt: int, p: Params) -> int:
+    return int(lib().tdq_workspace_bytes(B, T, C_, dt, C.byref(p)))
+
+
+def alloc_workspace(B: int, T: int, C_: int, dt: int, p: Params, device) -> torch.Tensor:
+    n = workspace_bytes(B, T, C_, dt, p)
+    if n == 0:
+        raise TdqError(ERR_PARAM, "tdq_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def tdq_calibrate_groups(X: torch.Tensor, p: Params, workspace: Optional[torch.Tensor] = None,
+                         want_stats: bool = False, out=None):
+    """-> (group_id[B,T] int32, clip[B,G] f32, scale[B,G] f32, stats or None, workspace).
+    `stats` is a uint8 tensor [B*G, 48] holding tdq_group_stats records (see
+    `stats_to_numpy`).  Asynchronous on the current stream."""
+    B, T, Cc, ld = _btc(X)
+    G = p.n_groups
+    dev = X.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, Cc, _dt(X), p, dev)
+    if out is None:
+        gid = torch.empty((B, T), dtype=torch.int32, device=dev)
+        clip = torch.empty((B, G), dtype=torch.float32, device=dev)
+        scale = torch.empty((B, G), dtype=torch.float32, device=dev)
+    else:
+        gid, clip, scale = out
+    stats = (torch.empty((B * G, C.sizeof(GroupStats)), dtype=torch.uint8, device=dev)
+             if want_stats else None)
+    rc = lib().tdq_calibrate_groups(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p), gid.data_ptr(),
+                                    clip.data_ptr(), scale.data_ptr(), _ptr(stats),
+                                    workspace.data_ptr(), workspace.numel(), _stream())
+    _check(rc, "tdq_calibrate_groups")
+    return gid, clip, scale, stats, workspace
+
+
+def device_status(workspace: torch.Tensor) -> int:
+    """Status word left by the last tdq_calibrate_groups (synchronises)."""
+    return int(workspace[:4].view(torch.int32).item())
+
+
+def stats_to_numpy(stats: torch.Tensor):
+    import numpy as np
+    dt = np.dtype([("n", "<i8"), ("k", "<i8"), ("c_base", "<f4"), ("sigma", "<f4"), ("thr", "<f4"),
+                   ("c_tau", "<f4"), ("c_zr", "<f4"), ("clip", "<f4"), ("scale", "<f4"),
+                   ("bind", "<u4")])
+    return stats.cpu().numpy().view(dt).reshape(-1)
+
+
+def packed_row_bytes(K: int) -> int:
+    """Leading dimension (bytes) the contraction wants for K codes per row."""
+    return 16 * ((K + 31) // 32)
+
+
+def tdq_quantize_act(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],
+                     clip: torch.Tensor, scale: torch.Tensor,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """-> Qx[B*T, ld_q] uint8 packed int4 codes (ld_q = 16*ceil(C/32), bytes past
+    ceil(C/2) of a row are zero on a fresh buffer)."""
+    B, T, Cc, ld = _btc(X)
+    if out is None:
+        out = torch.zeros((B * T, packed_row_bytes(Cc)), dtype=torch.uint8, device=X.device)
+    rc = lib().tdq_quantize_act(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p), _ptr(gid),
+                                clip.data_ptr(), scale.data_ptr(), out.data_ptr(), out.stride(0),
+                                _stream())
+    _check(rc, "tdq_quantize_act")
+    return out
+
+
+def tdq_quantize_weight(W: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """W[N, K] fp32 (device) -> (Qw[N, ld_w] uint8 packed, w_scale[N] f32)."""
+    if W.dtype != torch.float32 or W.dim() != 2 or W.stride(1) != 1:
+        raise ValueError("W must be fp32 [N, K] with contiguous rows")
+    N, K = W.shape
+    Qw = torch.empty((N, packed_row_bytes(K)), dtype=torch.uint8, device=W.device)
+    ws = torch.empty((N,), dtype=torch.float32, device=W.device)
+    rc = lib().tdq_quantize_weight(W.data_ptr(), N, K, W.stride(0), Qw.data_ptr(), Qw.stride(0),
+                                   ws.data_ptr(), _stream())
+    _check(rc, "tdq_quantize_weight")
+    return Qw, ws
+
+
+def tdq_w4a4_linear(Qx: torch.Tensor, gid: Optional[torch.Tensor], scale: torch.Tensor, B: int,
+                    T: int, K: int, Qw: torch.Tensor, w_scale: torch.Tensor,
+                    bias: Optional[torch.Tensor] = None, out_dtype=torch.float32,
+                    out: Optional[torch.Tensor] = None, acc_dump: Optional[torch.Tensor] = None
+                    ) -> torch.Tensor:
+    """-> Y[B*T, N].  scale is [B, G]; gid [B, T] (may be None when G == 1)."""
+    N = Qw.shape[0]
+    G = scale.shape[1] if scale.dim() == 2 else scale.numel() // B
+    if out is None:
+        out = torch.empty((B * T, N), dtype=out_dtype, device=Qx.device)
+    rc = lib().tdq_w4a4_linear(Qx.data_ptr(), Qx.stride(0), _ptr(gid), scale.data_ptr(), B, T, K, N,
+                               G, Qw.data_ptr(), Qw.stride(0), w_scale.data_ptr(), _ptr(bias),
+                               out.data_ptr(), _dt(out), out.stride(0), _ptr(acc_dump), _stream())
+    _check(rc, "tdq_w4a4_linear")
+    return out

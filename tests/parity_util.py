@@ -1,0 +1,124 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI
+binding, run the CPU oracle on the same inputs, and compare with the bars
+stated for this path (group ids / codes / accumulators bit-exact, scales 1e-6
+relative, code flips only within 1e-5 of a step of a rounding boundary and at
+most 1e-4 of the elements, fp32 outputs 1e-5 relative)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import tdq_oracle as O
+from paper_2604_16855_amd import tdq
+
+SCALE_RTOL = 1e-6
+FLIP_DIST = 1e-5
+FLIP_FRAC = 1e-4
+OUT_RTOL = 1e-5
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def oracle_params(p: tdq.Params) -> O.Params:
+    return O.Params(n_groups=p.n_groups, flags=p.flags, tau=p.tau, zr=p.zr)
+
+
+def gpu_calibrate(X: np.ndarray, p: tdq.Params, ld_pad: int = 0):
+    """X[B,T,C] numpy -> dict of numpy results from tdq_calibrate_groups."""
+    Xd = to_device(X, ld_pad)
+    gid, clip, scale, stats, ws = tdq.tdq_calibrate_groups(Xd, p, want_stats=True)
+    torch.cuda.synchronize()
+    return dict(Xd=Xd, gid_d=gid, clip_d=clip, scale_d=scale, gid=gid.cpu().numpy(),
+                clip=clip.cpu().numpy(), scale=scale.cpu().numpy(),
+                stats=tdq.stats_to_numpy(stats), status=tdq.device_status(ws))
+
+
+def to_device(X: np.ndarray, ld_pad: int = 0) -> torch.Tensor:
+    """Host array -> device tensor, optionally with a padded row stride."""
+    t = torch.from_numpy(np.ascontiguousarray(X))
+    if ld_pad:
+        B, T, C = X.shape
+        buf = torch.full((B, T, C + ld_pad), 7.0, dtype=t.dtype)   # junk in the padding
+        buf[:, :, :C] = t
+        return buf.to(dev())[:, :, :C]
+    return t.to(dev())
+
+
+def unpack_device_codes(Q: torch.Tensor, C: int) -> np.ndarray:
+    return O.unpack_nibbles(Q.cpu().numpy()[:, :(C + 1) // 2], C)
+
+
+def assert_calibration_matches(g: dict, X: np.ndarray, p: tdq.Params):
+    """gid, n, k, thr, c_base, c_zr bit-exact; sigma and scales to 1e-6."""
+    B, T, C = X.shape
+    G = p.n_groups
+    gid, clip, scale, st = O.calibrate_groups(X, oracle_params(p))
+    assert np.array_equal(g["gid"], gid), "group ids differ"
+    gs = g["stats"].reshape(B, G)
+    for b in range(B):
+        for j in range(G):
+            o, s = st[b][j], gs[b, j]
+            assert s["n"] == o["n"], (b, j)
+            if o["n"] == 0:
+                assert s["bind"] == 4
+                continue
+            assert s["k"] == o["k"], (b, j)
+            assert s["thr"] == o["thr"], (b, j, s["thr"], o["thr"])
+            assert s["c_base"] == o["c_base"], (b, j)
+            assert s["c_zr"] == o["c_zr"], (b, j)
+            assert abs(float(s["sigma"]) - float(o["sigma"])) <= SCALE_RTOL * float(o["sigma"]), \
+                (b, j, s["sigma"], o["sigma"])
+    assert np.allclose(g["clip"], clip, rtol=SCALE_RTOL, atol=0), "clip radii differ"
+    assert np.allclose(g["scale"], scale, rtol=SCALE_RTOL, atol=0), "steps differ"
+    assert np.array_equal(gs["clip"], g["clip"]) and np.array_equal(gs["scale"], g["scale"])
+    return gid, clip, scale, st
+
+
+def assert_codes_match(q_gpu: np.ndarray, q_ref: np.ndarray, X: np.ndarray, c_row: np.ndarray,
+                       d_row: np.ndarray, exact: bool):
+    """q arrays [M, C]; c_row/d_row [M] are the ORACLE's clip and step per row."""
+    diff = q_gpu != q_ref
+    n_flip = int(diff.sum())
+    if exact:
+        assert n_flip == 0, f"{n_flip} codes differ although the scales are bit-identical"
+        return 0
+    assert n_flip <= FLIP_FRAC * q_ref.size, f"{n_flip} flips of {q_ref.size}"
+    if n_flip:
+        m, c = np.nonzero(diff)
+        x = X.reshape(q_ref.shape)[m, c].astype(np.float64)
+        y = np.clip(x, -c_row[m].astype(np.float64), c_row[m].astype(np.float64)) / d_row[m]
+        dist = np.abs(np.abs(y - np.floor(y)) - 0.5)
+        assert (dist <= FLIP_DIST).all(), "a differing code is not at a rounding boundary"
+        assert (np.abs(q_gpu[m, c].astype(int) - q_ref[m, c].astype(int)) == 1).all()
+    return n_flip
+
+
+def gpu_linear(Qx_d, gid_d, scale_d, B, T, K, Qw_d, ws_d, bias_d=None, out_dtype=torch.float32,
+               dump=True):
+    N = Qw_d.shape[0]
+    acc = torch.empty((B * T, N), dtype=torch.int32, device=dev()) if dump else None
+    Y = tdq.tdq_w4a4_linear(Qx_d, gid_d, scale_d, B, T, K, Qw_d, ws_d, bias_d, out_dtype,
+                            acc_dump=acc)
+    torch.cuda.synchronize()
+    return (acc.cpu().numpy() if dump else None), Y.cpu().numpy()
+
+
+def pack_to_device(codes: np.ndarray) -> torch.Tensor:
+    """int8 codes [R, K] -> device uint8 [R, 16*ceil(K/32)] packed, junk-free."""
+    R, K = codes.shape
+    ld = tdq.packed_row_bytes(K)
+    buf = np.zeros((R, ld), dtype=np.uint8)
+    pk = O.pack_nibbles(codes)
+    buf[:, :pk.shape[1]] = pk
+    return torch.from_numpy(buf).to(dev())
+
+
+def assert_outputs_close(Y: np.ndarray, Yref: np.ndarray, rtol: float = OUT_RTOL):
+    Y = Y.astype(np.float64)
+    Yref = Yref.astype(np.float64)
+    tol = rtol * np.abs(Yref) + 1e-30
+    bad = np.abs(Y - Yref) > tol
+    assert not bad.any(), f"{int(bad.sum())} outputs differ, worst " \
+                          f"{np.max(np.abs(Y - Yref) / (np.abs(Yref) + 1e-30))}"

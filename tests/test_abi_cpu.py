@@ -1,0 +1,125 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before launching."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_16855_amd import tdq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tdq.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(tdq.LIB_PATH),
+                                reason="libtdq.so not built (python -m paper_2604_16855_amd.build)")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(tdq_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
+            "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
+            "tdq_status_string", "tdq_default_params"} <= set(names)
+    L = tdq.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_strings():
+    assert tdq.version() == 100
+    assert tdq.status_string(0) == "ok"
+    for s in range(-8, 0):
+        assert tdq.status_string(s) != "unknown status"
+    assert tdq.status_string(-99) == "unknown status"
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(tdq.Params) == 48
+    assert C.sizeof(tdq.GroupStats) == 48
+    p = tdq.default_params()
+    assert (p.n_groups, p.act_bits, p.flags, p.tau, p.zr) == (8, 4, 3, 1.0, 0.2)
+    assert abs(p.eps_scale - 1e-8) < 1e-15 and abs(p.eps_std - 1e-12) < 1e-19
+
+
+def test_workspace_bytes():
+    p = tdq.default_params(n_groups=16)
+    n = tdq.workspace_bytes(1, 7744, 64, tdq.TDQ_F16, p)
+    assert n > 7744 * 20 and n % 256 == 0
+    assert tdq.workspace_bytes(32, 4096, 1024, tdq.TDQ_F16, tdq.default_params(32)) > \
+        tdq.workspace_bytes(1, 4096, 1024, tdq.TDQ_F16, tdq.default_params(32))
+    assert tdq.workspace_bytes(0, 10, 10, tdq.TDQ_F16, p) == 0
+    assert tdq.workspace_bytes(1, 10, 10, 7, p) == 0
+    bad = tdq.default_params(n_groups=0)
+    assert tdq.workspace_bytes(1, 10, 10, tdq.TDQ_F16, bad) == 0
+
+
+FAKE = 4096   # a non-null, aligned "device pointer"; never dereferenced by a failing call
+
+
+def _calib(p, X=FAKE, dt=tdq.TDQ_F16, B=1, T=8, Cc=8, ld=8, gid=FAKE, clip=FAKE, scale=FAKE,
+           ws=FAKE, wsb=1 << 30):
+    return tdq.lib().tdq_calibrate_groups(X, dt, B, T, Cc, ld, C.byref(p), gid, clip, scale, None,
+                                          ws, wsb, None)
+
+
+def test_calibrate_rejects_bad_arguments():
+    p = tdq.default_params()
+    assert _calib(p, X=None) == tdq.ERR_NULL
+    assert _calib(p, gid=None) == tdq.ERR_NULL
+    assert _calib(p, ws=None) == tdq.ERR_NULL
+    assert _calib(p, dt=5) == tdq.ERR_DTYPE
+    assert _calib(p, B=0) == tdq.ERR_SHAPE
+    assert _calib(p, ld=7) == tdq.ERR_SHAPE
+    assert _calib(p, wsb=16) == tdq.ERR_WORKSPACE
+    assert _calib(p, ws=FAKE + 8) == tdq.ERR_WORKSPACE
+    assert _calib(p, X=FAKE + 1) == tdq.ERR_ALIGN
+    for field, val, err in (("n_groups", 0, tdq.ERR_PARAM), ("n_groups", 257, tdq.ERR_PARAM),
+                            ("tau", 0.0, tdq.ERR_PARAM), ("zr", 0.0, tdq.ERR_PARAM),
+                            ("zr", 1.0, tdq.ERR_PARAM), ("flags", 4, tdq.ERR_PARAM),
+                            ("act_bits", 3, tdq.ERR_PARAM), ("act_bits", 8, tdq.ERR_UNSUPPORTED),
+                            ("chan_group", 32, tdq.ERR_UNSUPPORTED),
+                            ("base_pct", 0.99, tdq.ERR_UNSUPPORTED),
+                            ("eps_scale", 0.0, tdq.ERR_PARAM)):
+        q = tdq.default_params()
+        setattr(q, field, val)
+        assert _calib(q) == err, (field, val)
+
+
+def test_quantize_and_linear_reject_bad_arguments():
+    L = tdq.lib()
+    p = tdq.default_params()
+    q = L.tdq_quantize_act
+    assert q(None, 0, 1, 8, 8, 8, C.byref(p), FAKE, FAKE, FAKE, FAKE, 4, None) == tdq.ERR_NULL
+    assert q(FAKE, 0, 1, 8, 8, 8, C.byref(p), None, FAKE, FAKE, FAKE, 4, None) == tdq.ERR_NULL
+    assert q(FAKE, 0, 1, 8, 8, 8, C.byref(p), FAKE, FAKE, FAKE, FAKE, 3, None) == tdq.ERR_SHAPE
+    assert q(FAKE, 9, 1, 8, 8, 8, C.byref(p), FAKE, FAKE, FAKE, FAKE, 4, None) == tdq.ERR_DTYPE
+    g = L.tdq_w4a4_linear
+    ok = dict(Qx=FAKE, ld_q=32, gid=FAKE, scale=FAKE, B=1, T=8, K=64, N=8, G=4, Qw=FAKE, ld_w=32,
+              ws=FAKE, bias=None, Y=FAKE, ydt=1, ld_y=8, dump=None, st=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return g(a["Qx"], a["ld_q"], a["gid"], a["scale"], a["B"], a["T"], a["K"], a["N"], a["G"],
+                 a["Qw"], a["ld_w"], a["ws"], a["bias"], a["Y"], a["ydt"], a["ld_y"], a["dump"],
+                 a["st"])
+
+    assert call(Qx=None) == tdq.ERR_NULL
+    assert call(gid=None) == tdq.ERR_NULL          # G > 1 needs group ids
+    assert call(K=0) == tdq.ERR_SHAPE
+    assert call(K=200000) == tdq.ERR_SHAPE
+    assert call(ld_q=16) == tdq.ERR_SHAPE          # 64 codes need 32 bytes
+    assert call(ld_q=40) == tdq.ERR_ALIGN
+    assert call(Qw=FAKE + 4) == tdq.ERR_ALIGN
+    assert call(ld_y=4) == tdq.ERR_SHAPE
+    assert call(ydt=3) == tdq.ERR_DTYPE
+    assert call(G=0) == tdq.ERR_PARAM
+    w = L.tdq_quantize_weight
+    assert w(None, 8, 8, 8, FAKE, 4, FAKE, None) == tdq.ERR_NULL
+    assert w(FAKE, 8, 8, 4, FAKE, 4, FAKE, None) == tdq.ERR_SHAPE
+    assert w(FAKE, 8, 8, 8, FAKE, 3, FAKE, None) == tdq.ERR_SHAPE

@@ -1,0 +1,338 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.  Stage-wise protocol: every stage is
+checked (i) end to end from X and (ii) in isolation, fed the oracle's upstream
+outputs, where group ids, codes and accumulators must be bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tdq_oracle as O
+from paper_2604_16855_amd import inputs as I
+from paper_2604_16855_amd import tdq
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _full_path(lc, p, X, W, bias=None, ld_pad=0, out_dtype=torch.float32):
+    """Runs calibrate -> quantize -> linear on the GPU and checks every stage."""
+    B, T, C = X.shape
+    N = W.shape[0]
+    _say(f"[case] {lc} B={B} T={T} C={C} N={N} G={p.n_groups} dtype={X.dtype} ld_pad={ld_pad}")
+    g = U.gpu_calibrate(X, p, ld_pad)
+    assert g["status"] == 0
+    gid, clip, scale, st = U.assert_calibration_matches(g, X, p)
+    op = U.oracle_params(p)
+
+    # (ii) quantizer in isolation: oracle gid / clip / step in, codes bit-exact out
+    gid_d = torch.from_numpy(gid).to(U.dev())
+    clip_d = torch.from_numpy(clip).to(U.dev())
+    scale_d = torch.from_numpy(scale).to(U.dev())
+    Q_iso = tdq.tdq_quantize_act(g["Xd"], p, gid_d, clip_d, scale_d)
+    q_ref = O.quantize_act(X, gid, clip, scale, op).reshape(B * T, C)
+    q_iso = U.unpack_device_codes(Q_iso, C)
+    assert np.array_equal(q_iso, q_ref), "codes differ given identical scales"
+    if C % 2:      # the pad nibble of an odd row is zero
+        assert not (Q_iso.cpu().numpy()[:, C // 2] >> 4).any()
+
+    # (i) quantizer end to end: GPU's own calibration
+    Q_e2e = tdq.tdq_quantize_act(g["Xd"], p, g["gid_d"], g["clip_d"], g["scale_d"])
+    q_e2e = U.unpack_device_codes(Q_e2e, C)
+    rows = np.arange(B)[:, None]
+    c_row = clip[rows, gid].reshape(-1)
+    d_row = scale[rows, gid].reshape(-1)
+    exact = np.array_equal(g["scale"], scale) and np.array_equal(g["clip"], clip)
+    flips = U.assert_codes_match(q_e2e, q_ref, X, c_row, d_row, exact)
+    _say(f"  scales bit-identical: {exact}; code flips end-to-end: {flips}")
+
+    # weights: offline quantizer parity
+    Wd = torch.from_numpy(W).to(U.dev())
+    Qw_d, ws_d = tdq.tdq_quantize_weight(Wd)
+    qw_ref, sw_ref = O.quantize_weight(W)
+    assert np.array_equal(U.unpack_device_codes(Qw_d, C), qw_ref)
+    assert np.array_equal(ws_d.cpu().numpy(), sw_ref)
+
+    # (ii) contraction in isolation: oracle codes and scales in
+    bias_d = None if bias is None else torch.from_numpy(bias).to(U.dev())
+    acc, Y = U.gpu_linear(Q_iso, gid_d, scale_d, B, T, C, Qw_d, ws_d, bias_d, out_dtype)
+    acc_ref, Y_ref = O.w4a4_linear(q_ref, O.row_scales(gid, scale), qw_ref, sw_ref, bias)
+    assert np.array_equal(acc, acc_ref), "int32 accumulators differ"
+    if out_dtype == torch.float16:
+        assert np.array_equal(Y, Y_ref.astype(np.float16))
+    else:
+        assert np.array_equal(Y, Y_ref), "fp32 epilogue differs given identical inputs"
+
+    # (i) contraction end to end; the oracle contraction re-run on the GPU's codes
+    acc2, Y2 = U.gpu_linear(Q_e2e, g["gid_d"], g["scale_d"], B, T, C, Qw_d, ws_d, bias_d, out_dtype)
+    acc2_ref, Y2_ref = O.w4a4_linear(q_e2e, O.row_scales(g["gid"], g["scale"]), qw_ref, sw_ref,
+                                     bias)
+    assert np.array_equal(acc2, acc2_ref)
+    if out_dtype == torch.float32:
+        assert np.array_equal(Y2, Y2_ref)
+        if flips == 0:
+            floor = 0 if bias is None else np.abs(bias)[None, :]
+            err = np.abs(Y2.astype(np.float64) - Y_ref)
+            assert (err <= U.OUT_RTOL * (np.abs(Y_ref) + floor) + 1e-30).all()
+    return g
+
+
+# --------------------------------------------------------------- named configs
+def test_cfg0_fp32_full_path():
+    lc = I.case("cfg0")
+    X, _ = I.make_activations(lc)
+    _full_path("cfg0", tdq.default_params(lc.G), X, I.make_weight(lc), I.make_bias(lc))
+
+
+def test_cfg1_fp16_full_path():
+    lc = I.case("cfg1")
+    X, _ = I.make_activations(lc)
+    _full_path("cfg1", tdq.default_params(lc.G), X, I.make_weight(lc))
+
+
+@pytest.mark.parametrize("name", ["cfg2_qkv", "cfg2_proj", "cfg2_fc2"])
+def test_cfg2_linears(name):
+    lc = I.case(name, B=4)          # 4 of the 16 images keep the oracle's GEMM to seconds
+    X, _ = I.make_activations(lc)
+    _full_path(name, tdq.default_params(lc.G), X, I.make_weight(lc))
+
+
+def test_cfg2_activation_path_full_batch():
+    lc = I.case("cfg2_fc1")
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G)
+    g = U.gpu_calibrate(X, p)
+    U.assert_calibration_matches(g, X, p)
+
+
+@pytest.mark.parametrize("name", ["cfg3_s2_kv", "cfg3_s4_fc1", "cfg3_s3_q"])
+def test_cfg3_shapes(name):
+    lc = I.case(name, B=2)
+    X, _ = I.make_activations(lc)
+    _full_path(name, tdq.default_params(lc.G), X, I.make_weight(lc), I.make_bias(lc))
+
+
+# --------------------------------------------------- ragged / unaligned shapes
+@pytest.mark.parametrize("B,T,C,N,G,dtype,ld_pad", [
+    (3, 37, 70, 19, 5, "f16", 0),      # C not a multiple of 8
+    (2, 50, 33, 7, 4, "f16", 0),       # odd C: pad nibble
+    (2, 41, 64, 130, 8, "f16", 3),     # row stride not a multiple of 8: scalar loads
+    (1, 1, 8, 1, 4, "f32", 0),         # a single token
+    (2, 3, 24, 5, 16, "f16", 0),       # more token sets than tokens
+    (2, 129, 100, 257, 32, "f32", 1),  # tile tails everywhere
+    (1, 300, 520, 96, 1, "f16", 0),    # one token set = per-image quantization
+    (1, 64, 2050, 40, 8, "f16", 0),    # many K stages plus a ragged last one
+])
+def test_ragged_shapes(B, T, C, N, G, dtype, ld_pad):
+    lc = I.LinearCase("ragged", B, T, C, N, G, dtype, 0.1, 0.1, False, (T, 1), 500 + C)
+    X, _ = I.make_activations(lc)
+    _full_path("ragged", tdq.default_params(G), X, I.make_weight(lc), I.make_bias(lc), ld_pad)
+
+
+@pytest.mark.parametrize("flags,tau,zr", [(0, 1.0, 0.2), (1, 0.3, 0.2), (2, 1.0, 0.05),
+                                          (3, 0.5, 0.5), (3, 2.0, 0.9)])
+def test_dcrp_variants(flags, tau, zr):
+    lc = I.case("cfg1", grid=(40, 40))
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G, tau=tau, zr=zr, flags=flags)
+    g = _full_path(f"variants flags={flags}", p, X, I.make_weight(lc))
+    binds = set(int(b) for b in g["stats"]["bind"])
+    if flags == 0:
+        assert binds <= {0, 4}
+    if flags == 1:
+        assert 2 not in binds
+    if flags == 2:
+        assert 1 not in binds
+
+
+def test_fp16_output():
+    lc = I.case("cfg2_proj", B=2)
+    X, _ = I.make_activations(lc)
+    _full_path("fp16 out", tdq.default_params(lc.G), X, I.make_weight(lc), I.make_bias(lc),
+               out_dtype=torch.float16)
+
+
+# ------------------------------------------------------------ degenerate input
+def test_degenerate_groups():
+    rng = np.random.Generator(np.random.PCG64(9))
+    X = rng.laplace(0, 1, (4, 40, 32)).astype(np.float16)
+    X[0] = 0                      # an all-zero image: every clip on the eps floor
+    X[1] = np.float16(2.5)        # a constant image: sigma = 1e-12, codes +1
+    X[2, :20] = 0                 # zero tokens beside normal ones (24-octave floor)
+    X[3, :, ::2] = 0              # half the elements exactly zero: thr = 0
+    p = tdq.default_params(4)
+    g = U.gpu_calibrate(X, p)
+    gid, clip, scale, st = U.assert_calibration_matches(g, X, p)
+    assert (g["clip"][0] == np.float32(1e-8)).all() and (g["clip"][1] == np.float32(1e-8)).all()
+    Q = tdq.tdq_quantize_act(g["Xd"], p, g["gid_d"], g["clip_d"], g["scale_d"])
+    q = U.unpack_device_codes(Q, 32)
+    q_ref = O.quantize_act(X, gid, clip, scale, U.oracle_params(p)).reshape(-1, 32)
+    exact = np.array_equal(g["scale"], scale)
+    U.assert_codes_match(q, q_ref, X, clip[np.arange(4)[:, None], gid].reshape(-1),
+                         scale[np.arange(4)[:, None], gid].reshape(-1), exact)
+    assert not q[:40].any() and (q[40:80] == 1).all()
+
+
+def test_nonfinite_flag():
+    X = np.ones((2, 16, 16), dtype=np.float16)
+    p = tdq.default_params(2)
+    assert U.gpu_calibrate(X, p)["status"] == 0
+    X[1, 3, 5] = np.inf
+    assert U.gpu_calibrate(X, p)["status"] == tdq.DEV_NONFINITE
+    X[1, 3, 5] = np.nan
+    assert U.gpu_calibrate(X, p)["status"] == tdq.DEV_NONFINITE
+    Xf = np.ones((1, 8, 8), dtype=np.float32)
+    Xf[0, 0, 0] = -np.inf
+    assert U.gpu_calibrate(Xf, p)["status"] == tdq.DEV_NONFINITE
+
+
+def test_user_supplied_radii_are_clamped():
+    """tdq_quantize_act with radii that are not a projection's (clip >> 7 step):
+    codes clamp to [-8, 7] as the definition says."""
+    rng = np.random.Generator(np.random.PCG64(10))
+    X = (rng.laplace(0, 4, (1, 32, 64))).astype(np.float32)
+    gid = np.zeros((1, 32), np.int32)
+    clip = np.array([[100.0]], np.float32)
+    scale = np.array([[0.37]], np.float32)
+    p = tdq.default_params(1)
+    Q = tdq.tdq_quantize_act(U.to_device(X), p, None, torch.from_numpy(clip).to(U.dev()),
+                             torch.from_numpy(scale).to(U.dev()))
+    q = U.unpack_device_codes(Q, 64)
+    q_ref = O.quantize_act(X, gid, clip, scale, U.oracle_params(p)).reshape(-1, 64)
+    assert np.array_equal(q, q_ref) and q.min() == -8 and q.max() == 7
+
+
+# --------------------------------------------------- contraction on raw codes
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (5, 31, 3), (64, 33, 64), (129, 64, 130),
+                                   (300, 100, 17), (128, 257, 128), (257, 1024, 200),
+                                   (100, 4100, 50)])
+def test_contraction_full_code_range(M, K, N):
+    """Codes drawn from the whole nibble range, -8 included; ragged M, N, K."""
+    _say(f"[gemm] M={M} K={K} N={N}")
+    qx = I.random_codes((M, K), 11 * M + K)
+    qw = I.random_codes((N, K), 13 * N + K)
+    rng = np.random.Generator(np.random.PCG64(M + K + N))
+    B, T = (1, M) if M % 3 else (3, M // 3)
+    G = 4
+    gid = rng.integers(0, G, (B, T)).astype(np.int32)
+    scale = rng.uniform(0.01, 2.0, (B, G)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    bias = rng.normal(0, 0.02, N).astype(np.float32)
+    acc, Y = U.gpu_linear(U.pack_to_device(qx), torch.from_numpy(gid).to(U.dev()),
+                          torch.from_numpy(scale).to(U.dev()), B, T, K, U.pack_to_device(qw),
+                          torch.from_numpy(sw).to(U.dev()), torch.from_numpy(bias).to(U.dev()))
+    acc_ref, Y_ref = O.w4a4_linear(qx, O.row_scales(gid, scale), qw, sw, bias)
+    assert np.array_equal(acc, acc_ref)
+    assert np.array_equal(Y, Y_ref)
+
+
+def test_contraction_extreme_accumulator():
+    """Every product at its largest magnitude: |acc| = 64 K."""
+    M, K, N = 40, 4096, 36
+    qx = np.full((M, K), -8, np.int8)
+    qw = np.full((N, K), -8, np.int8)
+    qw[::2] = 7
+    scale = np.ones((1, 1), np.float32)
+    sw = np.ones(N, np.float32)
+    acc, Y = U.gpu_linear(U.pack_to_device(qx), None, torch.from_numpy(scale).to(U.dev()), 1, M,
+                          K, U.pack_to_device(qw), torch.from_numpy(sw).to(U.dev()))
+    acc_ref, Y_ref = O.w4a4_linear(qx, np.ones(M, np.float32), qw, sw)
+    assert np.array_equal(acc, acc_ref) and acc.max() == 64 * K and acc.min() == -56 * K
+    assert np.array_equal(Y, Y_ref)
+
+
+def test_junk_past_row_end_is_ignored():
+    """Bytes between ceil(K/2) and the leading dimension must not reach the result."""
+    M, K, N = 33, 40, 20          # 20 packed bytes per row, ld = 32
+    qx = I.random_codes((M, K), 1)
+    qw = I.random_codes((N, K), 2)
+    A = U.pack_to_device(qx)
+    Bm = U.pack_to_device(qw)
+    A[:, 20:] = 0xAB
+    Bm[:, 20:] = 0xCD
+    scale = np.ones((1, 1), np.float32)
+    sw = np.ones(N, np.float32)
+    acc, _ = U.gpu_linear(A, None, torch.from_numpy(scale).to(U.dev()), 1, M, K, Bm,
+                          torch.from_numpy(sw).to(U.dev()))
+    assert np.array_equal(acc, O.int_accumulate(qx, qw))
+
+
+# ------------------------------------------------------------------ invariants
+def test_repeatable_bitwise():
+    lc = I.case("cfg2_qkv", B=3)
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G)
+    a = U.gpu_calibrate(X, p)
+    b = U.gpu_calibrate(X, p)
+    for k in ("gid", "clip", "scale"):
+        assert np.array_equal(a[k], b[k])
+    assert a["stats"].tobytes() == b["stats"].tobytes()
+
+
+def test_token_permutation_invariance_on_gpu():
+    lc = I.case("cfg1", grid=(48, 48))
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G)
+    a = U.gpu_calibrate(X, p)
+    perm = np.random.Generator(np.random.PCG64(5)).permutation(lc.T)
+    b = U.gpu_calibrate(X[:, perm], p)
+    assert np.array_equal(a["gid"][:, perm], b["gid"])
+    for k in ("n", "k", "thr", "c_base", "c_zr"):
+        assert np.array_equal(a["stats"][k], b["stats"][k])
+    assert np.allclose(a["scale"], b["scale"], rtol=1e-6, atol=0)
+
+
+# ------------------------------------------------- full size, sampled checks
+@pytest.mark.timeout(900)
+def test_cfg4_full_size_sampled():
+    """ViT-L-shaped stress at its full size in the launch configuration the
+    benchmark times; the oracle checks two whole images of the calibration and
+    sampled rows of codes and outputs."""
+    lc = I.case("cfg4_fc1_h10")
+    _say("[cfg4] generating inputs")
+    X, _ = I.make_activations(lc, workers=16)
+    W = I.make_weight(lc)
+    p = tdq.default_params(lc.G)
+    B, T, C, N, G = lc.B, lc.T, lc.C, lc.N, lc.G
+    _say("[cfg4] GPU path")
+    Xd = torch.from_numpy(X).to(U.dev())
+    gid_d, clip_d, scale_d, stats_d, ws = tdq.tdq_calibrate_groups(Xd, p, want_stats=True)
+    Q = tdq.tdq_quantize_act(Xd, p, gid_d, clip_d, scale_d)
+    Qw_d, ws_d = tdq.tdq_quantize_weight(torch.from_numpy(W).to(U.dev()))
+    Y = tdq.tdq_w4a4_linear(Q, gid_d, scale_d, B, T, C, Qw_d, ws_d)
+    torch.cuda.synchronize()
+    assert tdq.device_status(ws) == 0
+    gid, clip, scale = gid_d.cpu().numpy(), clip_d.cpu().numpy(), scale_d.cpu().numpy()
+    stats = tdq.stats_to_numpy(stats_d).reshape(B, G)
+    op = U.oracle_params(p)
+    qw_ref, sw_ref = O.quantize_weight(W)
+    assert np.array_equal(ws_d.cpu().numpy(), sw_ref)
+    # properties that hold at any size
+    assert int(stats["n"].sum()) == B * T * C
+    used = stats["n"] > 0
+    assert (stats["scale"][used] <= stats["sigma"][used] * (1 + 1e-6)).all()         # C1
+    assert (stats["scale"][used] / 2 <= stats["thr"][used] * (1 + 1e-6)).all()       # C2
+    for b in (0, B - 1):
+        _say(f"[cfg4] oracle calibration of image {b}")
+        g1, c1, s1, st1 = O.calibrate_groups(X[b:b + 1], op)
+        assert np.array_equal(gid[b], g1[0])
+        for j in range(G):
+            if st1[0][j]["n"]:
+                assert stats[b, j]["thr"] == st1[0][j]["thr"]
+                assert stats[b, j]["k"] == st1[0][j]["k"]
+        assert np.allclose(clip[b], c1[0], rtol=1e-6, atol=0)
+        assert np.allclose(scale[b], s1[0], rtol=1e-6, atol=0)
+        rows = np.random.Generator(np.random.PCG64(b)).choice(T, 48, replace=False)
+        q_ref = O.quantize_codes(X[b, rows], c1[0][g1[0][rows]][:, None],
+                                 s1[0][g1[0][rows]][:, None], op)
+        q_gpu = O.unpack_nibbles(Q[b * T + torch.from_numpy(rows).to(U.dev())].cpu().numpy(), C)
+        exact = np.array_equal(scale[b], s1[0]) and np.array_equal(clip[b], c1[0])
+        U.assert_codes_match(q_gpu, q_ref, X[b, rows], c1[0][g1[0][rows]], s1[0][g1[0][rows]],
+                             exact)
+        acc_ref, Y_ref = O.w4a4_linear(q_gpu, scale[b][gid[b, rows]], qw_ref, sw_ref)
+        Y_gpu = Y[b * T + torch.from_numpy(rows).to(U.dev())].cpu().numpy()
+        assert np.array_equal(Y_gpu, Y_ref)
