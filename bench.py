@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSTG+DCRP W4A4 linear hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of the ViT-L-shaped
+stress workload (config 4: batch 32, 4096 tokens, fc1 1024->4096 and fc2
+4096->1024, 32 token groups per image): for each of the two linears
+tdq_calibrate_groups -> tdq_quantize_act -> tdq_w4a4_linear.  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--heavy 10] [--small]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--heavy", type=int, default=10, choices=(2, 10, 25),
+                    help="heavy-tailed token fraction of config 4, percent")
+    ap.add_argument("--small", action="store_true",
+                    help="4 images instead of 32 (quick functional run, not the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-quality", action="store_true")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device-resident state of one quantized linear."""
+
+    def __init__(self, lc, out_dtype, torch, tdq, I, dev):
+        self.lc = lc
+        X, cls = I.make_activations(lc, workers=16)
+        self.X_host, self.cls = X, cls
+        self.X = torch.from_numpy(X).to(dev)
+        W = torch.from_numpy(I.make_weight(lc)).to(dev)
+        self.Qw, self.w_scale = tdq.tdq_quantize_weight(W)      # offline, not timed
+        self.p = tdq.default_params(lc.G)
+        dt = tdq.TDQ_F16 if lc.dtype == "f16" else tdq.TDQ_F32
+        self.ws = tdq.alloc_workspace(lc.B, lc.T, lc.C, dt, self.p, dev)
+        self.gid = torch.empty((lc.B, lc.T), dtype=torch.int32, device=dev)
+        self.clip = torch.empty((lc.B, lc.G), dtype=torch.float32, device=dev)
+        self.scale = torch.empty((lc.B, lc.G), dtype=torch.float32, device=dev)
+        self.Q = torch.zeros((lc.M, tdq.packed_row_bytes(lc.C)), dtype=torch.uint8, device=dev)
+        self.Y = torch.empty((lc.M, lc.N), dtype=out_dtype, device=dev)
+        e = lc.M * lc.C
+        s = 2 if lc.dtype == "f16" else 4
+        sweeps_cal = 3 if lc.dtype == "f16" else 1 + 4       # stats + radix levels
+        self.bytes = {
+            "calibrate": sweeps_cal * e * s + lc.M * 20,
+            "quantize": e * s + lc.M * 4 + e // 2,
+            "compulsory": e * s + e // 2,
+        }
+        ob = 2 if out_dtype == torch.float16 else 4
+        self.gemm_ops = 2 * lc.M * lc.N * lc.C
+        self.gemm_bytes = lc.M * lc.C // 2 + lc.N * lc.C // 2 + lc.M * lc.N * ob + 4 * (lc.M + lc.N)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (images are independent, so a larger job "
+              "would shard the batch with no exchange); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2604_16855_amd import inputs as I
+    from paper_2604_16855_amd import tdq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    tdq.lib()        # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    over = dict(B=4) if args.small else {}
+    t0 = time.time()
+    fc1 = Layer(I.case(f"cfg4_fc1_h{args.heavy}", **over), torch.float16, torch, tdq, I, dev)
+    fc2 = Layer(I.case(f"cfg4_fc2_h{args.heavy}", **over), torch.float32, torch, tdq, I, dev)
+    layers = [fc1, fc2]
+    torch.cuda.synchronize()
+    print(f"[bench] inputs ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    seg_names = ["calibrate", "quantize", "linear"]
+
+    def step(events=None):
+        for li, L in enumerate(layers):
+            lc = L.lc
+            if events is not None:
+                events[li][0].record()
+            tdq.tdq_calibrate_groups(L.X, L.p, L.ws, out=(L.gid, L.clip, L.scale))
+            if events is not None:
+                events[li][1].record()
+            tdq.tdq_quantize_act(L.X, L.p, L.gid, L.clip, L.scale, out=L.Q)
+            if events is not None:
+                events[li][2].record()
+            tdq.tdq_w4a4_linear(L.Q, L.gid, L.scale, lc.B, lc.T, lc.C, L.Qw, L.w_scale, None,
+                                out=L.Y)
+            if events is not None:
+                events[li][3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = [[[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in layers]
+                  for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step(all_events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+
+    seg_ms = np.zeros((len(layers), 3))
+    for ev in all_events:
+        for li in range(len(layers)):
+            for s in range(3):
+                seg_ms[li, s] += ev[li][s].elapsed_time(ev[li][s + 1])
+    seg_ms /= args.steps
+
+    act_ms = seg_ms[:, 0].sum() + seg_ms[:, 1].sum()
+    gemm_ms = seg_ms[:, 2].sum()
+    compulsory = sum(L.bytes["compulsory"] for L in layers)
+    sweeps = sum(L.bytes["calibrate"] + L.bytes["quantize"] for L in layers)
+    act_gbs = compulsory / (act_ms * 1e-3) / 1e9
+    act_sweep_gbs = sweeps / (act_ms * 1e-3) / 1e9
+    gemm_tops = sum(L.gemm_ops for L in layers) / (gemm_ms * 1e-3) / 1e12
+
+    rooflines = []
+    for li, L in enumerate(layers):
+        nm = L.lc.name
+        for s, key in ((0, "calibrate"), (1, "quantize")):
+            a = L.bytes[key] / (seg_ms[li, s] * 1e-3) / 1e9
+            rooflines.append({"kernel": f"{key}:{nm}", "bound": "hbm", "achieved": round(a, 1),
+                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(a / PEAK_HBM_GBS, 4),
+                              "ms": round(float(seg_ms[li, s]), 4)})
+        ai = L.gemm_ops / L.gemm_bytes
+        t = L.gemm_ops / (seg_ms[li, 2] * 1e-3) / 1e12
+        rooflines.append({"kernel": f"w4a4_linear:{nm}", "bound": "mfma", "achieved": round(t, 1),
+                          "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(t / PEAK_INT8_TOPS, 4),
+                          "ms": round(float(seg_ms[li, 2]), 4), "ops_per_byte": round(ai, 1),
+                          "hbm_gbs": round(L.gemm_bytes / (seg_ms[li, 2] * 1e-3) / 1e9, 1)})
+
+    # the dominant kernel: the int8-MFMA contraction (one launch per linear; the two
+    # launches of a step do the same 2*M*N*K operations)
+    roofline = {"kernel": "k_w4a4_gemm", "bound": "mfma", "achieved": round(gemm_tops, 1),
+                "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": None,
+                "avg_launch_ms": round(float(gemm_ms / len(layers)), 4)}
+
+    out = {
+        "metric": "DSTG+DCRP act-quant GB/s + W4A4 linear TOPS (% of HBM / int8 MFMA peak)",
+        "value": round(act_gbs, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8 MFMA / int32 acc; fp32 statistics (fp64 merge)",
+        "data": "synthetic",
+        "config": {"workload": f"config 4 (ViT-L-shaped stress): B={fc1.lc.B} x T=4096, "
+                               f"fc1 1024->4096 (fp16 out) + fc2 4096->1024 (fp32 out), "
+                               f"G=32, heavy {args.heavy}%, fp16 activations",
+                   "value_definition": "bytes of X read once + packed codes written, "
+                                       "divided by the time of calibrate+quantize of both linears"},
+        "act_quant_gbs": round(act_gbs, 1),
+        "act_quant_frac_hbm": round(act_gbs / PEAK_HBM_GBS, 4),
+        "act_sweep_gbs": round(act_sweep_gbs, 1),
+        "act_sweep_frac_hbm": round(act_sweep_gbs / PEAK_HBM_GBS, 4),
+        "linear_tops": round(gemm_tops, 1),
+        "linear_frac_mfma": round(gemm_tops / PEAK_INT8_TOPS, 4),
+        "act_ms": round(float(act_ms), 4), "linear_ms": round(float(gemm_ms), 4),
+        "roofline": roofline,
+        "rooflines": rooflines,
+    }
+    if not args.no_quality:
+        out["quality"] = quality(fc1, torch, tdq)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(fc1, np)
+    print(json.dumps(out), flush=True)
+
+
+def quality(L, torch, tdq):
+    """SQNR and zero-bin mass of the synthetic fc1 input under token-group DCRP and
+    under naive per-image abs-max (one group, DCRP off), from the GPU's own codes."""
+    lc = L.lc
+
+    def measure(gid, scale, Q):
+        lo = (Q[:, :lc.C // 2] & 0xF).to(torch.int8)
+        hi = (Q[:, :lc.C // 2] >> 4).to(torch.int8)
+        lo = torch.where(lo > 7, lo - 16, lo)
+        hi = torch.where(hi > 7, hi - 16, hi)
+        q = torch.stack((lo, hi), dim=-1).reshape(lc.M, lc.C)
+        rs = scale.reshape(lc.B, -1).gather(1, gid.reshape(lc.B, -1).long()).reshape(lc.M, 1)
+        x = L.X.reshape(lc.M, lc.C).float()
+        err = x - q.float() * rs
+        weak = torch.from_numpy(L.cls.reshape(-1) == 2).to(x.device)
+        res = {}
+        for nm, m in (("all", slice(None)), ("weak_tokens", weak)):
+            sx = (x[m].double() ** 2).sum()
+            se = (err[m].double() ** 2).sum()
+            res["sqnr_db_" + nm] = round(float(10 * torch.log10(sx / se)), 2)
+            res["rho0_" + nm] = round(float((q[m] == 0).float().mean()), 4)
+        return res
+
+    out = {"tdq": measure(L.gid, L.scale, L.Q)}
+    p1 = tdq.default_params(1, flags=0)
+    gid1, clip1, scale1, _, _ = tdq.tdq_calibrate_groups(L.X, p1)
+    Q1 = tdq.tdq_quantize_act(L.X, p1, gid1, clip1, scale1)
+    out["per_image_absmax"] = measure(gid1, scale1, Q1)
+    torch.cuda.synchronize()
+    return out
+
+
+def cpu_baseline(L, np):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the
+    activation path (calibrate + quantize) of the first images of fc1's input and
+    the contraction of 64 rows.  Host cores of this machine; numpy uses one thread."""
+    from oracle import tdq_oracle as O
+    lc = L.lc
+    nimg = min(2, lc.B)
+    X = L.X_host[:nimg]
+    p = O.Params(n_groups=lc.G)
+    t0 = time.perf_counter()
+    gid, clip, scale, _ = O.calibrate_groups(X, p)
+    q = O.quantize_act(X, gid, clip, scale, p)
+    t_act = time.perf_counter() - t0
+    e = X.size
+    rows = 64
+    qw = np.random.Generator(np.random.PCG64(1)).integers(-7, 8, (lc.N, lc.C), dtype=np.int8)
+    t0 = time.perf_counter()
+    O.w4a4_linear(q.reshape(-1, lc.C)[:rows], np.ones(rows, np.float32), qw,
+                  np.ones(lc.N, np.float32))
+    t_mm = time.perf_counter() - t0
+    return {"value": round(e * 2.5 / t_act / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"activation path (calibrate+quantize) of {nimg} of {lc.B} images of the "
+                      f"fc1 input, {e} elements, {t_act:.2f} s; contraction of {rows} rows x "
+                      f"{lc.N} x {lc.C}: {t_mm:.2f} s",
+            "linear_tops": round(2 * rows * lc.N * lc.C / t_mm / 1e12, 6),
+            "host_cpus_visible": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()
