@@ -15,6 +15,8 @@ namespace tdq {
 // ---------------------------------------------------------------------------
 typedef unsigned short u16;
 typedef unsigned int u32;
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float h2f(u32 bits16) {
   return (float)__builtin_bit_cast(_Float16, (u16)bits16);
@@ -56,6 +58,50 @@ static int lanes_per_row(int C, int V) {
   return L;
 }
 
+// Reductions over groups of L adjacent lanes (L a power of two <= 64) with DPP
+// row shifts and row broadcasts, i.e. at vector-ALU speed instead of one LDS round
+// trip per step.  The result is valid in the LAST lane of every group
+// (lane % L == L - 1); the other lanes hold partial windows.
+//   steps 1, 2, 4, 8: row_shr inside rows of 16 lanes (zero shifted in),
+//   16: row_bcast15 into rows 1 and 3,  32: row_bcast31 into rows 2 and 3.
+#define TDQ_DPP_ROW_SHR(n) (0x110 + (n))
+#define TDQ_DPP_ROW_BCAST15 0x142
+#define TDQ_DPP_ROW_BCAST31 0x143
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ u32 dpp_u32(u32 v) {
+  return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+  const u32 lo = dpp_u32<CTRL, ROW_MASK>((u32)b), hi = dpp_u32<CTRL, ROW_MASK>((u32)(b >> 32));
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+template <int L>
+__device__ __forceinline__ double group_sum_f64(double v) {
+  if (L > 1) v += dpp_f64<TDQ_DPP_ROW_SHR(1), 0xF>(v);
+  if (L > 2) v += dpp_f64<TDQ_DPP_ROW_SHR(2), 0xF>(v);
+  if (L > 4) v += dpp_f64<TDQ_DPP_ROW_SHR(4), 0xF>(v);
+  if (L > 8) v += dpp_f64<TDQ_DPP_ROW_SHR(8), 0xF>(v);
+  if (L > 16) v += dpp_f64<TDQ_DPP_ROW_BCAST15, 0xA>(v);
+  if (L > 32) v += dpp_f64<TDQ_DPP_ROW_BCAST31, 0xC>(v);
+  return v;
+}
+template <int L>
+__device__ __forceinline__ u32 group_max_u32(u32 v) {
+  u32 o;
+  if (L > 1) { o = dpp_u32<TDQ_DPP_ROW_SHR(1), 0xF>(v); v = o > v ? o : v; }
+  if (L > 2) { o = dpp_u32<TDQ_DPP_ROW_SHR(2), 0xF>(v); v = o > v ? o : v; }
+  if (L > 4) { o = dpp_u32<TDQ_DPP_ROW_SHR(4), 0xF>(v); v = o > v ? o : v; }
+  if (L > 8) { o = dpp_u32<TDQ_DPP_ROW_SHR(8), 0xF>(v); v = o > v ? o : v; }
+  if (L > 16) { o = dpp_u32<TDQ_DPP_ROW_BCAST15, 0xA>(v); v = o > v ? o : v; }
+  if (L > 32) { o = dpp_u32<TDQ_DPP_ROW_BCAST31, 0xC>(v); v = o > v ? o : v; }
+  return v;
+}
+
+// xor-butterfly forms (every lane gets the result), used off the hot paths
 template <int L, typename F>
 __device__ __forceinline__ F xor_reduce_sum(F v) {
 #pragma unroll
@@ -93,24 +139,34 @@ __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, lo
   u32 kmax = 0;
   double a1 = 0.0, a2 = 0.0;
   const int nvec = vec_ok ? C / V : 0;
+  us2 kpk = {0, 0};                       // fp16: running max of the magnitude keys, two at a time
+  float one = 1.0f;                       // opaque to the optimizer, so x * one + p stays ONE mixed fma
+  asm volatile("" : "+v"(one));
 #pragma unroll 4
   for (int v = lr; v < nvec; v += L) {
     const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
-    T e[V];
-    Elem<T>::unpack(q, e);
     if constexpr (sizeof(T) == 2) {
+      // Per element one mixed-precision fma for the sum (x * 1 + p, the fp16 -> fp32
+      // conversion rides in the instruction) and one for the sum of squares (x * x is
+      // exact in binary32, so the fused form rounds exactly like multiply-then-add);
+      // the keys of a pair of elements are maxed with one packed 16-bit instruction.
+      const u32 w[4] = {q.x, q.y, q.z, q.w};
       float p1 = 0.f, p2 = 0.f;
 #pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const float f = Elem<T>::val(e[i]);
-        const u32 k = Elem<T>::key(e[i]);
-        kmax = k > kmax ? k : kmax;
-        p1 += f;
-        p2 += f * f;
+      for (int j = 0; j < 4; ++j) {
+        const h2 h = __builtin_bit_cast(h2, w[j]);
+        kpk = __builtin_elementwise_max(kpk, __builtin_bit_cast(us2, w[j] & 0x7FFF7FFFu));
+        const float f0 = (float)h[0], f1 = (float)h[1];
+        p1 = __builtin_fmaf(f0, one, p1);
+        p2 = __builtin_fmaf(f0, f0, p2);
+        p1 = __builtin_fmaf(f1, one, p1);
+        p2 = __builtin_fmaf(f1, f1, p2);
       }
       a1 += (double)p1;
       a2 += (double)p2;
     } else {
+      T e[V];
+      Elem<T>::unpack(q, e);
 #pragma unroll
       for (int i = 0; i < V; ++i) {
         const double f = (double)Elem<T>::val(e[i]);
@@ -129,13 +185,100 @@ __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, lo
     a1 += f;
     a2 += f * f;
   }
-  kmax = xor_reduce_max<L>(kmax);
-  a1 = xor_reduce_sum<L>(a1);
-  a2 = xor_reduce_sum<L>(a2);
-  if (lr == 0 && valid) {
+  if constexpr (sizeof(T) == 2) {
+    const u32 kp = kpk[0] > kpk[1] ? kpk[0] : kpk[1];
+    kmax = kp > kmax ? kp : kmax;
+  }
+  kmax = group_max_u32<L>(kmax);
+  a1 = group_sum_f64<L>(a1);
+  a2 = group_sum_f64<L>(a2);
+  if (lr == L - 1 && valid) {
     r[row] = Elem<T>::key_to_float(kmax);
     s1[row] = a1;
     s2[row] = a2;
+  }
+}
+
+// Wide rows (at least 256 16-byte pieces): one workgroup of four wavefronts per row,
+// so every lane issues only a few loads and the chip runs many short wavefronts
+// (measured faster for streaming reads than few long ones).  The four wavefront
+// totals are combined through LDS in a fixed order.
+template <typename T>
+__global__ __launch_bounds__(256) void k_token_stats_wide(const T* __restrict__ X, long long ld, int M,
+                                                          int C, float* __restrict__ r,
+                                                          double* __restrict__ s1,
+                                                          double* __restrict__ s2) {
+  constexpr int V = Elem<T>::V;
+  __shared__ double sh1[4], sh2[4];
+  __shared__ u32 shk[4];
+  const long long row = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const T* xp = X + row * ld;
+  u32 kmax = 0;
+  double a1 = 0.0, a2 = 0.0;
+  const int nvec = C / V;
+  us2 kpk = {0, 0};
+  float one = 1.0f;
+  asm volatile("" : "+v"(one));
+#pragma unroll 4
+  for (int v = tid; v < nvec; v += 256) {
+    const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
+    if constexpr (sizeof(T) == 2) {
+      const u32 w[4] = {q.x, q.y, q.z, q.w};
+      float p1 = 0.f, p2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const h2 h = __builtin_bit_cast(h2, w[j]);
+        kpk = __builtin_elementwise_max(kpk, __builtin_bit_cast(us2, w[j] & 0x7FFF7FFFu));
+        const float f0 = (float)h[0], f1 = (float)h[1];
+        p1 = __builtin_fmaf(f0, one, p1);
+        p2 = __builtin_fmaf(f0, f0, p2);
+        p1 = __builtin_fmaf(f1, one, p1);
+        p2 = __builtin_fmaf(f1, f1, p2);
+      }
+      a1 += (double)p1;
+      a2 += (double)p2;
+    } else {
+      T e[V];
+      Elem<T>::unpack(q, e);
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const double f = (double)Elem<T>::val(e[i]);
+        const u32 k = Elem<T>::key(e[i]);
+        kmax = k > kmax ? k : kmax;
+        a1 += f;
+        a2 += f * f;
+      }
+    }
+  }
+  for (int c = nvec * V + tid; c < C; c += 256) {
+    const T x = xp[c];
+    const double f = (double)Elem<T>::val(x);
+    const u32 k = Elem<T>::key(x);
+    kmax = k > kmax ? k : kmax;
+    a1 += f;
+    a2 += f * f;
+  }
+  if constexpr (sizeof(T) == 2) {
+    const u32 kp = kpk[0] > kpk[1] ? kpk[0] : kpk[1];
+    kmax = kp > kmax ? kp : kmax;
+  }
+  kmax = group_max_u32<64>(kmax);
+  a1 = group_sum_f64<64>(a1);
+  a2 = group_sum_f64<64>(a2);
+  if (lane == 63) { shk[wave] = kmax; sh1[wave] = a1; sh2[wave] = a2; }
+  __syncthreads();
+  if (tid == 0) {
+    u32 k = shk[0];
+    double t1 = sh1[0], t2 = sh2[0];
+    for (int w = 1; w < 4; ++w) {
+      k = shk[w] > k ? shk[w] : k;
+      t1 += sh1[w];
+      t2 += sh2[w];
+    }
+    r[row] = Elem<T>::key_to_float(k);
+    s1[row] = t1;
+    s2[row] = t2;
   }
 }
 
@@ -144,6 +287,10 @@ static hipError_t token_stats_t(const T* X, int M, int C, long long ld, float* r
                                 double* s2, hipStream_t st) {
   constexpr int V = Elem<T>::V;
   const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % V == 0) ? 1 : 0;
+  if (vec_ok && C / V >= 256) {
+    hipLaunchKernelGGL((k_token_stats_wide<T>), dim3(M), dim3(256), 0, st, X, ld, M, C, r, s1, s2);
+    return hipGetLastError();
+  }
   const int L = lanes_per_row(C, V);
   const long long threads = (long long)M * L;
   const unsigned grid = (unsigned)((threads + 255) / 256);
@@ -187,20 +334,35 @@ __device__ __forceinline__ u32 wave_min_u32(u32 v) {
   return v;
 }
 
+// Per-wavefront, per-token-set partial sums of the merge (kept in LDS).
+struct SetAcc {
+  double s1, s2;
+  u32 cnt, kmax;
+};
+
 __global__ __launch_bounds__(kAssignThreads) void k_assign(
     const float* __restrict__ r, const double* __restrict__ s1, const double* __restrict__ s2,
     int T, int C, int G, Scalars sc, int* __restrict__ gid, GroupWork* __restrict__ grp,
     u32* __restrict__ hist, LevelPlan lp, long long groups_total, u32* __restrict__ img_flag) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char assign_lds[];
   __shared__ u32 s_min[kAssignThreads / 64], s_max[kAssignThreads / 64];
   __shared__ u32 s_lo, s_hi;
+  SetAcc* wacc = reinterpret_cast<SetAcc*>(assign_lds);     // [NW][G]
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int NW = kAssignThreads / 64;
+  const int NW = blockDim.x >> 6;
   const float* rb = r + (long long)b * T;
+  const double* s1b = s1 + (long long)b * T;
+  const double* s2b = s2 + (long long)b * T;
   int* gb = gid + (long long)b * T;
 
+  for (int i = tid; i < NW * G; i += blockDim.x) {
+    SetAcc z;
+    z.s1 = 0.0; z.s2 = 0.0; z.cnt = 0; z.kmax = 0;
+    wacc[i] = z;
+  }
   u32 kmin = 0xFFFFFFFFu, kmax = 0;
-  for (int t = tid; t < T; t += kAssignThreads) {
+  for (int t = tid; t < T; t += blockDim.x) {
     const u32 k = __float_as_uint(rb[t]);
     kmin = k < kmin ? k : kmin;
     kmax = k > kmax ? k : kmax;
@@ -224,60 +386,110 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
   __syncthreads();
   const u32 lo = s_lo, hi = s_hi;
   const unsigned long long width = (unsigned long long)(hi - lo) + 1ull;
-  for (int t = tid; t < T; t += kAssignThreads) {
-    const u32 k = __float_as_uint(rb[t]);
-    int g = 0;
-    if (G > 1 && hi != lo && k > lo)
-      g = (int)(((unsigned long long)(k - lo) * (unsigned long long)G) / width);
-    gb[t] = g;
-  }
-  __syncthreads();   // gid of this image visible to the whole workgroup (global, same block)
 
-  // one wavefront per token set, fixed lane-strided order + xor tree: deterministic
-  for (int g = wave; g < G; g += NW) {
+  // Wavefront w owns the token batches w, w + NW, ... (64 tokens each).  Inside a
+  // batch the tokens of one set are summed with a fixed xor tree and added to the
+  // wavefront's accumulator of that set, sets in order of first appearance: every
+  // floating-point sum has a fixed order, so the result is bitwise repeatable.
+  SetAcc* mine = wacc + wave * G;
+  const int n_batches = (T + 63) / 64;
+  // the loads of the next batch are issued before the current one is reduced
+  u32 nk = 0;
+  double n1 = 0.0, n2 = 0.0;
+  if (wave < n_batches && wave * 64 + lane < T) {
+    const int t = wave * 64 + lane;
+    nk = __float_as_uint(rb[t]);
+    n1 = s1b[t];
+    n2 = s2b[t];
+  }
+  for (int bt = wave; bt < n_batches; bt += NW) {
+    const int t = bt * 64 + lane;
+    const bool live = t < T;
+    const u32 k = nk;
+    const double v1 = n1, v2 = n2;
+    {
+      const int tn = t + NW * 64;
+      if (bt + NW < n_batches && tn < T) {
+        nk = __float_as_uint(rb[tn]);
+        n1 = s1b[tn];
+        n2 = s2b[tn];
+      }
+    }
+    int g = -1;
+    if (live) {
+      g = 0;
+#if defined(TDQ_EXP) && (TDQ_EXP & 64)
+      if (G > 1 && hi != lo && k > lo) g = (int)((k - lo) >> 27) % G;
+#else
+      if (G > 1 && hi != lo && k > lo)
+        g = (int)(((unsigned long long)(k - lo) * (unsigned long long)G) / width);
+#endif
+      gb[t] = g;
+    }
+    unsigned long long todo = __ballot(live);
+#if defined(TDQ_EXP) && (TDQ_EXP & 16)
+    todo = 0;
+#endif
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int gg = __builtin_amdgcn_readlane(g, leader);
+      const bool sel = g == gg;
+      const unsigned long long m = __ballot(sel);
+      const double a1 = group_sum_f64<64>(sel ? v1 : 0.0);     // totals land in lane 63
+      const double a2 = group_sum_f64<64>(sel ? v2 : 0.0);
+      const u32 km = group_max_u32<64>(sel ? k : 0u);
+      if (lane == 63) {
+        SetAcc a = mine[gg];
+        a.s1 += a1;
+        a.s2 += a2;
+        a.cnt += (u32)__popcll(m);
+        a.kmax = km > a.kmax ? km : a.kmax;
+        mine[gg] = a;
+      }
+      todo &= ~m;
+    }
+  }
+  __syncthreads();
+
+  for (int g = tid; g < G; g += blockDim.x) {      // merge the wavefronts in a fixed order
     u32 cnt = 0, cmax = 0;
     double S1 = 0.0, S2 = 0.0;
-    for (int t = lane; t < T; t += 64) {
-      if (gb[t] == g) {
-        const u32 k = __float_as_uint(rb[t]);
-        cnt += 1;
-        cmax = k > cmax ? k : cmax;
-        S1 += s1[(long long)b * T + t];
-        S2 += s2[(long long)b * T + t];
-      }
+    for (int w = 0; w < NW; ++w) {
+      const SetAcc a = wacc[w * G + g];
+      cnt += a.cnt;
+      cmax = a.kmax > cmax ? a.kmax : cmax;
+      S1 += a.s1;
+      S2 += a.s2;
     }
-    cnt = (u32)xor_reduce_sum<64>((int)cnt);
-    cmax = wave_max_u32(cmax);
-    S1 = xor_reduce_sum<64>(S1);
-    S2 = xor_reduce_sum<64>(S2);
-    if (lane == 0) {
-      GroupWork w;
-      w.tokens = cnt;
-      w.n = (long long)cnt * (long long)C;
-      w.prefix = 0;
-      w.c_base = __uint_as_float(cmax);
-      if (cnt == 0) {
-        w.k_rem = 0;
-        w.sigma = 0.f;
-      } else {
-        const double n = (double)w.n;
-        const double mu = S1 / n;
-        double var = S2 / n - mu * mu;
-        var = var > 0.0 ? var : 0.0;
-        w.sigma = (float)(sqrt(var) + sc.eps_std);
-        long long k = (long long)ceil(sc.zr * n);   // binary64 product, then ceil
-        k = k < 1 ? 1 : (k > w.n ? w.n : k);
-        w.k_rem = k;
-      }
-      grp[(long long)b * G + g] = w;
+    GroupWork w;
+    w.tokens = cnt;
+    w.n = (long long)cnt * (long long)C;
+    w.prefix = 0;
+    w.c_base = __uint_as_float(cmax);
+    if (cnt == 0) {
+      w.k_rem = 0;
+      w.sigma = 0.f;
+    } else {
+      const double n = (double)w.n;
+      const double mu = S1 / n;
+      double var = S2 / n - mu * mu;
+      var = var > 0.0 ? var : 0.0;
+      w.sigma = (float)(sqrt(var) + sc.eps_std);
+      long long k = (long long)ceil(sc.zr * n);   // binary64 product, then ceil
+      k = k < 1 ? 1 : (k > w.n ? w.n : k);
+      w.k_rem = k;
     }
+    grp[(long long)b * G + g] = w;
   }
   // clear this image's slice of every level's histogram
   size_t off = 0;
+#if defined(TDQ_EXP) && (TDQ_EXP & 32)
+  if (T < 0)
+#endif
   for (int l = 0; l < lp.n_levels; ++l) {
     const size_t nb = (size_t)1 << lp.bits[l];
     u32* h = hist + off + (size_t)b * G * nb;
-    for (size_t i = tid; i < (size_t)G * nb; i += kAssignThreads) h[i] = 0;
+    for (size_t i = tid; i < (size_t)G * nb; i += blockDim.x) h[i] = 0;
     off += (size_t)groups_total * nb;
   }
 }
@@ -285,8 +497,11 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
 hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int C,
                          int G, const Scalars& sc, int* gid, GroupWork* grp, unsigned* hist,
                          unsigned* img_flag, const LevelPlan& lp, hipStream_t st) {
-  hipLaunchKernelGGL(k_assign, dim3(B), dim3(kAssignThreads), 0, st, r, s1, s2, T, C, G, sc, gid,
-                     grp, hist, lp, (long long)B * G, img_flag);
+  int nw = 2048 / G;                       // keep the per-wavefront accumulators under 48 KiB
+  nw = nw > kAssignThreads / 64 ? kAssignThreads / 64 : (nw < 1 ? 1 : nw);
+  const size_t lds = (size_t)nw * G * sizeof(SetAcc);
+  hipLaunchKernelGGL(k_assign, dim3(B), dim3(nw * 64), lds, st, r, s1, s2, T, C, G, sc, gid, grp,
+                     hist, lp, (long long)B * G, img_flag);
   return hipGetLastError();
 }
 
@@ -298,7 +513,7 @@ hipError_t launch_assign(const float* r, const double* s1, const double* s2, int
 // ---------------------------------------------------------------------------
 constexpr int kHistThreads = 1024;
 
-template <typename T, int L>
+template <typename T, int L, bool FIRST>
 __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, long long ld, int T_,
                                                        int C, int G, int vec_ok,
                                                        const int* __restrict__ gid,
@@ -307,13 +522,16 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
                                                        int rows_per_block) {
   extern __shared__ u32 lds[];
   constexpr int V = Elem<T>::V;
-  const int b = blockIdx.y;
+  // The top level walks X backwards: it runs right after the forward statistics sweep,
+  // so the end of X is what the last-level cache still holds.
+  const int b = FIRST ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+  const int chunk = FIRST ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
   const int tid = threadIdx.x;
   const int nwords = G << bits;
   for (int i = tid; i < nwords; i += kHistThreads) lds[i] = 0;
   __syncthreads();
 
-  const int row0 = blockIdx.x * rows_per_block;
+  const int row0 = chunk * rows_per_block;
   int nrows = T_ - row0;
   nrows = nrows < rows_per_block ? nrows : rows_per_block;
   const u32 mask = (1u << bits) - 1u;
@@ -324,23 +542,34 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
   for (int rr = slot; rr < nrows; rr += SLOTS) {
     const long long row = (long long)b * T_ + row0 + rr;
     const int g = gid[row];
-    const u32 prefix = grp[(long long)b * G + g].prefix;
+    const u32 prefix = FIRST ? 0u : grp[(long long)b * G + g].prefix;
     u32* h = lds + (g << bits);
     const T* xp = X + row * ld;
 #pragma unroll 2
     for (int v = lr; v < nvec; v += L) {
       const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
-      T e[V];
-      Elem<T>::unpack(q, e);
+      if constexpr (FIRST && sizeof(T) == 2) {
+        // top level of fp16: the digit is a bit field of the packed word (the sign
+        // bit lies above it), one extract and one address add per element
+        const u32 w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const u32 k = Elem<T>::key(e[i]);
-        if ((hs >= 32 ? 0u : (k >> hs)) == prefix) atomicAdd(&h[(k >> shift) & mask], 1u);
+        for (int j = 0; j < 4; ++j) {
+          atomicAdd(&h[__builtin_amdgcn_ubfe(w[j], (u32)shift, (u32)bits)], 1u);
+          atomicAdd(&h[__builtin_amdgcn_ubfe(w[j], (u32)(16 + shift), (u32)bits)], 1u);
+        }
+      } else {
+        T e[V];
+        Elem<T>::unpack(q, e);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const u32 k = Elem<T>::key(e[i]);
+          if (FIRST || (hs >= 32 ? 0u : (k >> hs)) == prefix) atomicAdd(&h[(k >> shift) & mask], 1u);
+        }
       }
     }
     for (int c = nvec * V + lr; c < C; c += L) {
       const u32 k = Elem<T>::key(xp[c]);
-      if ((hs >= 32 ? 0u : (k >> hs)) == prefix) atomicAdd(&h[(k >> shift) & mask], 1u);
+      if (FIRST || (hs >= 32 ? 0u : (k >> hs)) == prefix) atomicAdd(&h[(k >> shift) & mask], 1u);
     }
   }
   __syncthreads();
@@ -367,10 +596,19 @@ static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, 
   if (rpb > T_) rpb = T_;
   const unsigned chunks = (unsigned)((T_ + rpb - 1) / rpb);
   const size_t lds_bytes = (size_t)(G << bits) * sizeof(u32);
+  const bool first = shift + bits >= (int)(sizeof(T) == 2 ? 15 : 31);   // the top level: no prefix yet
 #define TDQ_HIST(LL)                                                                              \
   case LL:                                                                                     \
-    hipLaunchKernelGGL((k_hist<T, LL>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, st, X, \
-                       ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);           \
+    if (first) {                                                                               \
+      if (lds_bytes > 65536)                                                                   \
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<T, LL, true>),         \
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
+      hipLaunchKernelGGL((k_hist<T, LL, true>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, \
+                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);  \
+    } else {                                                                                   \
+      hipLaunchKernelGGL((k_hist<T, LL, false>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, \
+                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);  \
+    }                                                                                          \
     break;
   switch (L) {
     TDQ_HIST(1) TDQ_HIST(2) TDQ_HIST(4) TDQ_HIST(8) TDQ_HIST(16) TDQ_HIST(32) TDQ_HIST(64)
@@ -514,6 +752,41 @@ __device__ __forceinline__ u32 quant_nibble(float x, float c, float d, float rcp
   return __float_as_uint(m) & 0xFu;
 }
 
+// Rounded quotient of one element as a float bit pattern whose low 4 bits are the
+// two's-complement code (see above).  CLAMP adds the clamp to [-8, 7], needed only
+// when the radii are not a projection's (c > 7.25 * Delta).
+template <bool CLAMP>
+__device__ __forceinline__ u32 quant_bits(float x, float c, float d, float rcp) {
+  const float xt = __builtin_amdgcn_fmed3f(x, -c, c);
+  const float y0 = xt * rcp;
+  const float e = __builtin_fmaf(-y0, d, xt);
+  float y = __builtin_fmaf(e, rcp, y0);
+  if (CLAMP) y = __builtin_amdgcn_fmed3f(y, (float)kQMin, (float)kQMax);
+  return __float_as_uint(y + 12582912.0f);
+}
+
+// Eight fp16 elements (one 16-byte load) -> eight packed codes.  The low bytes of
+// the eight results are gathered with byte permutes into a word of the even and a
+// word of the odd elements, which are then merged nibble-wise.
+template <bool CLAMP>
+__device__ __forceinline__ u32 quant8_f16(const uint4& q, float c, float d, float rcp) {
+  const u32 w[4] = {q.x, q.y, q.z, q.w};
+  u32 m[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const h2 h = __builtin_bit_cast(h2, w[j]);
+    m[2 * j] = quant_bits<CLAMP>((float)h[0], c, d, rcp);
+    m[2 * j + 1] = quant_bits<CLAMP>((float)h[1], c, d, rcp);
+  }
+  // v_perm_b32(s0, s1, sel): selector bytes 0-3 pick bytes of s1, 4-7 bytes of s0, 0x0c is zero
+  const u32 e02 = __builtin_amdgcn_perm(m[2], m[0], 0x0c0c0400u);   // [m0.b0, m2.b0, 0, 0]
+  const u32 e46 = __builtin_amdgcn_perm(m[6], m[4], 0x04000c0cu);   // [0, 0, m4.b0, m6.b0]
+  const u32 o13 = __builtin_amdgcn_perm(m[3], m[1], 0x0c0c0400u);
+  const u32 o57 = __builtin_amdgcn_perm(m[7], m[5], 0x04000c0cu);
+  const u32 ev = e02 | e46, od = (o13 | o57) << 4;
+  return (ev & 0x0F0F0F0Fu) | (od & 0xF0F0F0F0u);
+}
+
 template <typename T, int L>
 __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ X, long long ld, int M, int C,
                                                   int T_, int G, int vec_ok,
@@ -523,7 +796,9 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ X, long 
                                                   uint8_t* __restrict__ Q, long long ld_q) {
   constexpr int V = Elem<T>::V;
   constexpr int U = 8 / V;                 // 16-byte loads per 8 elements
-  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;
+  // rows are walked from the end of X: the sweep before this one (the last histogram
+  // level) ran forwards
+  const long long gt = (long long)(gridDim.x - 1 - blockIdx.x) * 256 + threadIdx.x;
   const long long row = gt / L;
   const int lr = (int)(gt % L);
   if (row >= M) return;
@@ -535,6 +810,22 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ X, long 
   const T* xp = X + row * ld;
   uint8_t* qp = Q + row * ld_q;
   const int n8 = vec_ok ? C / 8 : 0;       // units of 8 elements -> one 32-bit store
+  if constexpr (sizeof(T) == 2) {
+    const bool need_clamp = !(c <= 7.25f * d);
+    if (__builtin_amdgcn_ballot_w64(need_clamp) == 0) {
+#pragma unroll 4
+      for (int u = lr; u < n8; u += L) {
+        const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)u * 8);
+        *reinterpret_cast<u32*>(qp + (long long)u * 4) = quant8_f16<false>(q, c, d, rcp);
+      }
+    } else {
+#pragma unroll 2
+      for (int u = lr; u < n8; u += L) {
+        const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)u * 8);
+        *reinterpret_cast<u32*>(qp + (long long)u * 4) = quant8_f16<true>(q, c, d, rcp);
+      }
+    }
+  } else
 #pragma unroll 2
   for (int u = lr; u < n8; u += L) {
     u32 word = 0;

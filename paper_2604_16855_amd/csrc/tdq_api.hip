@@ -1,6 +1,7 @@
 // C ABI of libtdq: argument validation on the host, workspace layout, and the
 // launch sequence of each entry point.  Nothing here computes on the data.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "tdq_internal.hpp"
@@ -16,8 +17,17 @@ LevelPlan make_level_plan(tdq_dtype dt, int G) {
   int max_bits = 0;
   while ((G << (max_bits + 1)) <= kHistLdsWords && max_bits + 1 <= kMaxLevelBits) ++max_bits;
   if (max_bits < 1) max_bits = 1;
-  const int n = (lp.key_bits + max_bits - 1) / max_bits;
+  int n = (lp.key_bits + max_bits - 1) / max_bits;
   lp.n_levels = n;
+  if (const char* e = getenv("TDQ_HIST_BITS0")) {     // experiment: force the first level's width
+    const int b0 = atoi(e);
+    if (dt == TDQ_F16 && b0 >= 6 && b0 <= 11 && (G << b0) <= 32768 && 15 - b0 <= max_bits) {
+      lp.n_levels = 2;
+      lp.bits[0] = b0; lp.shift[0] = 15 - b0;
+      lp.bits[1] = 15 - b0; lp.shift[1] = 0;
+      return lp;
+    }
+  }
   int left = lp.key_bits;
   for (int l = 0; l < n; ++l) {
     const int levels_left = n - l;
