@@ -29,12 +29,15 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--heavy", type=int, default=10, choices=(2, 10, 25),
                     help="heavy-tailed token fraction of config 4, percent")
     ap.add_argument("--small", action="store_true",
                     help="4 images instead of 32 (quick functional run, not the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain device copy of 1 GiB (a kernel of known traffic, "
+                         "used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-quality", action="store_true")
     return ap.parse_args()
 
@@ -113,6 +116,14 @@ def main():
             if events is not None:
                 events[li][3].record()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -14,6 +14,8 @@
 // as both operands use the same one, which they do by construction.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "tdq_internal.hpp"
 
 namespace tdq {
@@ -28,12 +30,14 @@ constexpr int GEMM_THREADS = 256;      // 4 wavefronts, 2 x 2
 constexpr int XCDS = 8;
 
 // Two packed words (16 codes) -> the four operand registers of one matrix instruction.
-__device__ __forceinline__ v4i expand(u32 w0, u32 w1) {
+// `hi` is 0xF0F0F0F0; the pipelined kernel passes it in a scalar register so that the
+// four ANDs are 4-byte instructions instead of 8-byte ones carrying a literal.
+__device__ __forceinline__ v4i expand(u32 w0, u32 w1, u32 hi = 0xF0F0F0F0u) {
   v4i r;
-  r[0] = (int)((w0 << 4) & 0xF0F0F0F0u);   // even codes of w0, times 16
-  r[1] = (int)(w0 & 0xF0F0F0F0u);          // odd codes of w0, times 16
-  r[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
-  r[3] = (int)(w1 & 0xF0F0F0F0u);
+  r[0] = (int)((w0 << 4) & hi);   // even codes of w0, times 16
+  r[1] = (int)(w0 & hi);          // odd codes of w0, times 16
+  r[2] = (int)((w1 << 4) & hi);
+  r[3] = (int)(w1 & hi);
   return r;
 }
 
@@ -50,10 +54,17 @@ __device__ __forceinline__ void mask_piece(uint4& q, int keep) {
 
 template <typename OUT>
 __device__ __forceinline__ void store_out(OUT* p, float v);
+// Y is written once and not read again by this kernel: non-temporal stores keep the
+// output stream from evicting the packed operands (above all the weights, which every
+// tile re-reads) out of the L2.
 template <>
-__device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_out<float>(float* p, float v) {
+  __builtin_nontemporal_store(v, p);
+}
 template <>
-__device__ __forceinline__ void store_out<_Float16>(_Float16* p, float v) { *p = (_Float16)v; }
+__device__ __forceinline__ void store_out<_Float16>(_Float16* p, float v) {
+  __builtin_nontemporal_store((_Float16)v, p);
+}
 
 // Wavefront tile = (32 MT) x (32 NT) of Y, workgroup = 2 x 2 wavefronts.
 //   MT = NT = 4: 256 x 256 per workgroup, 256 accumulator registers per lane, one
@@ -234,274 +245,34 @@ __global__ __launch_bounds__(GEMM_THREADS, (MT * NT >= 16 ? 1 : MT * NT >= 8 ? 2
 }
 
 // ---------------------------------------------------------------------------
-// 256 x 256 tile, software pipelined (K a multiple of 128 codes).
-// One wavefront per SIMD owns 128 x 128 of Y in 256 accumulator registers, so
-// nothing but its own instruction stream hides latency.  The stream is laid out
-// by hand in bundles of two matrix instructions, the six expand operations of ONE
-// operand fragment of the NEXT operand set (3 vector ops per matrix op, which the
-// vector unit absorbs while the matrix unit is busy) and at most one LDS access.
-// Global loads run two stages ahead in two register sets.  Per stage of 128
-// codes (64 matrix instructions, 4 half-slabs of 8 bundles):
+// Software-pipelined kernel for large shapes (K a multiple of 128 codes).
+//
+// A wavefront owns (32 MT) x (32 NT) of Y; a workgroup is 2 x 2 wavefronts.
+//   MT = NT = 4: 256 x 256 tile, 256 accumulator registers, one wavefront per SIMD:
+//                nothing but the wavefront's own instruction stream hides latency.
+//   MT = 4, NT = 2: 256 x 128 tile, two workgroups per CU, so the prologue and the
+//                epilogue of one workgroup overlap the main loop of the other.
+// The stream is laid out by hand in bundles of one or two matrix instructions, the
+// six expand operations of ONE operand fragment of the NEXT operand set (3 vector
+// ops per matrix op at MT = NT = 4, which the vector unit absorbs while the matrix
+// unit is busy) and at most one LDS read or one global load.  Per stage of 128
+// codes (4 half-slabs of MT + NT bundles):
 //   X0: set 0 of slab 0 | expand set 1 of slab 0 | LDS reads of slab 1
-//   Y0: set 1 of slab 0 | expand set 0 of slab 1 | LDS writes of stage + 1
-//   barrier
+//   Y0: set 1 of slab 0 | expand set 0 of slab 1 | direct-to-LDS loads of stage + 2
+//   wait for stage + 1, barrier
 //   X1: set 0 of slab 1 | expand set 1 of slab 1 | LDS reads of slab 0 of stage + 1
 //   Y1: set 1 of slab 1 | expand set 0 of that slab
+//
 // The activations are the row operand of the matrix instruction, so the 32 lanes of
 // a half-wavefront hold 32 consecutive columns of one row of Y and every store
 // instruction writes whole 128-byte (fp32) / 64-byte (fp16) row segments.  (With
 // the operands swapped a lane would own 4 consecutive columns and could store 16
 // bytes at once, but into 64 different rows per instruction: measured 40 % slower.)
-// ---------------------------------------------------------------------------
-struct Frags {
-  uint4 a[4], b[4];     // packed 16-byte pieces: .x .y feed operand set 0, .z .w set 1
-};
-struct Operands {
-  v4i a[4], b[4];
-};
-
-template <int SET>
-__device__ __forceinline__ void expand_one(Operands& dst, const Frags& f, int e) {
-  // e is a compile-time constant after unrolling
-  if (e < 4) {
-    dst.a[e] = SET == 0 ? expand(f.a[e].x, f.a[e].y) : expand(f.a[e].z, f.a[e].w);
-  } else {
-    dst.b[e - 4] = SET == 0 ? expand(f.b[e - 4].x, f.b[e - 4].y) : expand(f.b[e - 4].z, f.b[e - 4].w);
-  }
-}
-
-// 16 matrix instructions on `cur`, interleaved with the 8 fragment expansions of
-// operand set EXP_SET taken from `f` into `nxt` and with lds(b), one LDS access per
-// bundle b = 0..7.
-template <int EXP_SET, typename LDS>
-__device__ __forceinline__ void half_slab(v16i (&acc)[4][4], const Operands& cur, Operands& nxt,
-                                          const Frags& f, LDS lds) {
-#pragma unroll
-  for (int b = 0; b < 8; ++b) {
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int m = 2 * b + q, i = m >> 2, j = m & 3;
-      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
-    }
-#if !defined(TDQ_EXP) || !(TDQ_EXP & 1)
-    expand_one<EXP_SET>(nxt, f, b);
-#endif
-#if !defined(TDQ_EXP) || !(TDQ_EXP & 2)
-    lds(b);
-#endif
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
-struct Staging {       // one stage of global loads of a thread: 4 pieces of A, 4 of B
-  uint4 a0, a1, a2, a3, b0, b1, b2, b3;
-};
-
-template <typename OUT>
-__global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_big(
-    const uint8_t* __restrict__ Qx, long long ld_q, const int* __restrict__ gid,
-    const float* __restrict__ scale, int M, int T, int K, int N, int G,
-    const uint8_t* __restrict__ Qw, long long ld_w, const float* __restrict__ w_scale,
-    const float* __restrict__ bias, OUT* __restrict__ Y, long long ld_y, int* __restrict__ acc_dump,
-    int m_tiles, int n_tiles) {
-  constexpr int BM = 256, BN = 256;
-  __shared__ __attribute__((aligned(16))) uint8_t sA[2][BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) uint8_t sB[2][BN * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) float sRow[BM], sCol[BN], sBias[BN];
-
-  const int bid = blockIdx.x;
-  const int xcd = bid % XCDS, idx = bid / XCDS;
-  const int m_tile = (idx / n_tiles) * XCDS + xcd;
-  const int n_tile = idx % n_tiles;
-  if (m_tile >= m_tiles) return;
-  const int m0 = m_tile * BM, n0 = n_tile * BN;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  const int k_tiles = ((K + 1) / 2) / BKB;          // host guarantees K % 128 == 0
-  const int frow = lane & 31, fhalf = (lane >> 5) * 16;
-
-  // Scales of the epilogue, one row and one column per thread (BM == BN == threads).
-  // The token-set id is fetched first; the scale that depends on it is fetched
-  // after the first stage's loads have been issued, so the two latencies overlap.
-  const int my_m = m0 + tid < M ? m0 + tid : M - 1;
-  const int my_g = gid ? gid[my_m] : 0;
-  const int ncol = n0 + tid;
-  const float my_ws = ncol < N ? w_scale[ncol] : 0.f;
-  const float my_bs = (bias && ncol < N) ? bias[ncol] : 0.f;
-
-  const int pr0 = tid >> 2, pc = (tid & 3) * 16;
-  const uint8_t* pa[4];
-  const uint8_t* pb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int r = m0 + pr0 + 64 * i;
-    r = r < M ? r : M - 1;
-    pa[i] = Qx + (long long)r * ld_q + pc;
-    int c = n0 + pr0 + 64 * i;
-    c = c < N ? c : N - 1;
-    pb[i] = Qw + (long long)c * ld_w + pc;
-  }
-  // Two register sets of staged global loads (kept in VGPRs from the load to the
-  // LDS write one stage later).
-  Staging g0, g1;
-#define TDQ_PIN(q) asm volatile("" : "+v"(q.x), "+v"(q.y), "+v"(q.z), "+v"(q.w))
-#define TDQ_LOAD_STAGE(G, kt)                                                           \
-  do {                                                                                  \
-    const int kc = (kt) < k_tiles ? (kt) : k_tiles - 1; /* past the end: harmless */    \
-    const long long ko = (long long)kc * BKB;                                           \
-    G.a0 = *reinterpret_cast<const uint4*>(pa[0] + ko);                                 \
-    G.a1 = *reinterpret_cast<const uint4*>(pa[1] + ko);                                 \
-    G.a2 = *reinterpret_cast<const uint4*>(pa[2] + ko);                                 \
-    G.a3 = *reinterpret_cast<const uint4*>(pa[3] + ko);                                 \
-    G.b0 = *reinterpret_cast<const uint4*>(pb[0] + ko);                                 \
-    G.b1 = *reinterpret_cast<const uint4*>(pb[1] + ko);                                 \
-    G.b2 = *reinterpret_cast<const uint4*>(pb[2] + ko);                                 \
-    G.b3 = *reinterpret_cast<const uint4*>(pb[3] + ko);                                 \
-  } while (0)
-  uint8_t* const st_a = &sA[0][pr0 * LDS_STRIDE + pc];
-  uint8_t* const st_b = &sB[0][pr0 * LDS_STRIDE + pc];
-  auto store_piece = [&](Staging& G, int buf, int e) {   // e = 0..7 compile-time
-    uint8_t* d = (e < 4 ? st_a + buf * (BM * LDS_STRIDE) : st_b + buf * (BN * LDS_STRIDE)) +
-                 (e & 3) * 64 * LDS_STRIDE;
-    uint4& q = e == 0 ? G.a0 : e == 1 ? G.a1 : e == 2 ? G.a2 : e == 3 ? G.a3
-             : e == 4 ? G.b0 : e == 5 ? G.b1 : e == 6 ? G.b2 : G.b3;
-    TDQ_PIN(q);
-    *reinterpret_cast<uint4*>(d) = q;
-  };
-  const int a_off = (wm * 128 + frow) * LDS_STRIDE + fhalf;
-  const int b_off = (wn * 128 + frow) * LDS_STRIDE + fhalf;
-  auto read_piece = [&](Frags& f, int buf, int ks, int e) {   // e = 0..7 compile-time
-    if (e < 4)
-      f.a[e] = *reinterpret_cast<const uint4*>(&sA[buf][a_off + e * 32 * LDS_STRIDE + ks * 32]);
-    else
-      f.b[e - 4] = *reinterpret_cast<const uint4*>(&sB[buf][b_off + (e - 4) * 32 * LDS_STRIDE + ks * 32]);
-  };
-
-  v16i acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-  Frags f0, f1;
-  Operands s0, s1;
-  TDQ_LOAD_STAGE(g0, 0);
-  {
-    const float rs = scale[(long long)(my_m / T) * G + my_g];
-    // the accumulators carry a factor 256; folding 2^-8 into the row scale is exact
-    sRow[tid] = acc_dump ? rs : rs * 0.00390625f;
-    sCol[tid] = my_ws;
-    sBias[tid] = my_bs;
-  }
-  TDQ_LOAD_STAGE(g1, 1);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) store_piece(g0, 0, e);
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < 8; ++e) read_piece(f0, 0, 0, e);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) expand_one<0>(s0, f0, e);
-
-  // The stage body is branch-free so that its bundles stay in one scheduling region:
-  // stages past the end re-load the last one and write / read the idle LDS buffer,
-  // which nobody consumes.  GL receives the loads of stage kt + 2, GS holds stage
-  // kt + 1 and is written to LDS; the two sets swap roles every stage.
-#if defined(TDQ_EXP) && (TDQ_EXP & 4)
-#define TDQ_EXP_LOADS(GL, kt)
-#else
-#define TDQ_EXP_LOADS(GL, kt) TDQ_LOAD_STAGE(GL, (kt) + 2); __syncthreads()
-#endif
-#define TDQ_STAGE(kt, GL, GS)                                                           \
-  do {                                                                                  \
-    const int cur = (kt) & 1;                                                           \
-    __builtin_amdgcn_sched_barrier(0);                                                  \
-    half_slab<1>(acc, s0, s1, f0, [&](int b) { read_piece(f1, cur, 1, b); });       /* X0 */ \
-    half_slab<0>(acc, s1, s0, f1, [&](int b) { store_piece(GS, cur ^ 1, b); });     /* Y0 */ \
-    TDQ_EXP_LOADS(GL, kt);                                                              \
-    __builtin_amdgcn_sched_barrier(0);                                                  \
-    half_slab<1>(acc, s0, s1, f1, [&](int b) { read_piece(f0, cur ^ 1, 0, b); });   /* X1 */ \
-    half_slab<0>(acc, s1, s0, f0, [&](int) {});                                     /* Y1 */ \
-  } while (0)
-
-  int kt = 0;
-  for (; kt + 1 < k_tiles; kt += 2) {
-    TDQ_STAGE(kt, g0, g1);
-    TDQ_STAGE(kt + 1, g1, g0);
-  }
-  if (kt < k_tiles) TDQ_STAGE(kt, g0, g1);
-#undef TDQ_STAGE
-#undef TDQ_EXP_LOADS
-#undef TDQ_LOAD_STAGE
-#undef TDQ_PIN
-
-  // Epilogue.  Register r of a 32x32 accumulator fragment held by lane l is
-  // element (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
-  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
-  const bool inside = m0 + BM <= M && n0 + BN <= N;
-  if (inside && !acc_dump) {
-    const long long lane_off = (long long)rquad * ld_y + ccol;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float4 rs4[4];                                   // row scales of rows 8q + rquad + 0..3
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        rs4[q] = *reinterpret_cast<const float4*>(&sRow[wm * 128 + i * 32 + q * 8 + rquad]);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int cl = wn * 128 + j * 32 + ccol;
-        const float ws = sCol[cl], bs = sBias[cl];
-        OUT* tile = Y + (long long)(m0 + wm * 128 + i * 32) * ld_y + (n0 + wn * 128 + j * 32);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float rsv[4] = {rs4[q].x, rs4[q].y, rs4[q].z, rs4[q].w};
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            float y = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws;
-            if (bias) y = y + bs;
-            store_out<OUT>(tile + (long long)(q * 8 + t) * ld_y + lane_off, y);
-          }
-        }
-      }
-    }
-    return;
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int cl = wn * 128 + j * 32 + ccol;
-      const int n = n0 + cl;
-      const float ws = sCol[cl], bs = sBias[cl];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rl = wm * 128 + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
-        const int m = m0 + rl;
-        if (m < M && n < N) {
-          float y;
-          if (acc_dump) {
-            const int a = acc[i][j][r] >> 8;          // exact: accumulator is 256 * acc
-            acc_dump[(long long)m * N + n] = a;
-            y = ((float)a * sRow[rl]) * ws;
-          } else {
-            y = ((float)acc[i][j][r] * sRow[rl]) * ws;
-          }
-          if (bias) y = y + bs;
-          store_out<OUT>(Y + (long long)m * ld_y + n, y);
-        }
-      }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// The same pipeline with the stages brought in by direct-to-LDS loads
-// (global_load_lds_dwordx4): no staging registers, no LDS write instructions in
-// the wavefront's stream (an LDS write of 16 bytes per lane costs more than twice
-// an LDS read of the same size on this chip), and a ring of three LDS slots so the
-// loads run two stages ahead.
+//
+// Stages arrive by direct-to-LDS loads (global_load_lds_dwordx4): no staging
+// registers and no LDS write instructions in the wavefront's stream (an LDS write of
+// 16 bytes per lane costs more than twice an LDS read of the same size on this
+// chip), into a ring of three LDS slots so the loads run two stages ahead.
 //
 // LDS layout of a slot: rows of 64 bytes (4 pieces of 16), piece c of row r stored
 // at position c ^ ((r >> 2) & 3): the 16-byte reads of 16 consecutive rows then
@@ -511,10 +282,52 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_big(
 // global piece that belongs there.
 //
 // These loads are issued from inline assembly, so the compiler neither sees that
-// they write LDS nor counts them in vmcnt; the kernel waits for them itself:
-// every stage issues exactly 8 per thread, hence "vmcnt(8)" = everything but the
-// newest stage has landed.
+// they write LDS nor counts them in vmcnt; the kernel waits for them itself: every
+// stage issues exactly MT + NT per thread, hence "vmcnt(MT + NT)" = everything but
+// the newest stage has landed.
 // ---------------------------------------------------------------------------
+template <int MT, int NT>
+struct Frags {
+  uint4 a[MT], b[NT];     // packed 16-byte pieces: .x .y feed operand set 0, .z .w set 1
+};
+template <int MT, int NT>
+struct Operands {
+  v4i a[MT], b[NT];
+};
+
+template <int SET, int MT, int NT>
+__device__ __forceinline__ void expand_one(Operands<MT, NT>& dst, const Frags<MT, NT>& f, int e,
+                                           u32 hi) {
+  // e is a compile-time constant after unrolling
+  if (e < MT) {
+    dst.a[e] = SET == 0 ? expand(f.a[e].x, f.a[e].y, hi) : expand(f.a[e].z, f.a[e].w, hi);
+  } else {
+    dst.b[e - MT] = SET == 0 ? expand(f.b[e - MT].x, f.b[e - MT].y, hi)
+                             : expand(f.b[e - MT].z, f.b[e - MT].w, hi);
+  }
+}
+
+// MT * NT matrix instructions on `cur`, spread over MT + NT bundles, each with the
+// expansion of one fragment of operand set EXP_SET from `f` into `nxt` and with
+// mem(b), at most one memory instruction.
+template <int EXP_SET, int MT, int NT, typename MEM>
+__device__ __forceinline__ void half_slab(v16i (&acc)[MT][NT], const Operands<MT, NT>& cur,
+                                          Operands<MT, NT>& nxt, const Frags<MT, NT>& f, u32 hi,
+                                          MEM mem) {
+  constexpr int NB = MT + NT, NM = MT * NT;
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+#pragma unroll
+    for (int m = (b * NM) / NB; m < ((b + 1) * NM) / NB; ++m) {
+      const int i = m / NT, j = m % NT;
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+    }
+    expand_one<EXP_SET>(nxt, f, b, hi);
+    mem(b);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 __device__ __forceinline__ void dma16(const uint8_t* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
@@ -522,19 +335,21 @@ __device__ __forceinline__ void dma16(const uint8_t* gptr, unsigned lds_base) {
                : "memory");
 }
 
-constexpr int DMA_SLOT = 2 * 256 * BKB;        // bytes of one ring slot: A then B, 256 rows x 64 B
-
-template <typename OUT>
-__global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_dma(
+template <typename OUT, int MT, int NT>
+__global__ __launch_bounds__(GEMM_THREADS, (MT * NT >= 16 ? 1 : 2)) void k_w4a4_gemm_pipe(
     const uint8_t* __restrict__ Qx, long long ld_q, const int* __restrict__ gid,
     const float* __restrict__ scale, int M, int T, int K, int N, int G,
     const uint8_t* __restrict__ Qw, long long ld_w, const float* __restrict__ w_scale,
     const float* __restrict__ bias, OUT* __restrict__ Y, long long ld_y, int* __restrict__ acc_dump,
     int m_tiles, int n_tiles) {
-  constexpr int BM = 256, BN = 256;
-  __shared__ __attribute__((aligned(1024))) uint8_t ring[3 * DMA_SLOT];
+  constexpr int BM = 64 * MT, BN = 64 * NT, NB = MT + NT;
+  constexpr int SLOT = (BM + BN) * BKB;      // bytes of one ring slot: A rows then B rows, 64 B each
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[3 * SLOT];
   __shared__ __attribute__((aligned(16))) float sRow[BM], sCol[BN], sBias[BN];
 
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give
+  // every XCD whole rows of tiles so the activation tile it streams is reused by
+  // consecutive workgroups of the same XCD.
   const int bid = blockIdx.x;
   const int xcd = bid % XCDS, idx = bid / XCDS;
   const int m_tile = (idx / n_tiles) * XCDS + xcd;
@@ -548,109 +363,115 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_dma(
   const int wm = wave >> 1, wn = wave & 1;
   const int k_tiles = ((K + 1) / 2) / BKB;          // host guarantees K % 128 == 0
 
-  const int my_m = m0 + tid < M ? m0 + tid : M - 1;
-  const int my_g = gid ? gid[my_m] : 0;
-  const int ncol = n0 + tid;
-  const float my_ws = ncol < N ? w_scale[ncol] : 0.f;
-  const float my_bs = (bias && ncol < N) ? bias[ncol] : 0.f;
-
-  // global source of this lane's piece for load i (rows 64 i + 16 w + (l >> 2))
-  const uint8_t* pa[4];
-  const uint8_t* pb[4];
+  // Scales of the epilogue.  The token-set ids are fetched first; the scales that
+  // depend on them are fetched after the first stages' loads have been issued, so
+  // the latencies overlap.
+  int my_m[(BM + GEMM_THREADS - 1) / GEMM_THREADS], my_g[(BM + GEMM_THREADS - 1) / GEMM_THREADS];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int rl = 64 * i + 16 * wave + (lane >> 2);          // row inside the tile
-    const int c = (lane & 3) ^ ((rl >> 2) & 3);               // logical piece stored at position l & 3
-    int r = m0 + rl;
-    r = r < M ? r : M - 1;
-    pa[i] = Qx + (long long)r * ld_q + c * 16;
-    int n = n0 + rl;
-    n = n < N ? n : N - 1;
-    pb[i] = Qw + (long long)n * ld_w + c * 16;
+  for (int u = 0; u < (BM + GEMM_THREADS - 1) / GEMM_THREADS; ++u) {
+    const int m = m0 + tid + u * GEMM_THREADS;
+    my_m[u] = m < M ? m : M - 1;
+    my_g[u] = gid ? gid[my_m[u]] : 0;
+  }
+
+  // global source of this lane's piece of load i (rows 64 i + 16 w + (l >> 2))
+  const uint8_t* pa[MT];
+  const uint8_t* pb[NT];
+  {
+    const int rl0 = 16 * wave + (lane >> 2);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int rl = 64 * i + rl0;                            // row inside the tile
+      const int c = (lane & 3) ^ ((rl >> 2) & 3);             // logical piece stored at position l & 3
+      int r = m0 + rl;
+      r = r < M ? r : M - 1;
+      pa[i] = Qx + (long long)r * ld_q + c * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      const int rl = 64 * i + rl0;
+      const int c = (lane & 3) ^ ((rl >> 2) & 3);
+      int n = n0 + rl;
+      n = n < N ? n : N - 1;
+      pb[i] = Qw + (long long)n * ld_w + c * 16;
+    }
   }
   const unsigned ring_base =
       (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)ring;
   const unsigned dma_base = __builtin_amdgcn_readfirstlane(ring_base + wave * 1024);
-  auto dma_piece = [&](int slot, int kt, int e) {     // slot, e compile-time; e = 0..7
+  auto dma_piece = [&](int slot, int kt, int e) {     // slot, e compile-time; e = 0 .. NB-1
     const int kc = kt < k_tiles ? kt : k_tiles - 1;    // past the end: harmless re-load
     const long long ko = (long long)kc * BKB;
-    const unsigned d = dma_base + slot * DMA_SLOT + e * 4096;
-    dma16((e < 4 ? pa[e & 3] : pb[e & 3]) + ko, d);
+    if (e < MT)
+      dma16(pa[e] + ko, dma_base + slot * SLOT + e * 4096);
+    else
+      dma16(pb[e - MT] + ko, dma_base + slot * SLOT + BM * BKB + (e - MT) * 4096);
   };
-#define TDQ_DMA_STAGE(slot, kt)                                                          \
-  do {                                                                                   \
-    const int kc = (kt) < k_tiles ? (kt) : k_tiles - 1; /* past the end: harmless */     \
-    const long long ko = (long long)kc * BKB;                                            \
-    const unsigned d = dma_base + (slot) * DMA_SLOT;                                     \
-    dma16(pa[0] + ko, d);                                                                \
-    dma16(pa[1] + ko, d + 4096);                                                         \
-    dma16(pa[2] + ko, d + 8192);                                                         \
-    dma16(pa[3] + ko, d + 12288);                                                        \
-    dma16(pb[0] + ko, d + 16384);                                                        \
-    dma16(pb[1] + ko, d + 16384 + 4096);                                                 \
-    dma16(pb[2] + ko, d + 16384 + 8192);                                                 \
-    dma16(pb[3] + ko, d + 16384 + 12288);                                                \
-  } while (0)
 
   // fragment reads: lane (row r' = l & 31, half h = l >> 5) of fragment e reads piece
-  // 2 ks + h of row 32 e + r' (+ 128 wm / wn); the row's swizzle only depends on r'
+  // 2 ks + h of row 32 e + r' (+ the wavefront's offset); the swizzle only depends on r'
   const int frow = lane & 31, fh = lane >> 5, swz = (frow >> 2) & 3;
-  const int a_row = (wm * 128 + frow) * 64, b_row = 16384 + (wn * 128 + frow) * 64;
+  const int a_row = (wm * 32 * MT + frow) * 64, b_row = BM * BKB + (wn * 32 * NT + frow) * 64;
   const int off_k0 = ((0 + fh) ^ swz) * 16, off_k1 = ((2 + fh) ^ swz) * 16;
-  auto read_piece = [&](Frags& f, int slot, int ks, int e) {   // slot, ks, e compile-time
+  auto read_piece = [&](Frags<MT, NT>& f, int slot, int ks, int e) {   // slot, ks, e compile-time
     const int off = ks == 0 ? off_k0 : off_k1;
-    if (e < 4)
-      f.a[e] = *reinterpret_cast<const uint4*>(&ring[slot * DMA_SLOT + a_row + e * 2048 + off]);
+    if (e < MT)
+      f.a[e] = *reinterpret_cast<const uint4*>(&ring[slot * SLOT + a_row + e * 2048 + off]);
     else
-      f.b[e - 4] =
-          *reinterpret_cast<const uint4*>(&ring[slot * DMA_SLOT + b_row + (e - 4) * 2048 + off]);
+      f.b[e - MT] =
+          *reinterpret_cast<const uint4*>(&ring[slot * SLOT + b_row + (e - MT) * 2048 + off]);
   };
 
-  v16i acc[4][4];
+  v16i acc[MT][NT];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-  Frags f0, f1;
-  Operands s0, s1;
-  TDQ_DMA_STAGE(0, 0);
-  TDQ_DMA_STAGE(1, 1);
-  {
-    const float rs = scale[(long long)(my_m / T) * G + my_g];
-    // the accumulators carry a factor 256; folding 2^-8 into the row scale is exact
-    sRow[tid] = acc_dump ? rs : rs * 0.00390625f;
-    sCol[tid] = my_ws;
-    sBias[tid] = my_bs;
+  Frags<MT, NT> f0, f1;
+  Operands<MT, NT> s0, s1;
+  u32 hi;                                   // 0xF0F0F0F0 in a scalar register
+  asm volatile("s_mov_b32 %0, 0xf0f0f0f0" : "=s"(hi));
+#pragma unroll
+  for (int e = 0; e < NB; ++e) dma_piece(0, 0, e);
+#pragma unroll
+  for (int e = 0; e < NB; ++e) dma_piece(1, 1, e);
+#pragma unroll
+  for (int u = 0; u < (BM + GEMM_THREADS - 1) / GEMM_THREADS; ++u) {
+    const int i = tid + u * GEMM_THREADS;
+    if (i < BM) {
+      const float rs = scale[(long long)(my_m[u] / T) * G + my_g[u]];
+      // the accumulators carry a factor 256; folding 2^-8 into the row scale is exact
+      sRow[i] = acc_dump ? rs : rs * 0.00390625f;
+    }
   }
-  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");      // stage 0 has landed
+  for (int j = tid; j < BN; j += GEMM_THREADS) {
+    const int n = n0 + j;
+    sCol[j] = n < N ? w_scale[n] : 0.f;
+    sBias[j] = (bias && n < N) ? bias[n] : 0.f;
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NB) : "memory");      // stage 0 has landed
   __syncthreads();
 #pragma unroll
-  for (int e = 0; e < 8; ++e) read_piece(f0, 0, 0, e);
+  for (int e = 0; e < NB; ++e) read_piece(f0, 0, 0, e);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) expand_one<0>(s0, f0, e);
+  for (int e = 0; e < NB; ++e) expand_one<0>(s0, f0, e, hi);
 
   // One stage: CUR holds stage kt, NXT stage kt + 1 (in flight until the barrier),
-  // LD receives stage kt + 2 (the slot that held stage kt - 1).
-#if defined(TDQ_EXP) && (TDQ_EXP & 4)
-#define TDQ_EXP_DMA(LD, kt, b)
-#define TDQ_EXP_SYNC()
-#else
-#define TDQ_EXP_DMA(LD, kt, b) dma_piece(LD, kt, b)
-#define TDQ_EXP_SYNC()                                   \
-  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       \
-  __syncthreads()
-#endif
-#define TDQ_STAGE(kt, CUR, NXT, LD)                                                      \
-  do {                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                                   \
-    half_slab<1>(acc, s0, s1, f0, [&](int b) { read_piece(f1, CUR, 1, b); });   /* X0 */ \
-    half_slab<0>(acc, s1, s0, f1, [&](int b) { TDQ_EXP_DMA(LD, (kt) + 2, b); }); /* Y0 */ \
-    TDQ_EXP_SYNC();                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                   \
-    half_slab<1>(acc, s0, s1, f1, [&](int b) { read_piece(f0, NXT, 0, b); });   /* X1 */ \
-    half_slab<0>(acc, s1, s0, f0, [&](int) {});                                 /* Y1 */ \
+  // LD receives stage kt + 2 (the slot that held stage kt - 1).  The body is
+  // branch-free so that its bundles stay in one scheduling region: stages past the
+  // end re-load the last one into an idle slot that nobody reads.
+#define TDQ_STAGE(kt, CUR, NXT, LD)                                                              \
+  do {                                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    half_slab<1>(acc, s0, s1, f0, hi, [&](int b) { read_piece(f1, CUR, 1, b); });       /* X0 */ \
+    half_slab<0>(acc, s1, s0, f1, hi, [&](int b) { dma_piece(LD, (kt) + 2, b); });      /* Y0 */ \
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NB) : "memory");                                    \
+    __syncthreads();                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    half_slab<1>(acc, s0, s1, f1, hi, [&](int b) { read_piece(f0, NXT, 0, b); });       /* X1 */ \
+    half_slab<0>(acc, s1, s0, f0, hi, [&](int) {});                                     /* Y1 */ \
   } while (0)
 
   int kt = 0;
@@ -663,51 +484,67 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_dma(
   if (kt + 1 < k_tiles) TDQ_STAGE(kt + 1, 1, 2, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing of ours may still be landing
 #undef TDQ_STAGE
-#undef TDQ_EXP_DMA
-#undef TDQ_EXP_SYNC
-#undef TDQ_DMA_STAGE
 
   // Epilogue.  Register r of a 32x32 accumulator fragment held by lane l is
   // element (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
   const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+#if defined(TDQ_EXP) && (TDQ_EXP & 16)
+  if (ld_y != -12345) {            // experiment: no epilogue at all (keeps the accumulators alive)
+    if (acc[0][0][0] == 0x7fffffff) Y[0] = (OUT)1.0f;
+    return;
+  }
+#endif
   const bool inside = m0 + BM <= M && n0 + BN <= N;
-  if (inside && !acc_dump) {
-    const long long lane_off = (long long)rquad * ld_y + ccol;
+  if (inside && !acc_dump && (long long)(BM + 8) * ld_y < (1ll << 31) / (long long)sizeof(OUT)) {
+    // Fast path: whole tile inside Y.  Every address is a wavefront-uniform row pointer
+    // plus one per-lane 32-bit offset, and the bias branch is taken once, not per element.
+    const int lane_off = rquad * (int)ld_y + ccol;
+    auto body = [&](auto with_bias) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float4 rs4[4];                                   // row scales of rows 8q + rquad + 0..3
+      for (int i = 0; i < MT; ++i) {
+        float4 rs4[4];                                 // row scales of rows 8q + rquad + 0..3
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        rs4[q] = *reinterpret_cast<const float4*>(&sRow[wm * 128 + i * 32 + q * 8 + rquad]);
+        for (int q = 0; q < 4; ++q)
+          rs4[q] = *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int cl = wn * 128 + j * 32 + ccol;
-        const float ws = sCol[cl], bs = sBias[cl];
-        OUT* tile = Y + (long long)(m0 + wm * 128 + i * 32) * ld_y + (n0 + wn * 128 + j * 32);
+        for (int j = 0; j < NT; ++j) {
+          const int cl = wn * 32 * NT + j * 32 + ccol;
+          const float ws = sCol[cl], bs = sBias[cl];
+          OUT* tile =
+              Y + (long long)(m0 + wm * 32 * MT + i * 32) * ld_y + (n0 + wn * 32 * NT + j * 32);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float rsv[4] = {rs4[q].x, rs4[q].y, rs4[q].z, rs4[q].w};
+          for (int q = 0; q < 4; ++q) {
+            const float rsv[4] = {rs4[q].x, rs4[q].y, rs4[q].z, rs4[q].w};
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            float y = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws;
-            if (bias) y = y + bs;
-            store_out<OUT>(tile + (long long)(q * 8 + t) * ld_y + lane_off, y);
+            for (int t = 0; t < 4; ++t) {
+              float y = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws;
+              if (decltype(with_bias)::value) y = y + bs;
+              OUT* rowp = tile + (long long)(q * 8 + t) * ld_y;     // uniform
+#if defined(TDQ_EXP) && (TDQ_EXP & 8)
+              if (ld_y == -12345)
+#endif
+              store_out<OUT>(rowp + lane_off, y);
+            }
           }
         }
       }
-    }
+    };
+    if (bias)
+      body(std::true_type{});
+    else
+      body(std::false_type{});
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int cl = wn * 128 + j * 32 + ccol;
+    for (int j = 0; j < NT; ++j) {
+      const int cl = wn * 32 * NT + j * 32 + ccol;
       const int n = n0 + cl;
       const float ws = sCol[cl], bs = sBias[cl];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int rl = wm * 128 + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
+        const int rl = wm * 32 * MT + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
         const int m = m0 + rl;
         if (m < M && n < N) {
           float y;
@@ -739,30 +576,18 @@ static void launch_tile(const uint8_t* Qx, long long ld_q, const int* gid, const
                      acc_dump, m_tiles, n_tiles);
 }
 
-template <typename OUT>
-static void launch_dma(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale, int M,
-                       int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
-                       const float* w_scale, const float* bias, void* Y, long long ld_y,
-                       int* acc_dump, hipStream_t st) {
-  const int m_tiles = (M + 255) / 256, n_tiles = (N + 255) / 256;
+template <typename OUT, int MT, int NT>
+static void launch_pipe(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale, int M,
+                        int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
+                        const float* w_scale, const float* bias, void* Y, long long ld_y,
+                        int* acc_dump, hipStream_t st) {
+  constexpr int BM = 64 * MT, BN = 64 * NT;
+  const int m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
   const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
   const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
-  hipLaunchKernelGGL((k_w4a4_gemm_dma<OUT>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q, gid,
-                     scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, static_cast<OUT*>(Y), ld_y,
-                     acc_dump, m_tiles, n_tiles);
-}
-
-template <typename OUT>
-static void launch_big(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale, int M,
-                       int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
-                       const float* w_scale, const float* bias, void* Y, long long ld_y,
-                       int* acc_dump, hipStream_t st) {
-  const int m_tiles = (M + 255) / 256, n_tiles = (N + 255) / 256;
-  const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
-  const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
-  hipLaunchKernelGGL((k_w4a4_gemm_big<OUT>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q, gid,
-                     scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, static_cast<OUT*>(Y), ld_y,
-                     acc_dump, m_tiles, n_tiles);
+  hipLaunchKernelGGL((k_w4a4_gemm_pipe<OUT, MT, NT>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx,
+                     ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, static_cast<OUT*>(Y),
+                     ld_y, acc_dump, m_tiles, n_tiles);
 }
 
 hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale,
@@ -773,15 +598,16 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
   const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
   int mode = big_tiles >= 512 ? (K % 128 == 0 ? 97 : 44) : 22;
   if (const char* e = getenv("TDQ_GEMM_TILE")) mode = atoi(e);
-  if ((mode == 97 || mode == 99) && K % 128 != 0) mode = 44;
+  if (mode >= 95 && K % 128 != 0) mode = 44;
 #define TDQ_GEMM(OUT, MT, NT)                                                                   \
   launch_tile<OUT, MT, NT>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, \
                            acc_dump, st)
 #define TDQ_GEMM_MODES(OUT)                       \
   switch (mode) {                                 \
     case 44: TDQ_GEMM(OUT, 4, 4); break;          \
-    case 97: launch_dma<OUT>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
-    case 99: launch_big<OUT>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
+    case 97: launch_pipe<OUT, 4, 4>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
+    case 96: launch_pipe<OUT, 4, 2>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
+    case 95: launch_pipe<OUT, 2, 4>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
     case 42: TDQ_GEMM(OUT, 4, 2); break;          \
     case 24: TDQ_GEMM(OUT, 2, 4); break;          \
     default: TDQ_GEMM(OUT, 2, 2); break;          \
