@@ -336,3 +336,42 @@ def test_cfg4_full_size_sampled():
         acc_ref, Y_ref = O.w4a4_linear(q_gpu, scale[b][gid[b, rows]], qw_ref, sw_ref)
         Y_gpu = Y[b * T + torch.from_numpy(rows).to(U.dev())].cpu().numpy()
         assert np.array_equal(Y_gpu, Y_ref)
+
+
+# ------------------------------------- large-tile contraction, sampled checks
+@pytest.mark.parametrize("out_dtype,with_bias,ld_pad", [(torch.float32, True, 0),
+                                                        (torch.float16, False, 0),
+                                                        (torch.float16, True, 8),
+                                                        (torch.float32, False, 2)])
+def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad):
+    """A shape that takes the large-tile kernel (many 256x256 tiles, K a multiple of
+    128) without the accumulator dump, so interior tiles take the epilogue's fast
+    path and the ragged last row of tiles the bounds-checked one.  ld_pad gives Y a
+    padded leading dimension, whose padding must stay untouched.  The oracle checks
+    whole tiles' worth of rows plus a random sample."""
+    M, K, N = 8192 + 37, 256, 4096
+    _say(f"[gemm-large] M={M} K={K} N={N} out={out_dtype} bias={with_bias} ld_pad={ld_pad}")
+    qx = I.random_codes((M, K), 101)
+    qw = I.random_codes((N, K), 102)
+    rng = np.random.Generator(np.random.PCG64(103))
+    B, T, G = 1, M, 8
+    gid = rng.integers(0, G, (B, T)).astype(np.int32)
+    scale = rng.uniform(0.01, 2.0, (B, G)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    bias = rng.normal(0, 0.5, N).astype(np.float32) if with_bias else None
+    Ybuf = torch.full((M, N + ld_pad), -77.0, dtype=out_dtype, device=U.dev())
+    Y = tdq.tdq_w4a4_linear(U.pack_to_device(qx), torch.from_numpy(gid).to(U.dev()),
+                            torch.from_numpy(scale).to(U.dev()), B, T, K, U.pack_to_device(qw),
+                            torch.from_numpy(sw).to(U.dev()),
+                            None if bias is None else torch.from_numpy(bias).to(U.dev()),
+                            out_dtype, out=Ybuf[:, :N])
+    torch.cuda.synchronize()
+    if ld_pad:
+        assert (Ybuf[:, N:] == -77.0).all(), "wrote past the row end"
+    rows = np.unique(np.concatenate([np.arange(0, 256), np.arange(3 * 256 - 8, 3 * 256 + 8),
+                                     rng.choice(M, 128, replace=False), np.arange(8192 - 8, M)]))
+    _, Y_ref = O.w4a4_linear(qx[rows], O.row_scales(gid, scale)[rows], qw, sw, bias)
+    if out_dtype == torch.float16:
+        Y_ref = Y_ref.astype(np.float16)
+    Y_gpu = Y[torch.from_numpy(rows).to(U.dev())].cpu().numpy()
+    assert np.array_equal(Y_gpu, Y_ref)
