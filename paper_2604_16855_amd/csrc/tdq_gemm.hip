@@ -66,6 +66,10 @@ __device__ __forceinline__ void store_out<float>(float* p, float v) {
 }
 template <>
 __device__ __forceinline__ void store_out<_Float16>(_Float16* p, float v) {
+  // v is the binary32 result; it is rounded to binary16 in a second, separate step.
+  // The empty asm keeps the compiler from merging the last binary32 operation with the
+  // conversion into one mixed-precision instruction, which would round only once.
+  asm volatile("" : "+v"(v));
   __builtin_nontemporal_store((_Float16)v, p);
 }
 
