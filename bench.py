@@ -62,7 +62,9 @@ class Layer:
         self.Y = torch.empty((lc.M, lc.N), dtype=out_dtype, device=dev)
         e = lc.M * lc.C
         s = 2 if lc.dtype == "f16" else 4
-        sweeps_cal = 3 if lc.dtype == "f16" else 1 + 4       # stats + radix levels
+        # sweeps of X inside tdq_calibrate_groups: the statistics sweep plus the rank
+        # select (one sweep for binary16, four radix levels for binary32)
+        sweeps_cal = 2 if lc.dtype == "f16" else 1 + 4
         self.bytes = {
             "calibrate": sweeps_cal * e * s + lc.M * 20,
             "quantize": e * s + lc.M * 4 + e // 2,
@@ -196,6 +198,7 @@ def main():
         "roofline": roofline,
         "rooflines": rooflines,
     }
+    out["rank_select_missed_sets"] = [tdq.exact_select_sets(L.ws) for L in layers]
     if not args.no_quality:
         out["quality"] = quality(fc1, torch, tdq)
     if not args.no_cpu_baseline:
@@ -235,26 +238,38 @@ def quality(L, torch, tdq):
     return out
 
 
-def cpu_baseline(L, np):
+def cpu_baseline(L, np, budget_s=12.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the
-    activation path (calibrate + quantize) of the first images of fc1's input and
-    the contraction of 64 rows.  Host cores of this machine; numpy uses one thread."""
+    activation path (calibrate + quantize) of the first images of fc1's input, and the
+    contraction of the first rows, each sized from a one-image / 16-row probe to take
+    about budget_s / 2 seconds.  Host cores of this machine; numpy runs these loops and its
+    integer matmul on one thread."""
     from oracle import tdq_oracle as O
     lc = L.lc
-    nimg = min(2, lc.B)
-    X = L.X_host[:nimg]
     p = O.Params(n_groups=lc.G)
-    t0 = time.perf_counter()
-    gid, clip, scale, _ = O.calibrate_groups(X, p)
-    q = O.quantize_act(X, gid, clip, scale, p)
-    t_act = time.perf_counter() - t0
-    e = X.size
-    rows = 64
+
+    def act(n):
+        X = L.X_host[:n]
+        t0 = time.perf_counter()
+        gid, clip, scale, _ = O.calibrate_groups(X, p)
+        q = O.quantize_act(X, gid, clip, scale, p)
+        return time.perf_counter() - t0, X.size, q
+
+    t1, _, _ = act(1)
+    nimg = int(max(1, min(lc.B, round(budget_s / 2 / max(t1, 1e-3)))))
+    t_act, e, q = act(nimg)
     qw = np.random.Generator(np.random.PCG64(1)).integers(-7, 8, (lc.N, lc.C), dtype=np.int8)
-    t0 = time.perf_counter()
-    O.w4a4_linear(q.reshape(-1, lc.C)[:rows], np.ones(rows, np.float32), qw,
-                  np.ones(lc.N, np.float32))
-    t_mm = time.perf_counter() - t0
+    q2 = q.reshape(-1, lc.C)
+    ones_n = np.ones(lc.N, np.float32)
+
+    def mm(rows):
+        t0 = time.perf_counter()
+        O.w4a4_linear(q2[:rows], np.ones(rows, np.float32), qw, ones_n)
+        return time.perf_counter() - t0
+
+    t16 = mm(16)
+    rows = int(max(16, min(q2.shape[0], round(16 * budget_s / 2 / max(t16, 1e-3)))))
+    t_mm = mm(rows)
     return {"value": round(e * 2.5 / t_act / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"activation path (calibrate+quantize) of {nimg} of {lc.B} images of the "
                       f"fc1 input, {e} elements, {t_act:.2f} s; contraction of {rows} rows x "

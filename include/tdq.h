@@ -54,6 +54,10 @@ typedef enum {
 
 #define TDQ_FLAG_C1 1u /* constraint C1: Delta <= tau * sigma   (Eq. tau_constraint) */
 #define TDQ_FLAG_C2 2u /* constraint C2: Delta/2 <= Q_zr(|x|)   (Eq. zr_constraint)  */
+/* Validation switch, no effect on the result: resolve the zr rank of every token set
+ * of a binary16 input by the multi-level radix select alone (the route that is
+ * otherwise taken only by a set whose sampled key interval missed the rank). */
+#define TDQ_FLAG_EXACT_SELECT 256u
 
 #define TDQ_MAX_GROUPS 256
 
@@ -90,6 +94,10 @@ typedef struct tdq_group_stats {
 /* Bits of the device status word (first uint32 of the workspace after a call
  * to tdq_calibrate_groups; read it back after synchronising the stream). */
 #define TDQ_DEV_NONFINITE 1u /* X holds an Inf or NaN: results undefined          */
+/* The second uint32 of the workspace is a diagnostic: after a calibration of
+ * binary16 input, the number of (image, token set) pairs whose zr rank was resolved
+ * by the multi-level radix select because the sampled key interval missed it (or
+ * because TDQ_FLAG_EXACT_SELECT was set).  It has no bearing on the results. */
 
 int tdq_version(void);
 const char* tdq_status_string(int status);

@@ -6,117 +6,9 @@
 // clipx, dequant), Sec. 4.3 (DCRP: Eqs. tau_constraint, zr_constraint, dcrp),
 // Supp. "Quantile Implementation" (rank k = ceil(p n)), Supp. numerical
 // conventions (eps values, ties-to-even rounding), Eq. weight_quant.
-#include "tdq_internal.hpp"
+#include "tdq_device.hpp"
 
 namespace tdq {
-
-// ---------------------------------------------------------------------------
-// element access
-// ---------------------------------------------------------------------------
-typedef unsigned short u16;
-typedef unsigned int u32;
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ float h2f(u32 bits16) {
-  return (float)__builtin_bit_cast(_Float16, (u16)bits16);
-}
-
-template <typename T>
-struct Elem;
-template <>
-struct Elem<u16> {                 // fp16 stored as raw bits
-  static constexpr int V = 8;      // elements per 16-byte load
-  static constexpr u32 kNonFinite = 0x7C00u;
-  __device__ static __forceinline__ u32 key(u16 x) { return x & 0x7FFFu; }
-  __device__ static __forceinline__ float val(u16 x) { return h2f(x); }
-  __device__ static __forceinline__ float key_to_float(u32 k) { return h2f(k); }
-  __device__ static __forceinline__ void unpack(const uint4& q, u16 out[8]) {
-    out[0] = q.x & 0xFFFF; out[1] = q.x >> 16; out[2] = q.y & 0xFFFF; out[3] = q.y >> 16;
-    out[4] = q.z & 0xFFFF; out[5] = q.z >> 16; out[6] = q.w & 0xFFFF; out[7] = q.w >> 16;
-  }
-};
-template <>
-struct Elem<float> {
-  static constexpr int V = 4;
-  static constexpr u32 kNonFinite = 0x7F800000u;
-  __device__ static __forceinline__ u32 key(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
-  __device__ static __forceinline__ float val(float x) { return x; }
-  __device__ static __forceinline__ float key_to_float(u32 k) { return __uint_as_float(k); }
-  __device__ static __forceinline__ void unpack(const uint4& q, float out[4]) {
-    out[0] = __uint_as_float(q.x); out[1] = __uint_as_float(q.y);
-    out[2] = __uint_as_float(q.z); out[3] = __uint_as_float(q.w);
-  }
-};
-
-// Rows are shared out to groups of L adjacent lanes (L a power of two <= 64), so a
-// 64-wide wavefront covers 64/L rows; each lane reads 16-byte pieces of its row.
-static int lanes_per_row(int C, int V) {
-  int nvec = (C + V - 1) / V;
-  int L = 1;
-  while (L < nvec && L < 64) L <<= 1;
-  return L;
-}
-
-// Reductions over groups of L adjacent lanes (L a power of two <= 64) with DPP
-// row shifts and row broadcasts, i.e. at vector-ALU speed instead of one LDS round
-// trip per step.  The result is valid in the LAST lane of every group
-// (lane % L == L - 1); the other lanes hold partial windows.
-//   steps 1, 2, 4, 8: row_shr inside rows of 16 lanes (zero shifted in),
-//   16: row_bcast15 into rows 1 and 3,  32: row_bcast31 into rows 2 and 3.
-#define TDQ_DPP_ROW_SHR(n) (0x110 + (n))
-#define TDQ_DPP_ROW_BCAST15 0x142
-#define TDQ_DPP_ROW_BCAST31 0x143
-
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ u32 dpp_u32(u32 v) {
-  return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
-}
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ double dpp_f64(double v) {
-  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
-  const u32 lo = dpp_u32<CTRL, ROW_MASK>((u32)b), hi = dpp_u32<CTRL, ROW_MASK>((u32)(b >> 32));
-  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
-}
-
-template <int L>
-__device__ __forceinline__ double group_sum_f64(double v) {
-  if (L > 1) v += dpp_f64<TDQ_DPP_ROW_SHR(1), 0xF>(v);
-  if (L > 2) v += dpp_f64<TDQ_DPP_ROW_SHR(2), 0xF>(v);
-  if (L > 4) v += dpp_f64<TDQ_DPP_ROW_SHR(4), 0xF>(v);
-  if (L > 8) v += dpp_f64<TDQ_DPP_ROW_SHR(8), 0xF>(v);
-  if (L > 16) v += dpp_f64<TDQ_DPP_ROW_BCAST15, 0xA>(v);
-  if (L > 32) v += dpp_f64<TDQ_DPP_ROW_BCAST31, 0xC>(v);
-  return v;
-}
-template <int L>
-__device__ __forceinline__ u32 group_max_u32(u32 v) {
-  u32 o;
-  if (L > 1) { o = dpp_u32<TDQ_DPP_ROW_SHR(1), 0xF>(v); v = o > v ? o : v; }
-  if (L > 2) { o = dpp_u32<TDQ_DPP_ROW_SHR(2), 0xF>(v); v = o > v ? o : v; }
-  if (L > 4) { o = dpp_u32<TDQ_DPP_ROW_SHR(4), 0xF>(v); v = o > v ? o : v; }
-  if (L > 8) { o = dpp_u32<TDQ_DPP_ROW_SHR(8), 0xF>(v); v = o > v ? o : v; }
-  if (L > 16) { o = dpp_u32<TDQ_DPP_ROW_BCAST15, 0xA>(v); v = o > v ? o : v; }
-  if (L > 32) { o = dpp_u32<TDQ_DPP_ROW_BCAST31, 0xC>(v); v = o > v ? o : v; }
-  return v;
-}
-
-// xor-butterfly forms (every lane gets the result), used off the hot paths
-template <int L, typename F>
-__device__ __forceinline__ F xor_reduce_sum(F v) {
-#pragma unroll
-  for (int m = L >> 1; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
-  return v;
-}
-template <int L>
-__device__ __forceinline__ u32 xor_reduce_max(u32 v) {
-#pragma unroll
-  for (int m = L >> 1; m > 0; m >>= 1) {
-    u32 o = (u32)__shfl_xor((int)v, m, 64);
-    v = o > v ? o : v;
-  }
-  return v;
-}
 
 // ---------------------------------------------------------------------------
 // K_a: per-token range and moments (one sweep of X)
@@ -343,7 +235,8 @@ struct SetAcc {
 __global__ __launch_bounds__(kAssignThreads) void k_assign(
     const float* __restrict__ r, const double* __restrict__ s1, const double* __restrict__ s2,
     int T, int C, int G, Scalars sc, int* __restrict__ gid, GroupWork* __restrict__ grp,
-    u32* __restrict__ hist, LevelPlan lp, long long groups_total, u32* __restrict__ img_flag) {
+    u32* __restrict__ hist, LevelPlan lp, long long groups_total, u32* __restrict__ img_flag,
+    u32* __restrict__ status) {
   extern __shared__ __attribute__((aligned(16))) unsigned char assign_lds[];
   __shared__ u32 s_min[kAssignThreads / 64], s_max[kAssignThreads / 64];
   __shared__ u32 s_lo, s_hi;
@@ -382,6 +275,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
     s_lo = lo > floor_key ? lo : floor_key;
     s_hi = hi;
     img_flag[b] = hi >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
+    if (b == 0) status[1] = 0u;           // count of sets the single-sweep select misses
   }
   __syncthreads();
   const u32 lo = s_lo, hi = s_hi;
@@ -418,18 +312,11 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
     int g = -1;
     if (live) {
       g = 0;
-#if defined(TDQ_EXP) && (TDQ_EXP & 64)
-      if (G > 1 && hi != lo && k > lo) g = (int)((k - lo) >> 27) % G;
-#else
       if (G > 1 && hi != lo && k > lo)
         g = (int)(((unsigned long long)(k - lo) * (unsigned long long)G) / width);
-#endif
       gb[t] = g;
     }
     unsigned long long todo = __ballot(live);
-#if defined(TDQ_EXP) && (TDQ_EXP & 16)
-    todo = 0;
-#endif
     while (todo) {
       const int leader = __ffsll((long long)todo) - 1;
       const int gg = __builtin_amdgcn_readlane(g, leader);
@@ -483,9 +370,6 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
   }
   // clear this image's slice of every level's histogram
   size_t off = 0;
-#if defined(TDQ_EXP) && (TDQ_EXP & 32)
-  if (T < 0)
-#endif
   for (int l = 0; l < lp.n_levels; ++l) {
     const size_t nb = (size_t)1 << lp.bits[l];
     u32* h = hist + off + (size_t)b * G * nb;
@@ -496,12 +380,12 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
 
 hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int C,
                          int G, const Scalars& sc, int* gid, GroupWork* grp, unsigned* hist,
-                         unsigned* img_flag, const LevelPlan& lp, hipStream_t st) {
+                         unsigned* img_flag, unsigned* status, const LevelPlan& lp, hipStream_t st) {
   int nw = 2048 / G;                       // keep the per-wavefront accumulators under 48 KiB
   nw = nw > kAssignThreads / 64 ? kAssignThreads / 64 : (nw < 1 ? 1 : nw);
   const size_t lds = (size_t)nw * G * sizeof(SetAcc);
   hipLaunchKernelGGL(k_assign, dim3(B), dim3(nw * 64), lds, st, r, s1, s2, T, C, G, sc, gid, grp,
-                     hist, lp, (long long)B * G, img_flag);
+                     hist, lp, (long long)B * G, img_flag, status);
   return hipGetLastError();
 }
 
@@ -519,9 +403,11 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
                                                        const int* __restrict__ gid,
                                                        const GroupWork* __restrict__ grp,
                                                        u32* __restrict__ hist, int shift, int bits,
-                                                       int rows_per_block) {
+                                                       int rows_per_block,
+                                                       const u32* __restrict__ missed) {
   extern __shared__ u32 lds[];
   constexpr int V = Elem<T>::V;
+  if (missed && *missed == 0) return;      // nothing left to resolve (uniform over the grid)
   // The top level walks X backwards: it runs right after the forward statistics sweep,
   // so the end of X is what the last-level cache still holds.
   const int b = FIRST ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
@@ -542,7 +428,8 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
   for (int rr = slot; rr < nrows; rr += SLOTS) {
     const long long row = (long long)b * T_ + row0 + rr;
     const int g = gid[row];
-    const u32 prefix = FIRST ? 0u : grp[(long long)b * G + g].prefix;
+    const u32 prefix = (FIRST && !missed) ? 0u : grp[(long long)b * G + g].prefix;
+    if (missed && prefix == kResolved) continue;          // this row's set is done
     u32* h = lds + (g << bits);
     const T* xp = X + row * ld;
 #pragma unroll 2
@@ -582,7 +469,8 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
 
 template <typename T>
 static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, const int* gid,
-                         const GroupWork* grp, u32* hist, int shift, int bits, hipStream_t st) {
+                         const GroupWork* grp, u32* hist, int shift, int bits, const u32* missed,
+                         hipStream_t st) {
   constexpr int V = Elem<T>::V;
   const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % V == 0) ? 1 : 0;
   const int L = lanes_per_row(C, V);
@@ -604,10 +492,12 @@ static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, 
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<T, LL, true>),         \
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
       hipLaunchKernelGGL((k_hist<T, LL, true>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, \
-                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);  \
+                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb,   \
+                         missed);                                                              \
     } else {                                                                                   \
       hipLaunchKernelGGL((k_hist<T, LL, false>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, \
-                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);  \
+                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb,   \
+                         missed);                                                              \
     }                                                                                          \
     break;
   switch (L) {
@@ -619,12 +509,12 @@ static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, 
 
 hipError_t launch_hist(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                        const int* gid, const GroupWork* grp, unsigned* hist_level, int shift,
-                       int bits, hipStream_t st) {
+                       int bits, const unsigned* missed, hipStream_t st) {
   if (dt == TDQ_F16)
     return hist_t<u16>(static_cast<const u16*>(X), B, T, C, ld, G, gid, grp, hist_level, shift,
-                       bits, st);
+                       bits, missed, st);
   return hist_t<float>(static_cast<const float*>(X), B, T, C, ld, G, gid, grp, hist_level, shift,
-                       bits, st);
+                       bits, missed, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -638,10 +528,12 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
                                                float* __restrict__ clip, float* __restrict__ scale,
                                                tdq_group_stats* __restrict__ stats,
                                                const u32* __restrict__ img_flag, int B,
-                                               u32* __restrict__ status) {
+                                               u32* __restrict__ status,
+                                               const u32* __restrict__ missed) {
   const int idx = blockIdx.x;
   const int lane = threadIdx.x;
-  if (last && idx == 0) {   // fold the per-image flags into the status word
+  if (missed && (*missed == 0 || grp[idx].prefix == kResolved)) return;   // already resolved
+  if (last && idx == 0 && !missed) {   // fold the per-image flags into the status word
     u32 f = 0;
     for (int b = lane; b < B; b += 64) f |= img_flag[b];
     const unsigned long long any = __ballot(f != 0);
@@ -693,44 +585,16 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
     return;
   }
   if (lane != 0) return;
-  float thr = 0.f, c_tau = 0.f, c_zr = 0.f, c, d;
-  u32 bind = TDQ_BIND_EMPTY;
-  long long kk = 0;
-  if (w.tokens == 0) {
-    c = sc.eps_scale;
-    d = sc.eps_scale;
-  } else {
-    thr = is_f16 ? h2f(prefix) : __uint_as_float(prefix);
-    c_tau = sc.qmax_tau * w.sigma;            // q_max * tau * sigma
-    c_zr = sc.two_qmax * thr;                 // 2 * q_max * Q_zr(|x|)
-    c = w.c_base;
-    bind = TDQ_BIND_BASE;
-    if ((sc.flags & TDQ_FLAG_C1) && c_tau < c) { c = c_tau; bind = TDQ_BIND_C1; }
-    if ((sc.flags & TDQ_FLAG_C2) && c_zr < c) { c = c_zr; bind = TDQ_BIND_C2; }
-    if (!(c > sc.eps_scale)) { c = sc.eps_scale; bind = TDQ_BIND_EPS; }
-    d = c / sc.qmax;
-    d = d > sc.eps_scale ? d : sc.eps_scale;
-    // original rank (k_rem has been consumed): recompute for the record
-    const double n = (double)w.n;
-    kk = (long long)ceil(sc.zr * n);
-    kk = kk < 1 ? 1 : (kk > w.n ? w.n : kk);
-  }
-  clip[idx] = c;
-  scale[idx] = d;
-  if (stats) {
-    tdq_group_stats s;
-    s.n = w.n; s.k = kk; s.c_base = w.c_base; s.sigma = w.sigma; s.thr = thr;
-    s.c_tau = c_tau; s.c_zr = c_zr; s.clip = c; s.scale = d; s.bind = bind;
-    stats[idx] = s;
-  }
+  project_store(idx, w, prefix, is_f16 != 0, sc, clip, scale, stats);
 }
 
 hipError_t launch_select(unsigned* hist_level, int B, int G, int, int bits, bool last, tdq_dtype dt,
                          const Scalars& sc, GroupWork* grp, float* clip, float* scale,
                          tdq_group_stats* stats, const unsigned* img_flag, unsigned* status,
-                         hipStream_t st) {
+                         const unsigned* missed, hipStream_t st) {
   hipLaunchKernelGGL(k_select, dim3(B * G), dim3(64), 0, st, hist_level, bits, last ? 1 : 0,
-                     dt == TDQ_F16 ? 1 : 0, sc, grp, clip, scale, stats, img_flag, B, status);
+                     dt == TDQ_F16 ? 1 : 0, sc, grp, clip, scale, stats, img_flag, B, status,
+                     missed);
   return hipGetLastError();
 }
 

@@ -19,15 +19,6 @@ LevelPlan make_level_plan(tdq_dtype dt, int G) {
   if (max_bits < 1) max_bits = 1;
   int n = (lp.key_bits + max_bits - 1) / max_bits;
   lp.n_levels = n;
-  if (const char* e = getenv("TDQ_HIST_BITS0")) {     // experiment: force the first level's width
-    const int b0 = atoi(e);
-    if (dt == TDQ_F16 && b0 >= 6 && b0 <= 11 && (G << b0) <= 32768 && 15 - b0 <= max_bits) {
-      lp.n_levels = 2;
-      lp.bits[0] = b0; lp.shift[0] = 15 - b0;
-      lp.bits[1] = 15 - b0; lp.shift[1] = 0;
-      return lp;
-    }
-  }
   int left = lp.key_bits;
   for (int l = 0; l < n; ++l) {
     const int levels_left = n - l;
@@ -37,6 +28,12 @@ LevelPlan make_level_plan(tdq_dtype dt, int G) {
     lp.shift[l] = left;
   }
   return lp;
+}
+
+int bracket_bins(int G) {
+  int w = 2048;
+  while (w >= 64 && (long long)G * w > kBracketLdsWords) w >>= 1;
+  return w >= 64 ? w : 0;
 }
 
 WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {
@@ -55,6 +52,9 @@ WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {
     w.hist_level[l] = off;
     off += BG * ((size_t)1 << lp.bits[l]) * sizeof(unsigned);   // levels are contiguous
   }
+  off = align256(off);
+  w.br = off;       off = align256(off + BG * sizeof(Bracket));
+  w.bhist = off;    off = align256(off + BG * (size_t)bracket_bins(G) * sizeof(unsigned));
   w.total = align256(off);
   return w;
 }
@@ -63,7 +63,7 @@ static int check_params(const tdq_params* p) {
   if (!p) return TDQ_ERR_NULL;
   if (p->n_groups < 1 || p->n_groups > TDQ_MAX_GROUPS) return TDQ_ERR_PARAM;
   if (p->act_bits != 4) return p->act_bits == 8 ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
-  if (p->flags & ~(TDQ_FLAG_C1 | TDQ_FLAG_C2)) return TDQ_ERR_PARAM;
+  if (p->flags & ~(TDQ_FLAG_C1 | TDQ_FLAG_C2 | TDQ_FLAG_EXACT_SELECT)) return TDQ_ERR_PARAM;
   if (!(p->tau > 0.0) || !isfinite(p->tau)) return TDQ_ERR_PARAM;
   if (!(p->zr > 0.0 && p->zr < 1.0)) return TDQ_ERR_PARAM;
   if (!(p->eps_scale > 0.f) || !(p->eps_std >= 0.f)) return TDQ_ERR_PARAM;
@@ -167,15 +167,38 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
   const int M = B * T;
 
   if (launch_token_stats(X, dt, M, C, ld_x, r, s1, s2, st) != hipSuccess) return TDQ_ERR_HIP;
-  if (launch_assign(r, s1, s2, B, T, C, G, sc, group_id, grp, hist, img_flag, lp, st) != hipSuccess)
+
+  if (launch_assign(r, s1, s2, B, T, C, G, sc, group_id, grp, hist, img_flag, status, lp, st) !=
+      hipSuccess)
     return TDQ_ERR_HIP;
+
+  // binary16 input: one sweep resolves the rank of (nearly) every set exactly; the
+  // radix levels below then run restricted to the sets it missed, and return at once
+  // when there are none
+  const int W = bracket_bins(G);
+  const unsigned* missed = nullptr;
+  if (dt == TDQ_F16 && W > 0 && (long long)T * C < (1ll << 32)) {
+    Bracket* br = reinterpret_cast<Bracket*>(ws + wl.br);
+    unsigned* bhist = reinterpret_cast<unsigned*>(ws + wl.bhist);
+    const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
+    if (!exact_only) {
+      if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, grp, br, bhist, st) != hipSuccess)
+        return TDQ_ERR_HIP;
+      if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
+        return TDQ_ERR_HIP;
+    }
+    if (launch_bracket_select(bhist, B, G, W, exact_only, sc, grp, br, clip, scale, stats,
+                              img_flag, status, st) != hipSuccess)
+      return TDQ_ERR_HIP;
+    missed = status + 1;
+  }
   for (int l = 0; l < lp.n_levels; ++l) {
     unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
-    if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], st) !=
-        hipSuccess)
+    if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], missed,
+                    st) != hipSuccess)
       return TDQ_ERR_HIP;
     if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
-                      scale, stats, img_flag, status, st) != hipSuccess)
+                      scale, stats, img_flag, status, missed, st) != hipSuccess)
       return TDQ_ERR_HIP;
   }
   return TDQ_OK;

@@ -1,0 +1,168 @@
+// Device-side helpers shared by the activation kernels of libtdq: element access
+// for the two input types, DPP reductions over groups of lanes, and the DCRP
+// projection that turns a group's statistics into its clip radius and step.
+#pragma once
+
+#include "tdq_internal.hpp"
+
+namespace tdq {
+
+// ---------------------------------------------------------------------------
+// element access
+// ---------------------------------------------------------------------------
+typedef unsigned short u16;
+typedef unsigned int u32;
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float h2f(u32 bits16) {
+  return (float)__builtin_bit_cast(_Float16, (u16)bits16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<u16> {                 // fp16 stored as raw bits
+  static constexpr int V = 8;      // elements per 16-byte load
+  static constexpr u32 kNonFinite = 0x7C00u;
+  __device__ static __forceinline__ u32 key(u16 x) { return x & 0x7FFFu; }
+  __device__ static __forceinline__ float val(u16 x) { return h2f(x); }
+  __device__ static __forceinline__ float key_to_float(u32 k) { return h2f(k); }
+  __device__ static __forceinline__ void unpack(const uint4& q, u16 out[8]) {
+    out[0] = q.x & 0xFFFF; out[1] = q.x >> 16; out[2] = q.y & 0xFFFF; out[3] = q.y >> 16;
+    out[4] = q.z & 0xFFFF; out[5] = q.z >> 16; out[6] = q.w & 0xFFFF; out[7] = q.w >> 16;
+  }
+};
+template <>
+struct Elem<float> {
+  static constexpr int V = 4;
+  static constexpr u32 kNonFinite = 0x7F800000u;
+  __device__ static __forceinline__ u32 key(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+  __device__ static __forceinline__ float val(float x) { return x; }
+  __device__ static __forceinline__ float key_to_float(u32 k) { return __uint_as_float(k); }
+  __device__ static __forceinline__ void unpack(const uint4& q, float out[4]) {
+    out[0] = __uint_as_float(q.x); out[1] = __uint_as_float(q.y);
+    out[2] = __uint_as_float(q.z); out[3] = __uint_as_float(q.w);
+  }
+};
+
+// Rows are shared out to groups of L adjacent lanes (L a power of two <= 64), so a
+// 64-wide wavefront covers 64/L rows; each lane reads 16-byte pieces of its row.
+inline int lanes_per_row(int C, int V) {
+  int nvec = (C + V - 1) / V;
+  int L = 1;
+  while (L < nvec && L < 64) L <<= 1;
+  return L;
+}
+
+// Reductions over groups of L adjacent lanes (L a power of two <= 64) with DPP
+// row shifts and row broadcasts, i.e. at vector-ALU speed instead of one LDS round
+// trip per step.  The result is valid in the LAST lane of every group
+// (lane % L == L - 1); the other lanes hold partial windows.
+//   steps 1, 2, 4, 8: row_shr inside rows of 16 lanes (zero shifted in),
+//   16: row_bcast15 into rows 1 and 3,  32: row_bcast31 into rows 2 and 3.
+#define TDQ_DPP_ROW_SHR(n) (0x110 + (n))
+#define TDQ_DPP_ROW_BCAST15 0x142
+#define TDQ_DPP_ROW_BCAST31 0x143
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ u32 dpp_u32(u32 v) {
+  return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+  const u32 lo = dpp_u32<CTRL, ROW_MASK>((u32)b), hi = dpp_u32<CTRL, ROW_MASK>((u32)(b >> 32));
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+template <int L>
+__device__ __forceinline__ double group_sum_f64(double v) {
+  if (L > 1) v += dpp_f64<TDQ_DPP_ROW_SHR(1), 0xF>(v);
+  if (L > 2) v += dpp_f64<TDQ_DPP_ROW_SHR(2), 0xF>(v);
+  if (L > 4) v += dpp_f64<TDQ_DPP_ROW_SHR(4), 0xF>(v);
+  if (L > 8) v += dpp_f64<TDQ_DPP_ROW_SHR(8), 0xF>(v);
+  if (L > 16) v += dpp_f64<TDQ_DPP_ROW_BCAST15, 0xA>(v);
+  if (L > 32) v += dpp_f64<TDQ_DPP_ROW_BCAST31, 0xC>(v);
+  return v;
+}
+template <int L>
+__device__ __forceinline__ u32 group_max_u32(u32 v) {
+  u32 o;
+  if (L > 1) { o = dpp_u32<TDQ_DPP_ROW_SHR(1), 0xF>(v); v = o > v ? o : v; }
+  if (L > 2) { o = dpp_u32<TDQ_DPP_ROW_SHR(2), 0xF>(v); v = o > v ? o : v; }
+  if (L > 4) { o = dpp_u32<TDQ_DPP_ROW_SHR(4), 0xF>(v); v = o > v ? o : v; }
+  if (L > 8) { o = dpp_u32<TDQ_DPP_ROW_SHR(8), 0xF>(v); v = o > v ? o : v; }
+  if (L > 16) { o = dpp_u32<TDQ_DPP_ROW_BCAST15, 0xA>(v); v = o > v ? o : v; }
+  if (L > 32) { o = dpp_u32<TDQ_DPP_ROW_BCAST31, 0xC>(v); v = o > v ? o : v; }
+  return v;
+}
+
+// xor-butterfly forms (every lane gets the result), used off the hot paths
+template <int L, typename F>
+__device__ __forceinline__ F xor_reduce_sum(F v) {
+#pragma unroll
+  for (int m = L >> 1; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+template <int L>
+__device__ __forceinline__ u32 xor_reduce_max(u32 v) {
+#pragma unroll
+  for (int m = L >> 1; m > 0; m >>= 1) {
+    u32 o = (u32)__shfl_xor((int)v, m, 64);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+template <int L>
+__device__ __forceinline__ u32 group_sum_u32(u32 v) {
+  if (L > 1) v += dpp_u32<TDQ_DPP_ROW_SHR(1), 0xF>(v);
+  if (L > 2) v += dpp_u32<TDQ_DPP_ROW_SHR(2), 0xF>(v);
+  if (L > 4) v += dpp_u32<TDQ_DPP_ROW_SHR(4), 0xF>(v);
+  if (L > 8) v += dpp_u32<TDQ_DPP_ROW_SHR(8), 0xF>(v);
+  if (L > 16) v += dpp_u32<TDQ_DPP_ROW_BCAST15, 0xA>(v);
+  if (L > 32) v += dpp_u32<TDQ_DPP_ROW_BCAST31, 0xC>(v);
+  return v;
+}
+
+// DCRP projection of one (image, token set), in binary32 (Eq. dcrp with the eps
+// floors of the supplementary numerical conventions): key is the magnitude bit
+// pattern of the k-th smallest |x| of the set.  Called by one lane per set.
+__device__ inline void project_store(int idx, const GroupWork& w, u32 key, bool is_f16,
+                                     const Scalars& sc, float* __restrict__ clip,
+                                     float* __restrict__ scale,
+                                     tdq_group_stats* __restrict__ stats) {
+  float thr = 0.f, c_tau = 0.f, c_zr = 0.f, c, d;
+  u32 bind = TDQ_BIND_EMPTY;
+  long long kk = 0;
+  if (w.tokens == 0) {
+    c = sc.eps_scale;
+    d = sc.eps_scale;
+  } else {
+    thr = is_f16 ? h2f(key) : __uint_as_float(key);
+    c_tau = sc.qmax_tau * w.sigma;            // q_max * tau * sigma
+    c_zr = sc.two_qmax * thr;                 // 2 * q_max * Q_zr(|x|)
+    c = w.c_base;
+    bind = TDQ_BIND_BASE;
+    if ((sc.flags & TDQ_FLAG_C1) && c_tau < c) { c = c_tau; bind = TDQ_BIND_C1; }
+    if ((sc.flags & TDQ_FLAG_C2) && c_zr < c) { c = c_zr; bind = TDQ_BIND_C2; }
+    if (!(c > sc.eps_scale)) { c = sc.eps_scale; bind = TDQ_BIND_EPS; }
+    d = c / sc.qmax;
+    d = d > sc.eps_scale ? d : sc.eps_scale;
+    // original rank (k_rem has been consumed): recompute for the record
+    const double n = (double)w.n;
+    kk = (long long)ceil(sc.zr * n);
+    kk = kk < 1 ? 1 : (kk > w.n ? w.n : kk);
+  }
+  clip[idx] = c;
+  scale[idx] = d;
+  if (stats) {
+    tdq_group_stats s;
+    s.n = w.n; s.k = kk; s.c_base = w.c_base; s.sigma = w.sigma; s.thr = thr;
+    s.c_tau = c_tau; s.c_zr = c_zr; s.clip = c; s.scale = d; s.bind = bind;
+    stats[idx] = s;
+  }
+}
+
+}  // namespace tdq

@@ -27,6 +27,23 @@ struct GroupWork {
   float sigma;          // population std + eps_std
 };
 
+// Key interval [lo, lo + width) that a sample says holds the k-th smallest
+// magnitude key of an (image, token set), and what the sweep counted for it.
+struct Bracket {
+  unsigned lo;       // first key of the interval
+  unsigned width;    // keys in the interval (one histogram bin each), 0 = nothing to count
+  unsigned below;    // elements of the set with key < lo
+  unsigned pad;
+};
+constexpr int kBracketLdsWords = 16384;   // 64 KiB of LDS histogram per workgroup
+// GroupWork::prefix of a set whose rank the single-sweep select has resolved (and
+// projected); the radix levels that follow skip such sets.
+constexpr unsigned kResolved = 0xFFFFFFFFu;
+
+// Bins per set of the bracket histogram (0 = this many sets do not fit: use the
+// multi-level radix select instead).
+int bracket_bins(int G);
+
 // How the magnitude key (15 bits for fp16, 31 for fp32) is split into radix levels.
 struct LevelPlan {
   int n_levels;
@@ -39,7 +56,8 @@ LevelPlan make_level_plan(tdq_dtype dt, int G);
 
 // Byte offsets of the pieces of the calibration workspace (all 256-aligned).
 struct WorkspaceLayout {
-  size_t status;     // uint32[64]; word 0 is the device status word
+  size_t status;     // uint32[64]; word 0 = device status word, word 1 = sets whose rank the
+                     // last binary16 calibration's sampled key interval missed
   size_t img_flag;   // uint32[B]     per-image non-finite flag
   size_t r;          // float[M]      per-token range
   size_t s1;         // double[M]     per-token sum x
@@ -47,6 +65,8 @@ struct WorkspaceLayout {
   size_t grp;        // GroupWork[B*G]
   size_t hist;       // uint32 [levels][B*G][1 << bits[level]]
   size_t hist_level[kMaxLevels];   // offset of each level inside the workspace
+  size_t br;         // Bracket[B*G]
+  size_t bhist;      // uint32 [B*G][bracket_bins(G)]
   size_t total;
 };
 
@@ -67,14 +87,26 @@ hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long lo
                               float* r, double* s1, double* s2, hipStream_t st);
 hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int C,
                          int G, const Scalars& sc, int* gid, GroupWork* grp, unsigned* hist,
-                         unsigned* img_flag, const LevelPlan& lp, hipStream_t st);
+                         unsigned* img_flag, unsigned* status, const LevelPlan& lp, hipStream_t st);
+// `missed` = device counter of sets still to resolve, or null.  With a counter the
+// kernels return at once when it is zero and skip every set marked kResolved.
 hipError_t launch_hist(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                        const int* gid, const GroupWork* grp, unsigned* hist_level, int shift,
-                       int bits, hipStream_t st);
+                       int bits, const unsigned* missed, hipStream_t st);
 hipError_t launch_select(unsigned* hist_level, int B, int G, int shift, int bits, bool last,
                          tdq_dtype dt, const Scalars& sc, GroupWork* grp, float* clip,
                          float* scale, tdq_group_stats* stats, const unsigned* img_flag,
-                         unsigned* status, hipStream_t st);
+                         unsigned* status, const unsigned* missed, hipStream_t st);
+// single-sweep rank select for binary16 input
+hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
+                          const int* gid, const GroupWork* grp, Bracket* br, unsigned* bhist,
+                          hipStream_t st);
+hipError_t launch_bracket_hist(const void* X, int B, int T, int C, long long ld, int G, int W,
+                               const int* gid, Bracket* br, unsigned* bhist, hipStream_t st);
+hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,
+                                 const Scalars& sc, GroupWork* grp, const Bracket* br, float* clip,
+                                 float* scale, tdq_group_stats* stats, const unsigned* img_flag,
+                                 unsigned* status, hipStream_t st);
 hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                            const int* gid, const float* clip, const float* scale, uint8_t* Q,
                            long long ld_q, hipStream_t st);

@@ -1,0 +1,379 @@
+// Rank select of the zr quantile for binary16 activations in ONE sweep of X
+// (constraint C2 of DCRP, Eq. zr_constraint: the k-th smallest |x| of every
+// (image, token set), k = ceil(zr n), Supp. "Quantile Implementation").
+//
+// The magnitude key of a binary16 value has 15 bits.  A radix select over LDS
+// histograms needs two sweeps of X for that many bits.  Here a small sample of
+// every set first says where to look:
+//
+//   k_bracket         one workgroup per set reads up to 16 Ki sampled elements into
+//                     registers and finds, by bisection on the key bits, the sample
+//                     order statistic whose sample rank corresponds to k.  The key
+//                     interval [lo, lo + W) centred on it (W = as many one-key bins as
+//                     the LDS histogram has per set) holds the true answer unless the
+//                     sample is off by more than W/2 keys.
+//   k_bracket_hist    one sweep of X: per set, the number of keys below lo and an LDS
+//                     histogram, one bin per key, of the keys inside the interval.
+//   k_bracket_select  one wavefront per set: if below < k <= below + inside, the
+//                     answer is the bin where the running count reaches k - below --
+//                     the exact k-th smallest, no matter how the interval was chosen --
+//                     and the set is projected and marked resolved.  Otherwise the set
+//                     is counted as missed, and the host-side sequence that follows
+//                     (the multi-level radix select, restricted to missed sets, whose
+//                     kernels return at once when the count is zero) resolves it.
+//
+// The result is therefore always the exact order statistic; the sample only decides
+// which of the two routes computes it, i.e. how long it takes.
+#include "tdq_device.hpp"
+
+namespace tdq {
+
+constexpr int kSampleThreads = 256;                             // one wavefront per SIMD
+constexpr int kSampleWaves = kSampleThreads / 64;
+constexpr int kSamplePerThread = 64;
+constexpr int kRunLen = 32;                                     // channels per run (64 bytes)
+constexpr int kSampleMax = kSampleThreads * kSamplePerThread;   // 16 Ki keys per set
+constexpr int kSampleRuns = kSampleMax / kRunLen;               // 512 runs
+constexpr int kSampleTokens = kSampleRuns;                      // at most one run per token
+constexpr int kSampleBits = 10;                                 // key bits the bisection resolves
+constexpr int kSweepThreads = 1024;
+
+// ---------------------------------------------------------------------------
+// k_bracket
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kSampleThreads) void k_bracket(
+    const u16* __restrict__ X, long long ld, int T, int C, int G, int W,
+    const int* __restrict__ gid, const GroupWork* __restrict__ grp, Bracket* __restrict__ br,
+    u32* __restrict__ bhist) {
+  __shared__ int sel[kSampleTokens];                 // drawn token of every stratum
+  __shared__ long long run_base[kSampleRuns];        // element offset of every run's first channel
+  __shared__ int run_len[kSampleRuns];               // channels of the run (<= kRunLen)
+  __shared__ u32 wtot[kSampleWaves];
+  const int idx = blockIdx.x;
+  const int b = idx / G, j = idx - b * G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const GroupWork w = grp[idx];
+
+  // the sweep adds into this set's histogram and counter: clear them here
+  for (int i = tid; i < W; i += kSampleThreads) bhist[(size_t)idx * W + i] = 0;
+  if (w.tokens == 0) {
+    if (tid == 0) {
+      Bracket e;
+      e.lo = 0; e.width = 0; e.below = 0; e.pad = 0;
+      br[idx] = e;
+    }
+    return;
+  }
+
+  // Sample geometry.  The set's tokens, in index order, are cut into strata of
+  // `stride` tokens (at most kSampleTokens strata) and one token is drawn from each
+  // at a hashed position: a regular stride would alias with any period the token
+  // sequence has (image rows).  Of each drawn token `rpt` runs of kRunLen consecutive
+  // channels are read, the first at a hashed offset, so that all channels are
+  // represented; a row that fits is read whole.
+  const int tokens = (int)w.tokens;
+  const int stride = (tokens + kSampleTokens - 1) / kSampleTokens;
+  const int n_sel = (tokens + stride - 1) / stride;         // <= kSampleTokens
+  const int row_runs = (C + kRunLen - 1) / kRunLen;
+  int rpt = kSampleRuns / n_sel;                            // runs per drawn token, >= 1
+  rpt = rpt < row_runs ? rpt : row_runs;
+  const int cw = rpt == row_runs ? C : rpt * kRunLen;       // channels read per drawn token
+  const int n_runs = n_sel * rpt;                           // <= kSampleRuns
+  const long long m = (long long)n_sel * cw;                // sample size, <= kSampleMax
+
+  // rank of every token inside its set -> the drawn tokens' indices.  The set ids
+  // are fetched kRankBatch rounds at a time so that the loads' latencies overlap.
+  constexpr int kRankBatch = 8;
+  const int* gb = gid + (long long)b * T;
+  u32 base = 0;
+  for (int t0 = 0; t0 < T; t0 += kRankBatch * kSampleThreads) {
+    int gv[kRankBatch];
+#pragma unroll
+    for (int u = 0; u < kRankBatch; ++u) {
+      const int t = t0 + u * kSampleThreads + tid;
+      gv[u] = t < T ? gb[t] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < kRankBatch; ++u) {
+      if (t0 + u * kSampleThreads >= T) break;               // uniform
+      const int t = t0 + u * kSampleThreads + tid;
+      const bool match = gv[u] == j;
+      const unsigned long long mask = __ballot(match);
+      const u32 within = (u32)__popcll(mask & ((1ull << lane) - 1ull));
+      if (lane == 0) wtot[wave] = (u32)__popcll(mask);
+      __syncthreads();
+      u32 before = 0, total = 0;
+#pragma unroll
+      for (int w2 = 0; w2 < kSampleWaves; ++w2) {
+        const u32 v = wtot[w2];
+        before += w2 < wave ? v : 0u;
+        total += v;
+      }
+      if (match) {
+        const u32 rank = base + before + within;
+        const u32 stratum = rank / (u32)stride, first = stratum * (u32)stride;
+        const u32 len = (u32)tokens - first < (u32)stride ? (u32)tokens - first : (u32)stride;
+        const u32 pick =
+            first + (((stratum + 1u) * 2246822519u + (u32)idx * 3266489917u) >> 12) % len;
+        if (rank == pick) sel[stratum] = t;
+      }
+      base += total;
+      __syncthreads();
+    }
+  }
+  // table of runs, so that the load loop below has no division in it
+  for (int q = tid; q < kSampleRuns; q += kSampleThreads) {
+    long long rb = 0;
+    int rl = 0;
+    if (q < n_runs) {
+      const int slot = q / rpt, run = q - slot * rpt;
+      const int t = sel[slot];
+      const u32 off = ((u32)t * 2654435761u >> 8) % (u32)(C - cw + 1);
+      rb = ((long long)b * T + t) * ld + off + run * kRunLen;
+      rl = cw - run * kRunLen;
+      rl = rl < kRunLen ? rl : kRunLen;
+    } else {
+      rb = ((long long)b * T + sel[0]) * ld;          // a valid address; the key is discarded
+    }
+    run_base[q] = rb;
+    run_len[q] = rl;
+  }
+  __syncthreads();
+
+  // The sample, in registers: element e of lane l of wavefront w is channel l % 32
+  // of run 8 e + 2 w + l / 32.  Loads are issued unconditionally (clamped channel)
+  // so that they overlap.
+  u32 key[kSamplePerThread];
+  const int half = lane >> 5, cl = lane & 31;
+#pragma unroll
+  for (int e = 0; e < kSamplePerThread; ++e) {
+    const int q = e * (2 * kSampleWaves) + 2 * wave + half;
+    const int rl = run_len[q];
+    const int ch = cl < rl ? cl : (rl > 0 ? rl - 1 : 0);
+    const u32 x = X[run_base[q] + ch];
+    key[e] = cl < rl ? (x & 0x7FFFu) : 0xFFFFu;              // filler: above every candidate
+  }
+
+  // Sample rank that corresponds to rank k of the set, and (the top kSampleBits bits
+  // of) that order statistic: the r-th smallest key is the largest v with
+  // #{key < v} < r, built bit by bit.  The low bits do not matter to the interval.
+  const double n = (double)w.n, kd = (double)w.k_rem;
+  long long r = (long long)(kd / n * (double)m + 0.5);
+  r = r < 1 ? 1 : (r > m ? m : r);
+  u32 v = 0;
+  for (int bit = 14; bit > 14 - kSampleBits; --bit) {
+    const u32 c = v | (1u << bit);
+    u32 cnt = 0;
+#pragma unroll
+    for (int e = 0; e < kSamplePerThread; ++e) cnt += key[e] < c ? 1u : 0u;
+    cnt = group_sum_u32<64>(cnt);
+    __syncthreads();                       // the previous pass has been read by everyone
+    if (lane == 63) wtot[wave] = cnt;
+    __syncthreads();
+    u32 tot = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < kSampleWaves; ++w2) tot += wtot[w2];
+    if ((long long)tot < r) v = c;
+  }
+
+  if (tid == 0) {
+    // v <= estimate < v + 2^(15 - kSampleBits): centre the interval on the middle
+    const u32 mid = v + (1u << (14 - kSampleBits));
+    Bracket e;
+    e.below = 0; e.pad = 0;
+    e.lo = mid > (u32)W / 2 ? mid - (u32)W / 2 : 0u;
+    e.width = (u32)W;
+    br[idx] = e;
+  }
+}
+
+hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
+                          const int* gid, const GroupWork* grp, Bracket* br, unsigned* bhist,
+                          hipStream_t st) {
+  hipLaunchKernelGGL(k_bracket, dim3(B * G), dim3(kSampleThreads), 0, st,
+                     static_cast<const u16*>(X), ld, T, C, G, W, gid, grp, br, bhist);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// k_bracket_hist: the one sweep
+// ---------------------------------------------------------------------------
+typedef short s2v __attribute__((ext_vector_type(2)));
+
+template <int L>
+__global__ __launch_bounds__(kSweepThreads) void k_bracket_hist(
+    const u16* __restrict__ X, long long ld, int T_, int C, int G, int W, int vec_ok,
+    const int* __restrict__ gid, Bracket* __restrict__ br, u32* __restrict__ bhist,
+    int rows_per_block) {
+  extern __shared__ u32 lds[];                    // [G][W] bins, then per set: below, lo, width
+  // walks X backwards: it runs right after the forward statistics sweep, so the end of
+  // X is what the last-level cache still holds
+  const int b = (int)(gridDim.y - 1 - blockIdx.y);
+  const int chunk = (int)(gridDim.x - 1 - blockIdx.x);
+  const int tid = threadIdx.x;
+  const int nwords = G * W;
+  u32* s_below = lds + nwords;
+  u32* s_lo = s_below + G;
+  u32* s_width = s_lo + G;
+  for (int i = tid; i < nwords + G; i += kSweepThreads) lds[i] = 0;
+  for (int g = tid; g < G; g += kSweepThreads) {
+    const Bracket e = br[(long long)b * G + g];
+    s_lo[g] = e.lo;
+    s_width[g] = e.width;
+  }
+  __syncthreads();
+
+  const int row0 = chunk * rows_per_block;
+  int nrows = T_ - row0;
+  nrows = nrows < rows_per_block ? nrows : rows_per_block;
+  constexpr int SLOTS = kSweepThreads / L;
+  const int slot = tid / L, lr = tid % L;
+  const int nvec = vec_ok ? C / 8 : 0;
+  for (int rr = slot; rr < nrows; rr += SLOTS) {
+    const long long row = (long long)b * T_ + row0 + rr;
+    const int g = gid[row];
+    const u32 lo = s_lo[g], width = s_width[g];
+    const u32 lo2 = lo | (lo << 16);
+    u32* h = lds + g * W;
+    const u16* xp = X + row * ld;
+    u32 below = 0;
+#pragma unroll 2
+    for (int v = lr; v < nvec; v += L) {
+      const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * 8);
+      const u32 wd[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // both halves at once: keys and lo are below 2^15, so the 16-bit differences
+        // cannot overflow and their sign bits say "key < lo"
+        const s2v d = __builtin_bit_cast(s2v, wd[i] & 0x7FFF7FFFu) - __builtin_bit_cast(s2v, lo2);
+        const u32 d2 = __builtin_bit_cast(u32, d);
+        below += (u32)__builtin_popcount(d2 & 0x80008000u);
+        const u32 dl = d2 & 0xFFFFu, dh = d2 >> 16;       // negative ones are >= 2^15 > width
+        if (dl < width) atomicAdd(&h[dl], 1u);
+        if (dh < width) atomicAdd(&h[dh], 1u);
+      }
+    }
+    for (int c = nvec * 8 + lr; c < C; c += L) {
+      const u32 k = xp[c] & 0x7FFFu;
+      below += k < lo ? 1u : 0u;
+      const u32 d = k - lo;
+      if (k >= lo && d < width) atomicAdd(&h[d], 1u);
+    }
+    below = group_sum_u32<L>(below);                       // total in the row's last lane
+    if (lr == L - 1 && below) atomicAdd(&s_below[g], below);
+  }
+  __syncthreads();
+  u32* gh = bhist + (size_t)b * G * W;
+  for (int i = tid; i < nwords; i += kSweepThreads) {
+    const u32 v = lds[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+  for (int g = tid; g < G; g += kSweepThreads) {
+    const u32 v = s_below[g];
+    if (v) atomicAdd(&br[(long long)b * G + g].below, v);
+  }
+}
+
+hipError_t launch_bracket_hist(const void* Xv, int B, int T_, int C, long long ld, int G, int W,
+                               const int* gid, Bracket* br, unsigned* bhist, hipStream_t st) {
+  const u16* X = static_cast<const u16*>(Xv);
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0) ? 1 : 0;
+  const int L = lanes_per_row(C, 8);
+  // enough workgroups to fill 256 CUs several times over, but at least ~64 Ki elements
+  // each so the flush of the G * W bins stays small beside the sweep
+  long long rows_min = (65536 + C - 1) / C;
+  long long target_blocks = 1024 / (B > 0 ? B : 1);
+  if (target_blocks < 1) target_blocks = 1;
+  long long rpb = (T_ + target_blocks - 1) / target_blocks;
+  if (rpb < rows_min) rpb = rows_min;
+  if (rpb > T_) rpb = T_;
+  const unsigned chunks = (unsigned)((T_ + rpb - 1) / rpb);
+  const size_t lds_bytes = ((size_t)G * W + 3 * (size_t)G) * sizeof(u32);
+#define TDQ_BH(LL)                                                                              \
+  case LL:                                                                                      \
+    if (lds_bytes > 65536)                                                                      \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bracket_hist<LL>),             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);    \
+    hipLaunchKernelGGL((k_bracket_hist<LL>), dim3(chunks, B), dim3(kSweepThreads), lds_bytes,   \
+                       st, X, ld, T_, C, G, W, vec_ok, gid, br, bhist, (int)rpb);               \
+    break;
+  switch (L) { TDQ_BH(1) TDQ_BH(2) TDQ_BH(4) TDQ_BH(8) TDQ_BH(16) TDQ_BH(32) TDQ_BH(64) }
+#undef TDQ_BH
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// k_bracket_select
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_bracket_select(
+    const u32* __restrict__ bhist, int W, int force_miss, Scalars sc, GroupWork* __restrict__ grp,
+    const Bracket* __restrict__ br, float* __restrict__ clip, float* __restrict__ scale,
+    tdq_group_stats* __restrict__ stats, const u32* __restrict__ img_flag, int B,
+    u32* __restrict__ status) {
+  const int idx = blockIdx.x;
+  const int lane = threadIdx.x;
+  if (idx == 0) {   // fold the per-image flags into the status word
+    u32 f = 0;
+    for (int b = lane; b < B; b += 64) f |= img_flag[b];
+    const unsigned long long any = __ballot(f != 0);
+    if (lane == 0) status[0] = any ? TDQ_DEV_NONFINITE : 0u;
+  }
+  const GroupWork w = grp[idx];
+  if (w.tokens == 0) {
+    if (lane == 0) {
+      project_store(idx, w, 0u, true, sc, clip, scale, stats);
+      grp[idx].prefix = kResolved;
+    }
+    return;
+  }
+  bool ok = false;
+  unsigned long long need = 0, mine = 0, incl = 0;
+  const u32* h = bhist + (size_t)idx * W;
+  const int per = W / 64;                     // W is a multiple of 64
+  const int first = lane * per;
+  Bracket e;
+  e.lo = 0; e.width = 0; e.below = 0; e.pad = 0;
+  if (!force_miss) {
+    e = br[idx];
+    const unsigned long long k = (unsigned long long)w.k_rem;
+    for (int i = 0; i < per; ++i) mine += h[first + i];
+    incl = mine;                              // inclusive scan over lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const unsigned long long o = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += o;
+    }
+    const unsigned long long inside = __shfl(incl, 63, 64);
+    ok = k > e.below && k - e.below <= inside;
+    need = k - e.below;
+  }
+  if (!ok) {                                  // wavefront-uniform
+    if (lane == 0) atomicAdd(&status[1], 1u); // prefix stays 0, k_rem = k: radix levels take over
+    return;
+  }
+  const unsigned long long hit = __ballot(incl >= need);
+  const int src = __ffsll((long long)hit) - 1;          // hit != 0 because need <= inside
+  if (lane == src) {
+    unsigned long long cum = incl - mine;
+    int i = 0;
+    for (; i < per - 1; ++i) {
+      const unsigned long long c = h[first + i];
+      if (cum + c >= need) break;
+      cum += c;
+    }
+    project_store(idx, w, e.lo + (u32)(first + i), true, sc, clip, scale, stats);
+    grp[idx].prefix = kResolved;
+  }
+}
+
+hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,
+                                 const Scalars& sc, GroupWork* grp, const Bracket* br, float* clip,
+                                 float* scale, tdq_group_stats* stats, const unsigned* img_flag,
+                                 unsigned* status, hipStream_t st) {
+  hipLaunchKernelGGL(k_bracket_select, dim3(B * G), dim3(64), 0, st, bhist, W, force_miss ? 1 : 0,
+                     sc, grp, br, clip, scale, stats, img_flag, B, status);
+  return hipGetLastError();
+}
+
+}  // namespace tdq

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(HERE, "libtdq.so")
 
 TDQ_F16, TDQ_F32 = 0, 1
 FLAG_C1, FLAG_C2 = 1, 2
+FLAG_EXACT_SELECT = 256     # validation switch: rank select by the radix levels only
 DEV_NONFINITE = 1
 BIND_NAMES = ("base", "C1", "C2", "eps", "empty")
 
@@ -166,6 +167,12 @@ def tdq_calibrate_groups(X: torch.Tensor, p: Params, workspace: Optional[torch.T
 def device_status(workspace: torch.Tensor) -> int:
     """Status word left by the last tdq_calibrate_groups (synchronises)."""
     return int(workspace[:4].view(torch.int32).item())
+
+
+def exact_select_sets(workspace: torch.Tensor) -> int:
+    """How many token sets the last binary16 tdq_calibrate_groups resolved by the
+    radix levels because the sampled key interval missed their rank (synchronises)."""
+    return int(workspace[4:8].view(torch.int32).item())
 
 
 def stats_to_numpy(stats: torch.Tensor):

@@ -22,7 +22,7 @@ def dev():
 
 
 def oracle_params(p: tdq.Params) -> O.Params:
-    return O.Params(n_groups=p.n_groups, flags=p.flags, tau=p.tau, zr=p.zr)
+    return O.Params(n_groups=p.n_groups, flags=p.flags & 3, tau=p.tau, zr=p.zr)
 
 
 def gpu_calibrate(X: np.ndarray, p: tdq.Params, ld_pad: int = 0):
@@ -32,7 +32,8 @@ def gpu_calibrate(X: np.ndarray, p: tdq.Params, ld_pad: int = 0):
     torch.cuda.synchronize()
     return dict(Xd=Xd, gid_d=gid, clip_d=clip, scale_d=scale, gid=gid.cpu().numpy(),
                 clip=clip.cpu().numpy(), scale=scale.cpu().numpy(),
-                stats=tdq.stats_to_numpy(stats), status=tdq.device_status(ws))
+                stats=tdq.stats_to_numpy(stats), status=tdq.device_status(ws),
+                exact_sets=tdq.exact_select_sets(ws))
 
 
 def to_device(X: np.ndarray, ld_pad: int = 0) -> torch.Tensor:

@@ -375,3 +375,54 @@ def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad):
         Y_ref = Y_ref.astype(np.float16)
     Y_gpu = Y[torch.from_numpy(rows).to(U.dev())].cpu().numpy()
     assert np.array_equal(Y_gpu, Y_ref)
+
+
+# ------------------------------------------- the two routes of the rank select
+def test_exact_select_route_alone():
+    """TDQ_FLAG_EXACT_SELECT resolves every set's zr rank by the per-set radix
+    select (the route a set takes when its sampled key interval misses the rank):
+    same results as the oracle, and every non-empty set is counted."""
+    lc = I.case("cfg2_fc2", B=3)
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G)
+    p.flags |= tdq.FLAG_EXACT_SELECT
+    g = U.gpu_calibrate(X, p)
+    U.assert_calibration_matches(g, X, p)
+    assert g["exact_sets"] == int((g["stats"]["n"] > 0).sum())
+    p2 = tdq.default_params(lc.G)
+    g2 = U.gpu_calibrate(X, p2)
+    assert g2["stats"].tobytes() == g["stats"].tobytes()
+    assert g2["exact_sets"] == 0, "a sampled interval missed on the benchmark's own input recipe"
+
+
+def test_sampled_interval_miss_falls_back_exactly():
+    """An input built to defeat the sample: nine tokens of 4096 channels, all with
+    the same range (so they share one token set although G = 32, which leaves that
+    set 512 one-key bins), whose smallest fifth sits in one contiguous run of
+    channels, so that the share of it inside a token's sampled channel window depends
+    on where the window starts; the rest is spread over ten octaves, which turns the
+    sample's rank error into thousands of keys.  The result must still be the exact
+    order statistic; the diagnostic counter shows that the radix levels produced it."""
+    T, C = 9, 4096
+    rng = np.random.Generator(np.random.PCG64(77))
+    X = np.exp2(rng.uniform(-9.0, 1.0, (1, T, C))).astype(np.float16)
+    X[:, :, 0:819] = rng.uniform(1e-4, 2e-4, (1, T, 819)).astype(np.float16)
+    X[:, :, 4000] = 2.0
+    X *= rng.choice([-1.0, 1.0], X.shape).astype(np.float16)
+    p = tdq.default_params(32)
+    g = U.gpu_calibrate(X, p)
+    assert (g["gid"] == 0).all()
+    U.assert_calibration_matches(g, X, p)
+    assert g["exact_sets"] == 1
+
+
+@pytest.mark.parametrize("T,C,G", [(700, 8, 4), (9, 33, 2), (1500, 48, 256), (64, 4100, 1)])
+def test_rank_select_shapes(T, C, G):
+    """Shapes around the sample geometry: sets smaller than the sample, rows narrower
+    than one sampled run, odd and unaligned C, and the largest number of sets (only
+    64 one-key bins each)."""
+    rng = np.random.Generator(np.random.PCG64(T + C + G))
+    X = (rng.laplace(0, 1, (2, T, C)) * rng.lognormal(0, 1.0, (2, T, 1))).astype(np.float16)
+    p = tdq.default_params(G)
+    g = U.gpu_calibrate(X, p, ld_pad=3 if C % 2 else 0)
+    U.assert_calibration_matches(g, X, p)
