@@ -257,8 +257,9 @@ __global__ __launch_bounds__(GEMM_THREADS, (MT * NT >= 16 ? 1 : MT * NT >= 8 ? 2
 // A wavefront owns (32 MT) x (32 NT) of Y; a workgroup is 2 x 2 wavefronts.
 //   MT = NT = 4: 256 x 256 tile, 256 accumulator registers, one wavefront per SIMD:
 //                nothing but the wavefront's own instruction stream hides latency.
-//   MT = 4, NT = 2: 256 x 128 tile, two workgroups per CU, so the prologue and the
-//                epilogue of one workgroup overlap the main loop of the other.
+//   (The template also builds 256 x 128 and 128 x 256 tiles with two workgroups per
+//   CU; on the 131072-row shapes of the largest configuration they measured within
+//   3 % of the square tile, slower on K = 4096, so the dispatcher does not use them.)
 // The stream is laid out by hand in bundles of one or two matrix instructions, the
 // six expand operations of ONE operand fragment of the NEXT operand set (3 vector
 // ops per matrix op at MT = NT = 4, which the vector unit absorbs while the matrix
@@ -595,23 +596,21 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
                             int M, int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
                             const float* w_scale, const float* bias, void* Y, tdq_dtype y_dt,
                             long long ld_y, int* acc_dump, hipStream_t st) {
-  // big tiles once they can fill the 256 CUs at least twice over
+  // big tiles once they can fill the 256 CUs at least twice over; the pipelined kernel
+  // needs whole 128-code steps of K
   const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-  int mode = big_tiles >= 512 ? (K % 128 == 0 ? 97 : 44) : 22;
-  if (const char* e = getenv("TDQ_GEMM_TILE")) mode = atoi(e);
-  if (mode >= 95 && K % 128 != 0) mode = 44;
+  const int mode = big_tiles >= 512 ? (K % 128 == 0 ? 2 : 1) : 0;
 #define TDQ_GEMM(OUT, MT, NT)                                                                   \
   launch_tile<OUT, MT, NT>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, \
                            acc_dump, st)
-#define TDQ_GEMM_MODES(OUT)                       \
-  switch (mode) {                                 \
-    case 44: TDQ_GEMM(OUT, 4, 4); break;          \
-    case 97: launch_pipe<OUT, 4, 4>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
-    case 96: launch_pipe<OUT, 4, 2>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
-    case 95: launch_pipe<OUT, 2, 4>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, acc_dump, st); break; \
-    case 42: TDQ_GEMM(OUT, 4, 2); break;          \
-    case 24: TDQ_GEMM(OUT, 2, 4); break;          \
-    default: TDQ_GEMM(OUT, 2, 2); break;          \
+#define TDQ_GEMM_MODES(OUT)                                                                      \
+  switch (mode) {                                                                                \
+    case 2:                                                                                      \
+      launch_pipe<OUT, 4, 4>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y,    \
+                             ld_y, acc_dump, st);                                                \
+      break;                                                                                     \
+    case 1: TDQ_GEMM(OUT, 4, 4); break;                                                          \
+    default: TDQ_GEMM(OUT, 2, 2); break;                                                         \
   }
   if (y_dt == TDQ_F32) { TDQ_GEMM_MODES(float) } else { TDQ_GEMM_MODES(_Float16) }
 #undef TDQ_GEMM_MODES

@@ -339,17 +339,20 @@ def test_cfg4_full_size_sampled():
 
 
 # ------------------------------------- large-tile contraction, sampled checks
-@pytest.mark.parametrize("out_dtype,with_bias,ld_pad", [(torch.float32, True, 0),
-                                                        (torch.float16, False, 0),
-                                                        (torch.float16, True, 8),
-                                                        (torch.float32, False, 2)])
-def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad):
-    """A shape that takes the large-tile kernel (many 256x256 tiles, K a multiple of
-    128) without the accumulator dump, so interior tiles take the epilogue's fast
+@pytest.mark.parametrize("out_dtype,with_bias,ld_pad,K", [(torch.float32, True, 0, 256),
+                                                          (torch.float16, False, 0, 256),
+                                                          (torch.float16, True, 8, 256),
+                                                          (torch.float32, False, 2, 256),
+                                                          (torch.float32, True, 0, 320),
+                                                          (torch.float16, False, 6, 200)])
+def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad, K):
+    """Shapes that take the large-tile kernels (many 256x256 tiles; K a multiple of
+    128 for the pipelined one, K = 320 and 200 for the generic one with its K tail)
+    without the accumulator dump, so interior tiles take the epilogue's fast
     path and the ragged last row of tiles the bounds-checked one.  ld_pad gives Y a
     padded leading dimension, whose padding must stay untouched.  The oracle checks
     whole tiles' worth of rows plus a random sample."""
-    M, K, N = 8192 + 37, 256, 4096
+    M, N = 8192 + 37, 4096
     _say(f"[gemm-large] M={M} K={K} N={N} out={out_dtype} bias={with_bias} ld_pad={ld_pad}")
     qx = I.random_codes((M, K), 101)
     qw = I.random_codes((N, K), 102)
