@@ -6,8 +6,8 @@
 // histograms needs two sweeps of X for that many bits.  Here a small sample of
 // every set first says where to look:
 //
-//   k_bracket         one workgroup per set reads up to 16 Ki sampled elements into
-//                     registers and finds, by bisection on the key bits, the sample
+//   k_bracket         one workgroup per set reads up to 16 Ki sampled elements and
+//                     finds, in an LDS histogram of their top key bits, the sample
 //                     order statistic whose sample rank corresponds to k.  The key
 //                     interval [lo, lo + W) centred on it (W = as many one-key bins as
 //                     the LDS histogram has per set) holds the true answer unless the
@@ -35,7 +35,7 @@ constexpr int kRunLen = 32;                                     // channels per 
 constexpr int kSampleMax = kSampleThreads * kSamplePerThread;   // 16 Ki keys per set
 constexpr int kSampleRuns = kSampleMax / kRunLen;               // 512 runs
 constexpr int kSampleTokens = kSampleRuns;                      // at most one run per token
-constexpr int kSampleBits = 10;                                 // key bits the bisection resolves
+constexpr int kSampleBits = 10;                                 // key bits the sample histogram resolves
 constexpr int kSweepThreads = 1024;
 
 // ---------------------------------------------------------------------------
@@ -48,7 +48,9 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   __shared__ int sel[kSampleTokens];                 // drawn token of every stratum
   __shared__ long long run_base[kSampleRuns];        // element offset of every run's first channel
   __shared__ int run_len[kSampleRuns];               // channels of the run (<= kRunLen)
+  __shared__ u32 shist[1 << kSampleBits];            // sample histogram over the top key bits
   __shared__ u32 wtot[kSampleWaves];
+  __shared__ u32 s_bin;
   const int idx = blockIdx.x;
   const int b = idx / G, j = idx - b * G;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -141,9 +143,11 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   }
   __syncthreads();
 
-  // The sample, in registers: element e of lane l of wavefront w is channel l % 32
-  // of run 8 e + 2 w + l / 32.  Loads are issued unconditionally (clamped channel)
-  // so that they overlap.
+  // The sample: element e of lane l of wavefront w is channel l % 32 of run
+  // 8 e + 2 w + l / 32.  Loads are issued unconditionally (clamped channel) so that
+  // they overlap; every live key then adds one to an LDS histogram of its top
+  // kSampleBits bits.
+  for (int i = tid; i < (1 << kSampleBits); i += kSampleThreads) shist[i] = 0;
   u32 key[kSamplePerThread];
   const int half = lane >> 5, cl = lane & 31;
 #pragma unroll
@@ -152,30 +156,49 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
     const int rl = run_len[q];
     const int ch = cl < rl ? cl : (rl > 0 ? rl - 1 : 0);
     const u32 x = X[run_base[q] + ch];
-    key[e] = cl < rl ? (x & 0x7FFFu) : 0xFFFFu;              // filler: above every candidate
+    key[e] = cl < rl ? (x & 0x7FFFu) : 0xFFFFu;
   }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < kSamplePerThread; ++e)
+    if (key[e] != 0xFFFFu) atomicAdd(&shist[key[e] >> (15 - kSampleBits)], 1u);
+  __syncthreads();
 
-  // Sample rank that corresponds to rank k of the set, and (the top kSampleBits bits
-  // of) that order statistic: the r-th smallest key is the largest v with
-  // #{key < v} < r, built bit by bit.  The low bits do not matter to the interval.
+  // Sample rank that corresponds to rank k of the set, and the histogram bin that
+  // holds that order statistic (the low key bits do not matter to the interval).
   const double n = (double)w.n, kd = (double)w.k_rem;
   long long r = (long long)(kd / n * (double)m + 0.5);
   r = r < 1 ? 1 : (r > m ? m : r);
-  u32 v = 0;
-  for (int bit = 14; bit > 14 - kSampleBits; --bit) {
-    const u32 c = v | (1u << bit);
-    u32 cnt = 0;
+  constexpr int kBinsPerThread = (1 << kSampleBits) / kSampleThreads;
+  u32 c[kBinsPerThread], mine = 0;
 #pragma unroll
-    for (int e = 0; e < kSamplePerThread; ++e) cnt += key[e] < c ? 1u : 0u;
-    cnt = group_sum_u32<64>(cnt);
-    __syncthreads();                       // the previous pass has been read by everyone
-    if (lane == 63) wtot[wave] = cnt;
-    __syncthreads();
-    u32 tot = 0;
-#pragma unroll
-    for (int w2 = 0; w2 < kSampleWaves; ++w2) tot += wtot[w2];
-    if ((long long)tot < r) v = c;
+  for (int i = 0; i < kBinsPerThread; ++i) {
+    c[i] = shist[tid * kBinsPerThread + i];
+    mine += c[i];
   }
+  u32 incl = mine;                           // inclusive scan over the wavefront
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const u32 o = (u32)__shfl_up((int)incl, d, 64);
+    if (lane >= d) incl += o;
+  }
+  if (lane == 63) wtot[wave] = incl;
+  __syncthreads();
+  u32 before = 0;
+#pragma unroll
+  for (int w2 = 0; w2 < kSampleWaves; ++w2) before += w2 < wave ? wtot[w2] : 0u;
+  incl += before;
+  if ((long long)(incl - mine) < r && r <= (long long)incl) {     // exactly one thread
+    u32 cum = incl - mine;
+    int i = 0;
+    for (; i < kBinsPerThread - 1; ++i) {
+      if ((long long)(cum + c[i]) >= r) break;
+      cum += c[i];
+    }
+    s_bin = (u32)(tid * kBinsPerThread + i);
+  }
+  __syncthreads();
+  const u32 v = s_bin << (15 - kSampleBits);
 
   if (tid == 0) {
     // v <= estimate < v + 2^(15 - kSampleBits): centre the interval on the middle
