@@ -23,6 +23,9 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
+# HBM bytes per launch of the fc1 contraction on the default workload, from the
+# FETCH_SIZE + WRITE_SIZE counters (see profiles/bench_cfg4_hbm_traffic_pmc.txt)
+GEMM_FC1_TRAFFIC_BYTES = 1192946161
 
 
 def parse():
@@ -169,12 +172,20 @@ def main():
                           "ms": round(float(seg_ms[li, 2]), 4), "ops_per_byte": round(ai, 1),
                           "hbm_gbs": round(L.gemm_bytes / (seg_ms[li, 2] * 1e-3) / 1e9, 1)})
 
-    # the dominant kernel: the int8-MFMA contraction (one launch per linear; the two
-    # launches of a step do the same 2*M*N*K operations)
-    roofline = {"kernel": "k_w4a4_gemm", "bound": "mfma", "achieved": round(gemm_tops, 1),
-                "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": None,
-                "avg_launch_ms": round(float(gemm_ms / len(layers)), 4)}
+    # The dominant kernel of a step: the fc1 contraction, k_w4a4_gemm_pipe<_Float16, 4, 4>,
+    # one launch per step (tdq_w4a4_linear launches nothing else), timed by the HIP
+    # events around that entry point on the stream it runs on.  Algorithmic work per
+    # launch = 2 M N K integer operations.  `traffic` is the HBM bytes per launch
+    # measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled on a 1 GiB copy)
+    # for exactly this workload; it is not known for other --heavy / --small settings.
+    fc1_ms = float(seg_ms[0, 2])
+    fc1_tops = fc1.gemm_ops / (fc1_ms * 1e-3) / 1e12
+    traffic = GEMM_FC1_TRAFFIC_BYTES if (fc1.lc.B == 32 and args.heavy == 10) else None
+    roofline = {"kernel": "k_w4a4_gemm_pipe<_Float16,4,4> (fc1 contraction, M=131072 K=1024 N=4096)",
+                "bound": "mfma", "achieved": round(fc1_tops, 1), "peak": PEAK_INT8_TOPS,
+                "unit": "TOP/s", "frac": round(fc1_tops / PEAK_INT8_TOPS, 4), "traffic": traffic,
+                "avg_launch_ms": round(fc1_ms, 4), "ops_per_launch": fc1.gemm_ops,
+                "algorithmic_bytes": fc1.gemm_bytes}
 
     out = {
         "metric": "DSTG+DCRP act-quant GB/s + W4A4 linear TOPS (% of HBM / int8 MFMA peak)",
@@ -202,7 +213,7 @@ def main():
     if not args.no_quality:
         out["quality"] = quality(fc1, torch, tdq)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(fc1, np)
+        out["cpu_baseline"] = cpu_baseline(layers, np)
     print(json.dumps(out), flush=True)
 
 
@@ -238,28 +249,35 @@ def quality(L, torch, tdq):
     return out
 
 
-def cpu_baseline(L, np, budget_s=12.0):
+def cpu_baseline(layers, np, budget_s=16.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the
-    activation path (calibrate + quantize) of the first images of fc1's input, and the
-    contraction of the first rows, each sized from a one-image / 16-row probe to take
-    about budget_s / 2 seconds.  Host cores of this machine; numpy runs these loops and its
-    integer matmul on one thread."""
+    activation path (calibrate + quantize) of the first images of both linears'
+    inputs, and the contraction of the first rows of fc1, each sized from a small
+    probe so that the whole leg takes about budget_s seconds.  Host cores of this box;
+    numpy runs these loops and its integer matmul on one thread."""
     from oracle import tdq_oracle as O
-    lc = L.lc
-    p = O.Params(n_groups=lc.G)
 
-    def act(n):
+    def act(L, n):
         X = L.X_host[:n]
+        p = O.Params(n_groups=L.lc.G)
         t0 = time.perf_counter()
         gid, clip, scale, _ = O.calibrate_groups(X, p)
         q = O.quantize_act(X, gid, clip, scale, p)
         return time.perf_counter() - t0, X.size, q
 
-    t1, _, _ = act(1)
-    nimg = int(max(1, min(lc.B, round(budget_s / 2 / max(t1, 1e-3)))))
-    t_act, e, q = act(nimg)
+    t_act, e_act, parts, q1 = 0.0, 0, [], None
+    for L in layers:
+        t1, e1, _ = act(L, 1)
+        nimg = int(max(1, min(L.lc.B, round(budget_s / 4 / max(t1, 1e-3)))))
+        t, e, q = act(L, nimg)
+        t_act += t
+        e_act += e
+        parts.append(f"{nimg} of {L.lc.B} images of {L.lc.name} ({e} elements, {t:.2f} s)")
+        if q1 is None:
+            q1 = q
+    lc = layers[0].lc
     qw = np.random.Generator(np.random.PCG64(1)).integers(-7, 8, (lc.N, lc.C), dtype=np.int8)
-    q2 = q.reshape(-1, lc.C)
+    q2 = q1.reshape(-1, lc.C)
     ones_n = np.ones(lc.N, np.float32)
 
     def mm(rows):
@@ -270,10 +288,9 @@ def cpu_baseline(L, np, budget_s=12.0):
     t16 = mm(16)
     rows = int(max(16, min(q2.shape[0], round(16 * budget_s / 2 / max(t16, 1e-3)))))
     t_mm = mm(rows)
-    return {"value": round(e * 2.5 / t_act / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"activation path (calibrate+quantize) of {nimg} of {lc.B} images of the "
-                      f"fc1 input, {e} elements, {t_act:.2f} s; contraction of {rows} rows x "
-                      f"{lc.N} x {lc.C}: {t_mm:.2f} s",
+    return {"value": round(e_act * 2.5 / t_act / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "activation path (calibrate+quantize) of " + " and ".join(parts) +
+                      f"; contraction of {rows} rows x {lc.N} x {lc.C}: {t_mm:.2f} s",
             "linear_tops": round(2 * rows * lc.N * lc.C / t_mm / 1e12, 6),
             "host_cpus_visible": os.cpu_count()}
 
