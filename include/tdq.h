@@ -118,8 +118,10 @@ size_t tdq_workspace_bytes(int32_t B, int32_t T, int32_t C, tdq_dtype dt, const 
  *     bins between the image's smallest and largest key, the lower end raised to
  *     at most 24 octaves below the top (integer arithmetic, exact);
  *  3. per group: c_base = max r_t, sigma = population std + eps_std;
- *     thr = the ceil(zr n)-th smallest |x| of the group (exact radix select on the
- *     magnitude bit patterns with LDS histograms);
+ *     thr = the ceil(zr n)-th smallest |x| of the group, exact: an order statistic
+ *     of the magnitude bit patterns found with LDS histograms (binary16 input: one
+ *     sweep over a key interval chosen from a sample, verified by counting, with a
+ *     radix select for any set the interval missed; binary32 input: radix select);
  *  4. c = max(min(c_base, q_max tau sigma, 2 q_max thr), eps),
  *     Delta = max(c / q_max, eps)                    (Eqs. dcrp, clipx; Lemma 1).
  *
