@@ -73,6 +73,18 @@ __device__ __forceinline__ void store_out<_Float16>(_Float16* p, float v) {
   __builtin_nontemporal_store((_Float16)v, p);
 }
 
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+typedef float f2v __attribute__((ext_vector_type(2)));
+// Two binary32 results -> two binary16 values with one packed conversion (round to
+// nearest even, as the scalar one).  As in store_out, the empty asm keeps the last
+// binary32 operations from being merged with the conversion into mixed-precision
+// instructions that would round only once.
+__device__ __forceinline__ h2v round_pair_to_half(float a, float b) {
+  asm volatile("" : "+v"(a), "+v"(b));
+  const f2v v = {a, b};
+  return __builtin_convertvector(v, h2v);
+}
+
 // Wavefront tile = (32 MT) x (32 NT) of Y, workgroup = 2 x 2 wavefronts.
 //   MT = NT = 4: 256 x 256 per workgroup, 256 accumulator registers per lane, one
 //                wavefront per SIMD; 3 expand operations per matrix instruction.
@@ -516,16 +528,37 @@ __global__ __launch_bounds__(GEMM_THREADS, (MT * NT >= 16 ? 1 : 2)) void k_w4a4_
           const float4 rs4 =
               *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
           const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
+          // Two rows at a time.  The NT column blocks of one row are stored back to
+          // back: together they cover whole cache lines of Y, written within a few
+          // instructions of each other.
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            OUT* rowp = wtile + (long long)(i * 32 + q * 8 + t) * ld_y;     // uniform
-            // the NT column blocks of one row back to back: together they cover whole
-            // cache lines of Y, written within a few instructions of each other
+          for (int t = 0; t < 4; t += 2) {
+            OUT* row0 = wtile + (long long)(i * 32 + q * 8 + t) * ld_y + lane_offu;   // uniform + lane
+            OUT* row1 = row0 + ld_y;
+            float y0[NT], y1[NT];
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
-              float y = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws[j];
-              if (decltype(with_bias)::value) y = y + bs[j];
-              store_out<OUT>(rowp + lane_offu + j * 32, y);
+              y0[j] = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws[j];
+              y1[j] = ((float)acc[i][j][4 * q + t + 1] * rsv[t + 1]) * ws[j];
+              if (decltype(with_bias)::value) {
+                y0[j] = y0[j] + bs[j];
+                y1[j] = y1[j] + bs[j];
+              }
+            }
+            if constexpr (sizeof(OUT) == 2) {
+              // one packed conversion rounds the two rows' binary32 results to binary16
+              h2v p[NT];
+#pragma unroll
+              for (int j = 0; j < NT; ++j) p[j] = round_pair_to_half(y0[j], y1[j]);
+#pragma unroll
+              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][0], row0 + j * 32);
+#pragma unroll
+              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][1], row1 + j * 32);
+            } else {
+#pragma unroll
+              for (int j = 0; j < NT; ++j) store_out<OUT>(row0 + j * 32, y0[j]);
+#pragma unroll
+              for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
             }
           }
         }
