@@ -226,22 +226,17 @@ __device__ __forceinline__ u32 wave_min_u32(u32 v) {
   return v;
 }
 
-// Per-wavefront, per-token-set partial sums of the merge (kept in LDS).
-struct SetAcc {
-  double s1, s2;
-  u32 cnt, kmax;
-};
-
 __global__ __launch_bounds__(kAssignThreads) void k_assign(
     const float* __restrict__ r, const double* __restrict__ s1, const double* __restrict__ s2,
-    int T, int C, int G, Scalars sc, int* __restrict__ gid, GroupWork* __restrict__ grp,
-    u32* __restrict__ hist, LevelPlan lp, long long groups_total, u32* __restrict__ img_flag,
-    u32* __restrict__ status) {
+    int T, int G, int* __restrict__ gid, SetAcc* __restrict__ part, u32* __restrict__ hist,
+    LevelPlan lp, long long groups_total, u32* __restrict__ img_flag, u32* __restrict__ status) {
   extern __shared__ __attribute__((aligned(16))) unsigned char assign_lds[];
   __shared__ u32 s_min[kAssignThreads / 64], s_max[kAssignThreads / 64];
   __shared__ u32 s_lo, s_hi;
   SetAcc* wacc = reinterpret_cast<SetAcc*>(assign_lds);     // [NW][G]
-  const int b = blockIdx.x;
+  // S workgroups share an image: each finds the image's key range over all T tokens
+  // (cheap) and then handles every S-th group of token batches
+  const int b = blockIdx.y, sub = blockIdx.x, S = gridDim.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NW = blockDim.x >> 6;
   const float* rb = r + (long long)b * T;
@@ -274,14 +269,17 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
     const u32 floor_key = hi > span ? hi - span : 0u;
     s_lo = lo > floor_key ? lo : floor_key;
     s_hi = hi;
-    img_flag[b] = hi >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
-    if (b == 0) status[1] = 0u;           // count of sets the single-sweep select misses
+    if (sub == 0) {
+      img_flag[b] = hi >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
+      if (b == 0) status[1] = 0u;         // count of sets the single-sweep select misses
+    }
   }
   __syncthreads();
   const u32 lo = s_lo, hi = s_hi;
   const unsigned long long width = (unsigned long long)(hi - lo) + 1ull;
 
-  // Wavefront w owns the token batches w, w + NW, ... (64 tokens each).  Inside a
+  // Wavefront w of workgroup `sub` owns the token batches sub NW + w, + S NW, ... (64
+  // tokens each).  Inside a
   // batch the tokens of one set are summed with a fixed xor tree and added to the
   // wavefront's accumulator of that set, sets in order of first appearance: every
   // floating-point sum has a fixed order, so the result is bitwise repeatable.
@@ -290,20 +288,21 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
   // the loads of the next batch are issued before the current one is reduced
   u32 nk = 0;
   double n1 = 0.0, n2 = 0.0;
-  if (wave < n_batches && wave * 64 + lane < T) {
-    const int t = wave * 64 + lane;
+  const int bt0 = sub * NW + wave, bstep = S * NW;
+  if (bt0 < n_batches && bt0 * 64 + lane < T) {
+    const int t = bt0 * 64 + lane;
     nk = __float_as_uint(rb[t]);
     n1 = s1b[t];
     n2 = s2b[t];
   }
-  for (int bt = wave; bt < n_batches; bt += NW) {
+  for (int bt = bt0; bt < n_batches; bt += bstep) {
     const int t = bt * 64 + lane;
     const bool live = t < T;
     const u32 k = nk;
     const double v1 = n1, v2 = n2;
     {
-      const int tn = t + NW * 64;
-      if (bt + NW < n_batches && tn < T) {
+      const int tn = t + bstep * 64;
+      if (bt + bstep < n_batches && tn < T) {
         nk = __float_as_uint(rb[tn]);
         n1 = s1b[tn];
         n2 = s2b[tn];
@@ -339,54 +338,63 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
   __syncthreads();
 
   for (int g = tid; g < G; g += blockDim.x) {      // merge the wavefronts in a fixed order
-    u32 cnt = 0, cmax = 0;
-    double S1 = 0.0, S2 = 0.0;
+    SetAcc m;
+    m.s1 = 0.0; m.s2 = 0.0; m.cnt = 0; m.kmax = 0;
     for (int w = 0; w < NW; ++w) {
       const SetAcc a = wacc[w * G + g];
-      cnt += a.cnt;
-      cmax = a.kmax > cmax ? a.kmax : cmax;
-      S1 += a.s1;
-      S2 += a.s2;
+      m.cnt += a.cnt;
+      m.kmax = a.kmax > m.kmax ? a.kmax : m.kmax;
+      m.s1 += a.s1;
+      m.s2 += a.s2;
     }
-    GroupWork w;
-    w.tokens = cnt;
-    w.n = (long long)cnt * (long long)C;
-    w.prefix = 0;
-    w.c_base = __uint_as_float(cmax);
-    if (cnt == 0) {
-      w.k_rem = 0;
-      w.sigma = 0.f;
-    } else {
-      const double n = (double)w.n;
-      const double mu = S1 / n;
-      double var = S2 / n - mu * mu;
-      var = var > 0.0 ? var : 0.0;
-      w.sigma = (float)(sqrt(var) + sc.eps_std);
-      long long k = (long long)ceil(sc.zr * n);   // binary64 product, then ceil
-      k = k < 1 ? 1 : (k > w.n ? w.n : k);
-      w.k_rem = k;
-    }
-    grp[(long long)b * G + g] = w;
+    part[((long long)b * S + sub) * G + g] = m;
   }
-  // clear this image's slice of every level's histogram
+  // clear this workgroup's share of the image's slice of every level's histogram
   size_t off = 0;
   for (int l = 0; l < lp.n_levels; ++l) {
     const size_t nb = (size_t)1 << lp.bits[l];
     u32* h = hist + off + (size_t)b * G * nb;
-    for (size_t i = tid; i < (size_t)G * nb; i += blockDim.x) h[i] = 0;
+    for (size_t i = (size_t)sub * blockDim.x + tid; i < (size_t)G * nb; i += (size_t)S * blockDim.x)
+      h[i] = 0;
     off += (size_t)groups_total * nb;
   }
 }
 
-hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int C,
-                         int G, const Scalars& sc, int* gid, GroupWork* grp, unsigned* hist,
-                         unsigned* img_flag, unsigned* status, const LevelPlan& lp, hipStream_t st) {
+// One thread per (image, token set): merges the partial records into the working record.
+__global__ __launch_bounds__(256) void k_finalize_groups(const SetAcc* __restrict__ part, int S, int G,
+                                                         int C, Scalars sc, long long groups_total,
+                                                         GroupWork* __restrict__ grp) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= groups_total) return;
+  grp[idx] = merge_partials(part, (int)(idx / G), (int)(idx % G), S, G, C, sc);
+}
+
+int assign_split(int T) {
+  int s = T / 1024;                        // about 16 batches of 64 tokens per workgroup
+  return s < 1 ? 1 : (s > kAssignSplitMax ? kAssignSplitMax : s);
+}
+
+hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int G,
+                         int* gid, void* part, unsigned* hist, unsigned* img_flag,
+                         unsigned* status, const LevelPlan& lp, hipStream_t st) {
   int nw = 2048 / G;                       // keep the per-wavefront accumulators under 48 KiB
   nw = nw > kAssignThreads / 64 ? kAssignThreads / 64 : (nw < 1 ? 1 : nw);
   const size_t lds = (size_t)nw * G * sizeof(SetAcc);
-  hipLaunchKernelGGL(k_assign, dim3(B), dim3(nw * 64), lds, st, r, s1, s2, T, C, G, sc, gid, grp,
-                     hist, lp, (long long)B * G, img_flag, status);
+  hipLaunchKernelGGL(k_assign, dim3(assign_split(T), B), dim3(nw * 64), lds, st, r, s1, s2, T, G,
+                     gid, static_cast<SetAcc*>(part), hist, lp, (long long)B * G, img_flag, status);
   return hipGetLastError();
+}
+
+hipError_t launch_finalize_groups(const void* part, int B, int T, int C, int G, const Scalars& sc,
+                                  GroupWork* grp, hipStream_t st) {
+  const long long total = (long long)B * G;
+  hipLaunchKernelGGL(k_finalize_groups, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const SetAcc*>(part), assign_split(T), G, C, sc, total, grp);
+  return hipGetLastError();
+}
+
+size_t assign_partial_bytes(int B, int G) {
+  return (size_t)B * kAssignSplitMax * G * sizeof(SetAcc);
 }
 
 // ---------------------------------------------------------------------------

@@ -46,6 +46,7 @@ WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {
   w.r = off;        off = align256(off + M * sizeof(float));
   w.s1 = off;       off = align256(off + M * sizeof(double));
   w.s2 = off;       off = align256(off + M * sizeof(double));
+  w.part = off;     off = align256(off + assign_partial_bytes(B, G));
   w.grp = off;      off = align256(off + BG * sizeof(GroupWork));
   w.hist = off;
   for (int l = 0; l < lp.n_levels; ++l) {
@@ -168,7 +169,8 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
 
   if (launch_token_stats(X, dt, M, C, ld_x, r, s1, s2, st) != hipSuccess) return TDQ_ERR_HIP;
 
-  if (launch_assign(r, s1, s2, B, T, C, G, sc, group_id, grp, hist, img_flag, status, lp, st) !=
+  void* part = ws + wl.part;
+  if (launch_assign(r, s1, s2, B, T, G, group_id, part, hist, img_flag, status, lp, st) !=
       hipSuccess)
     return TDQ_ERR_HIP;
 
@@ -182,15 +184,20 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
     unsigned* bhist = reinterpret_cast<unsigned*>(ws + wl.bhist);
     const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
     if (!exact_only) {
-      if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, grp, br, bhist, st) != hipSuccess)
+      if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, part, sc, grp, br, bhist, st) !=
+          hipSuccess)
         return TDQ_ERR_HIP;
       if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
         return TDQ_ERR_HIP;
     }
+    if (exact_only && launch_finalize_groups(part, B, T, C, G, sc, grp, st) != hipSuccess)
+      return TDQ_ERR_HIP;
     if (launch_bracket_select(bhist, B, G, W, exact_only, sc, grp, br, clip, scale, stats,
                               img_flag, status, st) != hipSuccess)
       return TDQ_ERR_HIP;
     missed = status + 1;
+  } else if (launch_finalize_groups(part, B, T, C, G, sc, grp, st) != hipSuccess) {
+    return TDQ_ERR_HIP;
   }
   for (int l = 0; l < lp.n_levels; ++l) {
     unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);

@@ -126,6 +126,47 @@ __device__ __forceinline__ u32 group_sum_u32(u32 v) {
   return v;
 }
 
+// Partial sums of one token set over part of an image's tokens.
+struct SetAcc {
+  double s1, s2;      // sum x, sum x^2
+  u32 cnt, kmax;      // tokens, largest range key
+};
+
+// Merges the S partial records of set j of image b (in index order, so the result is
+// bitwise repeatable) into the set's working record: n, c_base (DSTG base radius,
+// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2), rank k = ceil(zr n).
+__device__ inline GroupWork merge_partials(const SetAcc* __restrict__ part, int b, int j, int S,
+                                           int G, int C, const Scalars& sc) {
+  u32 cnt = 0, cmax = 0;
+  double S1 = 0.0, S2 = 0.0;
+  for (int s = 0; s < S; ++s) {
+    const SetAcc a = part[((long long)b * S + s) * G + j];
+    cnt += a.cnt;
+    cmax = a.kmax > cmax ? a.kmax : cmax;
+    S1 += a.s1;
+    S2 += a.s2;
+  }
+  GroupWork w;
+  w.tokens = cnt;
+  w.n = (long long)cnt * (long long)C;
+  w.prefix = 0;
+  w.c_base = __uint_as_float(cmax);
+  if (cnt == 0) {
+    w.k_rem = 0;
+    w.sigma = 0.f;
+  } else {
+    const double n = (double)w.n;
+    const double mu = S1 / n;
+    double var = S2 / n - mu * mu;
+    var = var > 0.0 ? var : 0.0;
+    w.sigma = (float)(sqrt(var) + sc.eps_std);
+    long long k = (long long)ceil(sc.zr * n);   // binary64 product, then ceil
+    k = k < 1 ? 1 : (k > w.n ? w.n : k);
+    w.k_rem = k;
+  }
+  return w;
+}
+
 // DCRP projection of one (image, token set), in binary32 (Eq. dcrp with the eps
 // floors of the supplementary numerical conventions): key is the magnitude bit
 // pattern of the k-th smallest |x| of the set.  Called by one lane per set.

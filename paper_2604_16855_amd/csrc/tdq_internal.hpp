@@ -62,6 +62,7 @@ struct WorkspaceLayout {
   size_t r;          // float[M]      per-token range
   size_t s1;         // double[M]     per-token sum x
   size_t s2;         // double[M]     per-token sum x^2
+  size_t part;       // per-workgroup partial set records of the assignment
   size_t grp;        // GroupWork[B*G]
   size_t hist;       // uint32 [levels][B*G][1 << bits[level]]
   size_t hist_level[kMaxLevels];   // offset of each level inside the workspace
@@ -85,9 +86,18 @@ struct Scalars {   // fp32 constants of the projection, rounded once on the host
 // ---- launch wrappers (each returns the hipError_t of its launch) -------------
 hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long long ld,
                               float* r, double* s1, double* s2, hipStream_t st);
-hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int C,
-                         int G, const Scalars& sc, int* gid, GroupWork* grp, unsigned* hist,
-                         unsigned* img_flag, unsigned* status, const LevelPlan& lp, hipStream_t st);
+// Token-set assignment.  An image is shared by assign_split(T) workgroups, each of
+// which leaves one partial record per set in `part`; the records are merged into
+// GroupWork either by launch_finalize_groups or, for binary16 input, by the first
+// kernel of the single-sweep rank select (launch_bracket).
+constexpr int kAssignSplitMax = 8;
+int assign_split(int T);
+size_t assign_partial_bytes(int B, int G);
+hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int G,
+                         int* gid, void* part, unsigned* hist, unsigned* img_flag,
+                         unsigned* status, const LevelPlan& lp, hipStream_t st);
+hipError_t launch_finalize_groups(const void* part, int B, int T, int C, int G, const Scalars& sc,
+                                  GroupWork* grp, hipStream_t st);
 // `missed` = device counter of sets still to resolve, or null.  With a counter the
 // kernels return at once when it is zero and skip every set marked kResolved.
 hipError_t launch_hist(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
@@ -99,8 +109,8 @@ hipError_t launch_select(unsigned* hist_level, int B, int G, int shift, int bits
                          unsigned* status, const unsigned* missed, hipStream_t st);
 // single-sweep rank select for binary16 input
 hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
-                          const int* gid, const GroupWork* grp, Bracket* br, unsigned* bhist,
-                          hipStream_t st);
+                          const int* gid, const void* part, const Scalars& sc, GroupWork* grp,
+                          Bracket* br, unsigned* bhist, hipStream_t st);
 hipError_t launch_bracket_hist(const void* X, int B, int T, int C, long long ld, int G, int W,
                                const int* gid, Bracket* br, unsigned* bhist, hipStream_t st);
 hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,

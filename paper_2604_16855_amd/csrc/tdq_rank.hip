@@ -43,8 +43,8 @@ constexpr int kSweepThreads = 1024;
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kSampleThreads) void k_bracket(
     const u16* __restrict__ X, long long ld, int T, int C, int G, int W,
-    const int* __restrict__ gid, const GroupWork* __restrict__ grp, Bracket* __restrict__ br,
-    u32* __restrict__ bhist) {
+    const int* __restrict__ gid, const SetAcc* __restrict__ part, int S, Scalars sc,
+    GroupWork* __restrict__ grp, Bracket* __restrict__ br, u32* __restrict__ bhist) {
   __shared__ int sel[kSampleTokens];                 // drawn token of every stratum
   __shared__ long long run_base[kSampleRuns];        // element offset of every run's first channel
   __shared__ int run_len[kSampleRuns];               // channels of the run (<= kRunLen)
@@ -55,7 +55,10 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   const int b = idx / G, j = idx - b * G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const GroupWork w = grp[idx];
+  // every thread merges the assignment's partial records of this set (same loads, same
+  // order, same result); one of them stores the working record for the later kernels
+  const GroupWork w = merge_partials(part, b, j, S, G, C, sc);
+  if (tid == 0) grp[idx] = w;
 
   // the sweep adds into this set's histogram and counter: clear them here
   for (int i = tid; i < W; i += kSampleThreads) bhist[(size_t)idx * W + i] = 0;
@@ -212,10 +215,11 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
 }
 
 hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
-                          const int* gid, const GroupWork* grp, Bracket* br, unsigned* bhist,
-                          hipStream_t st) {
+                          const int* gid, const void* part, const Scalars& sc, GroupWork* grp,
+                          Bracket* br, unsigned* bhist, hipStream_t st) {
   hipLaunchKernelGGL(k_bracket, dim3(B * G), dim3(kSampleThreads), 0, st,
-                     static_cast<const u16*>(X), ld, T, C, G, W, gid, grp, br, bhist);
+                     static_cast<const u16*>(X), ld, T, C, G, W, gid,
+                     static_cast<const SetAcc*>(part), assign_split(T), sc, grp, br, bhist);
   return hipGetLastError();
 }
 

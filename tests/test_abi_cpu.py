@@ -123,3 +123,14 @@ def test_quantize_and_linear_reject_bad_arguments():
     assert w(None, 8, 8, 8, FAKE, 4, FAKE, None) == tdq.ERR_NULL
     assert w(FAKE, 8, 8, 4, FAKE, 4, FAKE, None) == tdq.ERR_SHAPE
     assert w(FAKE, 8, 8, 8, FAKE, 3, FAKE, None) == tdq.ERR_SHAPE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only and says so."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr
