@@ -25,14 +25,15 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
 # HBM bytes per launch of the fc1 contraction on the default workload, from the
 # FETCH_SIZE + WRITE_SIZE counters (see profiles/bench_cfg4_hbm_traffic_pmc.txt)
-GEMM_FC1_TRAFFIC_BYTES = 1192946161
+GEMM_FC1_TRAFFIC_BYTES = 1182789066
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps first; the clocks take about 20 steps to settle")
     ap.add_argument("--heavy", type=int, default=10, choices=(2, 10, 25),
                     help="heavy-tailed token fraction of config 4, percent")
     ap.add_argument("--small", action="store_true",
