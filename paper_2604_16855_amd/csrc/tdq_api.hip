@@ -32,8 +32,8 @@ LevelPlan make_level_plan(tdq_dtype dt, int G) {
 
 int bracket_bins(int G) {
   int w = 2048;
-  while (w >= 64 && (long long)G * w > kBracketLdsWords) w >>= 1;
-  return w >= 64 ? w : 0;
+  while (w >= kBracketMinBins && (long long)G * w > kBracketLdsWords) w >>= 1;
+  return w >= kBracketMinBins ? w : 0;
 }
 
 WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {

@@ -35,13 +35,19 @@ struct Bracket {
   unsigned below;    // elements of the set with key < lo
   unsigned pad;
 };
-constexpr int kBracketLdsWords = 16384;   // 64 KiB of LDS histogram per workgroup
+constexpr int kBracketLdsWords = 16384;   // 64 KiB of LDS histogram per workgroup (128 KiB, one
+                                          // workgroup per CU, made the sweep 30 % slower)
+// Fewest one-key bins per set worth sampling for: with fewer the interval (half-width
+// bins / 2 keys, 1024 keys per octave) misses too often and the radix levels, which
+// then run anyway, are the cheaper route from the start.
+constexpr int kBracketMinBins = 256;
 // GroupWork::prefix of a set whose rank the single-sweep select has resolved (and
 // projected); the radix levels that follow skip such sets.
 constexpr unsigned kResolved = 0xFFFFFFFFu;
 
-// Bins per set of the bracket histogram (0 = this many sets do not fit: use the
-// multi-level radix select instead).
+// Bins per set of the interval histogram: the LDS budget shared out to G sets, rounded
+// down to a power of two, at most 2048 (0 = too many sets: use the multi-level radix
+// select instead).
 int bracket_bins(int G);
 
 // How the magnitude key (15 bits for fp16, 31 for fp32) is split into radix levels.

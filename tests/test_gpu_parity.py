@@ -419,11 +419,12 @@ def test_sampled_interval_miss_falls_back_exactly():
     assert g["exact_sets"] == 1
 
 
-@pytest.mark.parametrize("T,C,G", [(700, 8, 4), (9, 33, 2), (1500, 48, 256), (64, 4100, 1)])
+@pytest.mark.parametrize("T,C,G", [(700, 8, 4), (9, 33, 2), (1500, 48, 256), (64, 4100, 1),
+                                   (3000, 40, 64)])
 def test_rank_select_shapes(T, C, G):
     """Shapes around the sample geometry: sets smaller than the sample, rows narrower
-    than one sampled run, odd and unaligned C, and the largest number of sets (only
-    64 one-key bins each)."""
+    than one sampled run, odd and unaligned C, the largest number of sets that the
+    single-sweep select takes (64: 256 one-key bins each) and more (radix levels)."""
     rng = np.random.Generator(np.random.PCG64(T + C + G))
     X = (rng.laplace(0, 1, (2, T, C)) * rng.lognormal(0, 1.0, (2, T, 1))).astype(np.float16)
     p = tdq.default_params(G)
