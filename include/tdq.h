@@ -69,7 +69,8 @@ typedef struct tdq_params {
   uint32_t flags;     /* TDQ_FLAG_C1 | TDQ_FLAG_C2 = DCRP; 0 = base radius only   */
   double tau;         /* > 0                                                      */
   double zr;          /* in (0,1); rank k = ceil(zr * n) in binary64              */
-  double base_pct;    /* 0 or 1 = max-abs base radius (the only value built)      */
+  double base_pct;    /* 0 or 1 = max-abs base radius; p in (0,1) = rank quantile */
+                      /* Q_p(|x|), the ceil(p n)-th smallest (Eq. DSTG_clip)      */
   float eps_scale;    /* floor of clip radius and step, 1e-8 (Supp. numerical conv.) */
   float eps_std;      /* added to the population std, 1e-12                       */
 } tdq_params;

@@ -228,8 +228,8 @@ __device__ __forceinline__ u32 wave_min_u32(u32 v) {
 
 __global__ __launch_bounds__(kAssignThreads) void k_assign(
     const float* __restrict__ r, const double* __restrict__ s1, const double* __restrict__ s2,
-    int T, int G, int* __restrict__ gid, SetAcc* __restrict__ part, u32* __restrict__ hist,
-    LevelPlan lp, long long groups_total, u32* __restrict__ img_flag, u32* __restrict__ status) {
+    int T, int G, int* __restrict__ gid, SetAcc* __restrict__ part, u32* __restrict__ img_flag,
+    u32* __restrict__ status) {
   extern __shared__ __attribute__((aligned(16))) unsigned char assign_lds[];
   __shared__ u32 s_min[kAssignThreads / 64], s_max[kAssignThreads / 64];
   __shared__ u32 s_lo, s_hi;
@@ -271,7 +271,10 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
     s_hi = hi;
     if (sub == 0) {
       img_flag[b] = hi >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
-      if (b == 0) status[1] = 0u;         // count of sets the single-sweep select misses
+      if (b == 0) {                       // counts of sets the single-sweep select misses
+        status[1] = 0u;
+        status[2] = 0u;
+      }
     }
   }
   __syncthreads();
@@ -349,24 +352,21 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
     }
     part[((long long)b * S + sub) * G + g] = m;
   }
-  // clear this workgroup's share of the image's slice of every level's histogram
-  size_t off = 0;
-  for (int l = 0; l < lp.n_levels; ++l) {
-    const size_t nb = (size_t)1 << lp.bits[l];
-    u32* h = hist + off + (size_t)b * G * nb;
-    for (size_t i = (size_t)sub * blockDim.x + tid; i < (size_t)G * nb; i += (size_t)S * blockDim.x)
-      h[i] = 0;
-    off += (size_t)groups_total * nb;
-  }
 }
 
-// One thread per (image, token set): merges the partial records into the working record.
+// One workgroup per (image, token set): merges the partial records into the working
+// record of this pass and clears the set's radix-level histograms.
 __global__ __launch_bounds__(256) void k_finalize_groups(const SetAcc* __restrict__ part, int S, int G,
-                                                         int C, Scalars sc, long long groups_total,
-                                                         GroupWork* __restrict__ grp) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= groups_total) return;
-  grp[idx] = merge_partials(part, (int)(idx / G), (int)(idx % G), S, G, C, sc);
+                                                         int C, Scalars sc, int pass, int keep_base,
+                                                         GroupWork* __restrict__ grp,
+                                                         u32* __restrict__ hist, LevelPlan lp) {
+  const int idx = blockIdx.x;
+  if (threadIdx.x == 0) {
+    GroupWork w = merge_partials(part, idx / G, idx % G, S, G, C, sc, pass);
+    if (keep_base) w.c_base = grp[idx].c_base;
+    grp[idx] = w;
+  }
+  clear_level_hists(hist, lp, gridDim.x, idx, threadIdx.x, 256);
 }
 
 int assign_split(int T) {
@@ -375,21 +375,22 @@ int assign_split(int T) {
 }
 
 hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int G,
-                         int* gid, void* part, unsigned* hist, unsigned* img_flag,
-                         unsigned* status, const LevelPlan& lp, hipStream_t st) {
+                         int* gid, void* part, unsigned* img_flag, unsigned* status,
+                         hipStream_t st) {
   int nw = 2048 / G;                       // keep the per-wavefront accumulators under 48 KiB
   nw = nw > kAssignThreads / 64 ? kAssignThreads / 64 : (nw < 1 ? 1 : nw);
   const size_t lds = (size_t)nw * G * sizeof(SetAcc);
   hipLaunchKernelGGL(k_assign, dim3(assign_split(T), B), dim3(nw * 64), lds, st, r, s1, s2, T, G,
-                     gid, static_cast<SetAcc*>(part), hist, lp, (long long)B * G, img_flag, status);
+                     gid, static_cast<SetAcc*>(part), img_flag, status);
   return hipGetLastError();
 }
 
 hipError_t launch_finalize_groups(const void* part, int B, int T, int C, int G, const Scalars& sc,
-                                  GroupWork* grp, hipStream_t st) {
-  const long long total = (long long)B * G;
-  hipLaunchKernelGGL(k_finalize_groups, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     static_cast<const SetAcc*>(part), assign_split(T), G, C, sc, total, grp);
+                                  int pass, bool keep_base, GroupWork* grp, unsigned* hist,
+                                  const LevelPlan& lp, hipStream_t st) {
+  hipLaunchKernelGGL(k_finalize_groups, dim3(B * G), dim3(256), 0, st,
+                     static_cast<const SetAcc*>(part), assign_split(T), G, C, sc, pass,
+                     keep_base ? 1 : 0, grp, hist, lp);
   return hipGetLastError();
 }
 
@@ -537,11 +538,11 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
                                                tdq_group_stats* __restrict__ stats,
                                                const u32* __restrict__ img_flag, int B,
                                                u32* __restrict__ status,
-                                               const u32* __restrict__ missed) {
+                                               const u32* __restrict__ missed, int pass) {
   const int idx = blockIdx.x;
   const int lane = threadIdx.x;
   if (missed && (*missed == 0 || grp[idx].prefix == kResolved)) return;   // already resolved
-  if (last && idx == 0 && !missed) {   // fold the per-image flags into the status word
+  if (last && idx == 0 && !missed && pass == kPassZr) {   // fold the per-image flags into the status word
     u32 f = 0;
     for (int b = lane; b < B; b += 64) f |= img_flag[b];
     const unsigned long long any = __ballot(f != 0);
@@ -593,16 +594,21 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
     return;
   }
   if (lane != 0) return;
+  if (pass == kPassBase) {       // the order statistic found is the set's base radius Q_p(|x|)
+    if (w.tokens != 0) grp[idx].c_base = is_f16 ? h2f(prefix) : __uint_as_float(prefix);
+    grp[idx].prefix = kResolved;
+    return;
+  }
   project_store(idx, w, prefix, is_f16 != 0, sc, clip, scale, stats);
 }
 
 hipError_t launch_select(unsigned* hist_level, int B, int G, int, int bits, bool last, tdq_dtype dt,
                          const Scalars& sc, GroupWork* grp, float* clip, float* scale,
                          tdq_group_stats* stats, const unsigned* img_flag, unsigned* status,
-                         const unsigned* missed, hipStream_t st) {
+                         const unsigned* missed, int pass, hipStream_t st) {
   hipLaunchKernelGGL(k_select, dim3(B * G), dim3(64), 0, st, hist_level, bits, last ? 1 : 0,
                      dt == TDQ_F16 ? 1 : 0, sc, grp, clip, scale, stats, img_flag, B, status,
-                     missed);
+                     missed, pass);
   return hipGetLastError();
 }
 

@@ -69,8 +69,7 @@ static int check_params(const tdq_params* p) {
   if (!(p->zr > 0.0 && p->zr < 1.0)) return TDQ_ERR_PARAM;
   if (!(p->eps_scale > 0.f) || !(p->eps_std >= 0.f)) return TDQ_ERR_PARAM;
   if (p->chan_group != 0) return p->chan_group > 0 ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
-  if (p->base_pct != 0.0 && p->base_pct != 1.0)
-    return (p->base_pct > 0.0 && p->base_pct < 1.0) ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
+  if (!(p->base_pct >= 0.0 && p->base_pct <= 1.0)) return TDQ_ERR_PARAM;
   return TDQ_OK;
 }
 
@@ -89,6 +88,7 @@ static Scalars make_scalars(const tdq_params* p) {
   s.eps_scale = p->eps_scale;
   s.eps_std = (double)p->eps_std;
   s.zr = p->zr;
+  s.base_pct = (p->base_pct > 0.0 && p->base_pct < 1.0) ? p->base_pct : 0.0;
   s.flags = p->flags;
   return s;
 }
@@ -170,43 +170,51 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
   if (launch_token_stats(X, dt, M, C, ld_x, r, s1, s2, st) != hipSuccess) return TDQ_ERR_HIP;
 
   void* part = ws + wl.part;
-  if (launch_assign(r, s1, s2, B, T, G, group_id, part, hist, img_flag, status, lp, st) !=
-      hipSuccess)
+  if (launch_assign(r, s1, s2, B, T, G, group_id, part, img_flag, status, st) != hipSuccess)
     return TDQ_ERR_HIP;
 
-  // binary16 input: one sweep resolves the rank of (nearly) every set exactly; the
-  // radix levels below then run restricted to the sets it missed, and return at once
-  // when there are none
+  // One rank select per rank wanted of every set: first the base radius Q_p(|x|) when a
+  // percentile is asked for (Eq. DSTG_clip), then Q_zr(|x|) with the projection.
+  // binary16 input: one sweep resolves the rank of (nearly) every set exactly; the radix
+  // levels then run restricted to the sets it missed, and return at once when there are
+  // none.  binary32 input, or too many sets for the interval histogram: radix levels only.
   const int W = bracket_bins(G);
-  const unsigned* missed = nullptr;
-  if (dt == TDQ_F16 && W > 0 && (long long)T * C < (1ll << 32)) {
-    Bracket* br = reinterpret_cast<Bracket*>(ws + wl.br);
-    unsigned* bhist = reinterpret_cast<unsigned*>(ws + wl.bhist);
-    const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
-    if (!exact_only) {
-      if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, part, sc, grp, br, bhist, st) !=
-          hipSuccess)
+  const bool single_sweep = dt == TDQ_F16 && W > 0 && (long long)T * C < (1ll << 32);
+  const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
+  Bracket* br = reinterpret_cast<Bracket*>(ws + wl.br);
+  unsigned* bhist = reinterpret_cast<unsigned*>(ws + wl.bhist);
+  const bool two_passes = sc.base_pct > 0.0;
+  for (int pass = two_passes ? kPassBase : kPassZr; pass >= kPassZr; --pass) {
+    const bool keep_base = two_passes && pass == kPassZr;
+    const unsigned* missed = nullptr;
+    if (single_sweep) {
+      if (!exact_only) {
+        if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, part, sc, pass, keep_base, grp, br,
+                           bhist, hist, lp, st) != hipSuccess)
+          return TDQ_ERR_HIP;
+        if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
+          return TDQ_ERR_HIP;
+      } else if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
+                 hipSuccess) {
         return TDQ_ERR_HIP;
-      if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
+      }
+      if (launch_bracket_select(bhist, B, G, W, exact_only, sc, pass, grp, br, clip, scale, stats,
+                                img_flag, status, st) != hipSuccess)
+        return TDQ_ERR_HIP;
+      missed = status + 1 + pass;
+    } else if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
+               hipSuccess) {
+      return TDQ_ERR_HIP;
+    }
+    for (int l = 0; l < lp.n_levels; ++l) {
+      unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
+      if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], missed,
+                      st) != hipSuccess)
+        return TDQ_ERR_HIP;
+      if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
+                        scale, stats, img_flag, status, missed, pass, st) != hipSuccess)
         return TDQ_ERR_HIP;
     }
-    if (exact_only && launch_finalize_groups(part, B, T, C, G, sc, grp, st) != hipSuccess)
-      return TDQ_ERR_HIP;
-    if (launch_bracket_select(bhist, B, G, W, exact_only, sc, grp, br, clip, scale, stats,
-                              img_flag, status, st) != hipSuccess)
-      return TDQ_ERR_HIP;
-    missed = status + 1;
-  } else if (launch_finalize_groups(part, B, T, C, G, sc, grp, st) != hipSuccess) {
-    return TDQ_ERR_HIP;
-  }
-  for (int l = 0; l < lp.n_levels; ++l) {
-    unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
-    if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], missed,
-                    st) != hipSuccess)
-      return TDQ_ERR_HIP;
-    if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
-                      scale, stats, img_flag, status, missed, st) != hipSuccess)
-      return TDQ_ERR_HIP;
   }
   return TDQ_OK;
 }

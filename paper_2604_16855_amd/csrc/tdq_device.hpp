@@ -134,9 +134,10 @@ struct SetAcc {
 
 // Merges the S partial records of set j of image b (in index order, so the result is
 // bitwise repeatable) into the set's working record: n, c_base (DSTG base radius,
-// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2), rank k = ceil(zr n).
+// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2), and the rank this pass
+// looks for: k = ceil(zr n), or ceil(p n) in the base-radius pass.
 __device__ inline GroupWork merge_partials(const SetAcc* __restrict__ part, int b, int j, int S,
-                                           int G, int C, const Scalars& sc) {
+                                           int G, int C, const Scalars& sc, int pass) {
   u32 cnt = 0, cmax = 0;
   double S1 = 0.0, S2 = 0.0;
   for (int s = 0; s < S; ++s) {
@@ -160,11 +161,24 @@ __device__ inline GroupWork merge_partials(const SetAcc* __restrict__ part, int 
     double var = S2 / n - mu * mu;
     var = var > 0.0 ? var : 0.0;
     w.sigma = (float)(sqrt(var) + sc.eps_std);
-    long long k = (long long)ceil(sc.zr * n);   // binary64 product, then ceil
+    long long k = (long long)ceil((pass == kPassBase ? sc.base_pct : sc.zr) * n);   // binary64
     k = k < 1 ? 1 : (k > w.n ? w.n : k);
     w.k_rem = k;
   }
   return w;
+}
+
+// Clears the radix-level histograms of set idx (threads tid, tid + nthreads, ...).
+__device__ inline void clear_level_hists(u32* __restrict__ hist, const LevelPlan& lp,
+                                         long long groups_total, long long idx, int tid,
+                                         int nthreads) {
+  size_t off = 0;
+  for (int l = 0; l < lp.n_levels; ++l) {
+    const size_t nb = (size_t)1 << lp.bits[l];
+    u32* h = hist + off + (size_t)idx * nb;
+    for (size_t i = tid; i < nb; i += nthreads) h[i] = 0;
+    off += (size_t)groups_total * nb;
+  }
 }
 
 // DCRP projection of one (image, token set), in binary32 (Eq. dcrp with the eps

@@ -62,8 +62,9 @@ LevelPlan make_level_plan(tdq_dtype dt, int G);
 
 // Byte offsets of the pieces of the calibration workspace (all 256-aligned).
 struct WorkspaceLayout {
-  size_t status;     // uint32[64]; word 0 = device status word, word 1 = sets whose rank the
-                     // last binary16 calibration's sampled key interval missed
+  size_t status;     // uint32[64]; word 0 = device status word, words 1 and 2 = sets whose
+                     // rank the last binary16 calibration's sampled key interval missed in
+                     // pass kPassZr and pass kPassBase
   size_t img_flag;   // uint32[B]     per-image non-finite flag
   size_t r;          // float[M]      per-token range
   size_t s1;         // double[M]     per-token sum x
@@ -86,8 +87,15 @@ struct Scalars {   // fp32 constants of the projection, rounded once on the host
   float eps_scale;
   double eps_std;
   double zr;
+  double base_pct;   // 0 = base radius is the set's maximum; (0,1) = rank quantile Q_p (Eq. DSTG_clip)
   unsigned flags;
 };
+
+// The rank select runs once per rank wanted of every set: pass kPassBase finds the
+// base radius Q_p(|x|) (only when a percentile is asked for) and leaves it in
+// GroupWork::c_base; pass kPassZr finds Q_zr(|x|) and applies the projection.
+constexpr int kPassZr = 0;
+constexpr int kPassBase = 1;
 
 // ---- launch wrappers (each returns the hipError_t of its launch) -------------
 hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long long ld,
@@ -100,29 +108,34 @@ constexpr int kAssignSplitMax = 8;
 int assign_split(int T);
 size_t assign_partial_bytes(int B, int G);
 hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int G,
-                         int* gid, void* part, unsigned* hist, unsigned* img_flag,
-                         unsigned* status, const LevelPlan& lp, hipStream_t st);
+                         int* gid, void* part, unsigned* img_flag, unsigned* status,
+                         hipStream_t st);
+// Arms the radix levels for one pass: working record of every set (rank of this pass;
+// keep_base = keep the base radius an earlier pass left) and cleared level histograms.
 hipError_t launch_finalize_groups(const void* part, int B, int T, int C, int G, const Scalars& sc,
-                                  GroupWork* grp, hipStream_t st);
+                                  int pass, bool keep_base, GroupWork* grp, unsigned* hist,
+                                  const LevelPlan& lp, hipStream_t st);
 // `missed` = device counter of sets still to resolve, or null.  With a counter the
-// kernels return at once when it is zero and skip every set marked kResolved.
+// kernels return at once when it is zero and skip every set marked kResolved.  The last
+// level of pass kPassZr projects, that of pass kPassBase stores the base radius.
 hipError_t launch_hist(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                        const int* gid, const GroupWork* grp, unsigned* hist_level, int shift,
                        int bits, const unsigned* missed, hipStream_t st);
 hipError_t launch_select(unsigned* hist_level, int B, int G, int shift, int bits, bool last,
                          tdq_dtype dt, const Scalars& sc, GroupWork* grp, float* clip,
                          float* scale, tdq_group_stats* stats, const unsigned* img_flag,
-                         unsigned* status, const unsigned* missed, hipStream_t st);
+                         unsigned* status, const unsigned* missed, int pass, hipStream_t st);
 // single-sweep rank select for binary16 input
 hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
-                          const int* gid, const void* part, const Scalars& sc, GroupWork* grp,
-                          Bracket* br, unsigned* bhist, hipStream_t st);
+                          const int* gid, const void* part, const Scalars& sc, int pass,
+                          bool keep_base, GroupWork* grp, Bracket* br, unsigned* bhist,
+                          unsigned* hist, const LevelPlan& lp, hipStream_t st);
 hipError_t launch_bracket_hist(const void* X, int B, int T, int C, long long ld, int G, int W,
                                const int* gid, Bracket* br, unsigned* bhist, hipStream_t st);
 hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,
-                                 const Scalars& sc, GroupWork* grp, const Bracket* br, float* clip,
-                                 float* scale, tdq_group_stats* stats, const unsigned* img_flag,
-                                 unsigned* status, hipStream_t st);
+                                 const Scalars& sc, int pass, GroupWork* grp, const Bracket* br,
+                                 float* clip, float* scale, tdq_group_stats* stats,
+                                 const unsigned* img_flag, unsigned* status, hipStream_t st);
 hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                            const int* gid, const float* clip, const float* scale, uint8_t* Q,
                            long long ld_q, hipStream_t st);

@@ -43,8 +43,9 @@ constexpr int kSweepThreads = 1024;
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kSampleThreads) void k_bracket(
     const u16* __restrict__ X, long long ld, int T, int C, int G, int W,
-    const int* __restrict__ gid, const SetAcc* __restrict__ part, int S, Scalars sc,
-    GroupWork* __restrict__ grp, Bracket* __restrict__ br, u32* __restrict__ bhist) {
+    const int* __restrict__ gid, const SetAcc* __restrict__ part, int S, Scalars sc, int pass,
+    int keep_base, GroupWork* __restrict__ grp, Bracket* __restrict__ br, u32* __restrict__ bhist,
+    u32* __restrict__ hist, LevelPlan lp) {
   __shared__ int sel[kSampleTokens];                 // drawn token of every stratum
   __shared__ long long run_base[kSampleRuns];        // element offset of every run's first channel
   __shared__ int run_len[kSampleRuns];               // channels of the run (<= kRunLen)
@@ -57,11 +58,15 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // every thread merges the assignment's partial records of this set (same loads, same
   // order, same result); one of them stores the working record for the later kernels
-  const GroupWork w = merge_partials(part, b, j, S, G, C, sc);
+  GroupWork w = merge_partials(part, b, j, S, G, C, sc, pass);
+  if (keep_base) w.c_base = grp[idx].c_base;     // left by the base-radius pass (only this
+                                                 // field is read; thread 0 rewrites it unchanged)
   if (tid == 0) grp[idx] = w;
 
-  // the sweep adds into this set's histogram and counter: clear them here
+  // the sweep adds into this set's histogram and counter, the radix levels (should the
+  // interval miss) into theirs: clear them here
   for (int i = tid; i < W; i += kSampleThreads) bhist[(size_t)idx * W + i] = 0;
+  clear_level_hists(hist, lp, gridDim.x, idx, tid, kSampleThreads);
   if (w.tokens == 0) {
     if (tid == 0) {
       Bracket e;
@@ -215,11 +220,13 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
 }
 
 hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
-                          const int* gid, const void* part, const Scalars& sc, GroupWork* grp,
-                          Bracket* br, unsigned* bhist, hipStream_t st) {
+                          const int* gid, const void* part, const Scalars& sc, int pass,
+                          bool keep_base, GroupWork* grp, Bracket* br, unsigned* bhist,
+                          unsigned* hist, const LevelPlan& lp, hipStream_t st) {
   hipLaunchKernelGGL(k_bracket, dim3(B * G), dim3(kSampleThreads), 0, st,
                      static_cast<const u16*>(X), ld, T, C, G, W, gid,
-                     static_cast<const SetAcc*>(part), assign_split(T), sc, grp, br, bhist);
+                     static_cast<const SetAcc*>(part), assign_split(T), sc, pass,
+                     keep_base ? 1 : 0, grp, br, bhist, hist, lp);
   return hipGetLastError();
 }
 
@@ -334,13 +341,13 @@ hipError_t launch_bracket_hist(const void* Xv, int B, int T_, int C, long long l
 // k_bracket_select
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_bracket_select(
-    const u32* __restrict__ bhist, int W, int force_miss, Scalars sc, GroupWork* __restrict__ grp,
-    const Bracket* __restrict__ br, float* __restrict__ clip, float* __restrict__ scale,
-    tdq_group_stats* __restrict__ stats, const u32* __restrict__ img_flag, int B,
-    u32* __restrict__ status) {
+    const u32* __restrict__ bhist, int W, int force_miss, Scalars sc, int pass,
+    GroupWork* __restrict__ grp, const Bracket* __restrict__ br, float* __restrict__ clip,
+    float* __restrict__ scale, tdq_group_stats* __restrict__ stats,
+    const u32* __restrict__ img_flag, int B, u32* __restrict__ status) {
   const int idx = blockIdx.x;
   const int lane = threadIdx.x;
-  if (idx == 0) {   // fold the per-image flags into the status word
+  if (idx == 0 && pass == kPassZr) {   // fold the per-image flags into the status word
     u32 f = 0;
     for (int b = lane; b < B; b += 64) f |= img_flag[b];
     const unsigned long long any = __ballot(f != 0);
@@ -349,7 +356,7 @@ __global__ __launch_bounds__(64) void k_bracket_select(
   const GroupWork w = grp[idx];
   if (w.tokens == 0) {
     if (lane == 0) {
-      project_store(idx, w, 0u, true, sc, clip, scale, stats);
+      if (pass == kPassZr) project_store(idx, w, 0u, true, sc, clip, scale, stats);
       grp[idx].prefix = kResolved;
     }
     return;
@@ -376,7 +383,7 @@ __global__ __launch_bounds__(64) void k_bracket_select(
     need = k - e.below;
   }
   if (!ok) {                                  // wavefront-uniform
-    if (lane == 0) atomicAdd(&status[1], 1u); // prefix stays 0, k_rem = k: radix levels take over
+    if (lane == 0) atomicAdd(&status[1 + pass], 1u);   // prefix stays 0, k_rem = k: radix levels take over
     return;
   }
   const unsigned long long hit = __ballot(incl >= need);
@@ -389,17 +396,21 @@ __global__ __launch_bounds__(64) void k_bracket_select(
       if (cum + c >= need) break;
       cum += c;
     }
-    project_store(idx, w, e.lo + (u32)(first + i), true, sc, clip, scale, stats);
+    const u32 key = e.lo + (u32)(first + i);
+    if (pass == kPassBase)
+      grp[idx].c_base = h2f(key);              // the set's base radius Q_p(|x|)
+    else
+      project_store(idx, w, key, true, sc, clip, scale, stats);
     grp[idx].prefix = kResolved;
   }
 }
 
 hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,
-                                 const Scalars& sc, GroupWork* grp, const Bracket* br, float* clip,
-                                 float* scale, tdq_group_stats* stats, const unsigned* img_flag,
-                                 unsigned* status, hipStream_t st) {
+                                 const Scalars& sc, int pass, GroupWork* grp, const Bracket* br,
+                                 float* clip, float* scale, tdq_group_stats* stats,
+                                 const unsigned* img_flag, unsigned* status, hipStream_t st) {
   hipLaunchKernelGGL(k_bracket_select, dim3(B * G), dim3(64), 0, st, bhist, W, force_miss ? 1 : 0,
-                     sc, grp, br, clip, scale, stats, img_flag, B, status);
+                     sc, pass, grp, br, clip, scale, stats, img_flag, B, status);
   return hipGetLastError();
 }
 

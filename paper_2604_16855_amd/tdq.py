@@ -172,7 +172,7 @@ def device_status(workspace: torch.Tensor) -> int:
 def exact_select_sets(workspace: torch.Tensor) -> int:
     """How many token sets the last binary16 tdq_calibrate_groups resolved by the
     radix levels because the sampled key interval missed their rank (synchronises)."""
-    return int(workspace[4:8].view(torch.int32).item())
+    return int(workspace[4:12].view(torch.int32).sum().item())
 
 
 def stats_to_numpy(stats: torch.Tensor):

@@ -22,7 +22,8 @@ def dev():
 
 
 def oracle_params(p: tdq.Params) -> O.Params:
-    return O.Params(n_groups=p.n_groups, flags=p.flags & 3, tau=p.tau, zr=p.zr)
+    return O.Params(n_groups=p.n_groups, flags=p.flags & 3, tau=p.tau, zr=p.zr,
+                    base_pct=p.base_pct)
 
 
 def gpu_calibrate(X: np.ndarray, p: tdq.Params, ld_pad: int = 0):

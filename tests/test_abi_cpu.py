@@ -84,7 +84,7 @@ def test_calibrate_rejects_bad_arguments():
                             ("zr", 1.0, tdq.ERR_PARAM), ("flags", 4, tdq.ERR_PARAM),
                             ("act_bits", 3, tdq.ERR_PARAM), ("act_bits", 8, tdq.ERR_UNSUPPORTED),
                             ("chan_group", 32, tdq.ERR_UNSUPPORTED),
-                            ("base_pct", 0.99, tdq.ERR_UNSUPPORTED),
+                            ("base_pct", 1.5, tdq.ERR_PARAM), ("base_pct", -0.1, tdq.ERR_PARAM),
                             ("eps_scale", 0.0, tdq.ERR_PARAM)):
         q = tdq.default_params()
         setattr(q, field, val)

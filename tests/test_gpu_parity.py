@@ -430,3 +430,32 @@ def test_rank_select_shapes(T, C, G):
     p = tdq.default_params(G)
     g = U.gpu_calibrate(X, p, ld_pad=3 if C % 2 else 0)
     U.assert_calibration_matches(g, X, p)
+
+
+# ------------------------------------------------- percentile base radius Q_p
+@pytest.mark.parametrize("case,pct,flags,extra", [("cfg2_fc2", 0.99, 3, 0), ("cfg2_qkv", 0.5, 0, 0),
+                                                  ("cfg0", 0.99, 3, 0), ("cfg0", 0.9, 0, 0),
+                                                  ("cfg2_proj", 0.999, 3, 256)])
+def test_percentile_base_radius(case, pct, flags, extra):
+    """Base radius = the ceil(p n)-th smallest |x| of the set instead of its maximum
+    (Eq. DSTG_clip, percentile branch): binary16 input through the single-sweep select
+    (twice: base radius, then the zr quantile), binary32 input and the validation
+    switch through the radix levels.  flags = 0 makes the base radius the clip itself."""
+    lc = I.case(case) if case == "cfg0" else I.case(case, B=3)
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G, flags=flags)
+    p.base_pct = pct
+    p.flags |= extra
+    g = U.gpu_calibrate(X, p)
+    assert g["status"] == 0
+    gid, clip, scale, st = U.assert_calibration_matches(g, X, p)
+    used = g["stats"]["n"] > 0
+    if flags == 0:
+        assert np.array_equal(g["stats"]["clip"][used], np.maximum(g["stats"]["c_base"][used], 1e-8))
+    # quantize with the projected radii: codes match the oracle's
+    Q = tdq.tdq_quantize_act(g["Xd"], p, g["gid_d"], g["clip_d"], g["scale_d"])
+    q_ref = O.quantize_act(X, gid, clip, scale, U.oracle_params(p)).reshape(lc.M, lc.C)
+    rows = np.arange(lc.B)[:, None]
+    exact = np.array_equal(g["scale"], scale) and np.array_equal(g["clip"], clip)
+    U.assert_codes_match(U.unpack_device_codes(Q, lc.C), q_ref, X, clip[rows, gid].reshape(-1),
+                         scale[rows, gid].reshape(-1), exact)
