@@ -173,7 +173,7 @@ def main():
                           "ms": round(float(seg_ms[li, 2]), 4), "ops_per_byte": round(ai, 1),
                           "hbm_gbs": round(L.gemm_bytes / (seg_ms[li, 2] * 1e-3) / 1e9, 1)})
 
-    # The dominant kernel of a step: the fc1 contraction, k_w4a4_gemm_pipe<_Float16, 4, 4>,
+    # The dominant kernel of a step: the fc1 contraction, k_w4a4_gemm_wide<_Float16>,
     # one launch per step (tdq_w4a4_linear launches nothing else), timed by the HIP
     # events around that entry point on the stream it runs on.  Algorithmic work per
     # launch = 2 M N K integer operations.  `traffic` is the HBM bytes per launch
@@ -182,7 +182,7 @@ def main():
     fc1_ms = float(seg_ms[0, 2])
     fc1_tops = fc1.gemm_ops / (fc1_ms * 1e-3) / 1e12
     traffic = GEMM_FC1_TRAFFIC_BYTES if (fc1.lc.B == 32 and args.heavy == 10) else None
-    roofline = {"kernel": "k_w4a4_gemm_pipe<_Float16,4,4> (fc1 contraction, M=131072 K=1024 N=4096)",
+    roofline = {"kernel": "k_w4a4_gemm_wide<_Float16> (fc1 contraction, M=131072 K=1024 N=4096)",
                 "bound": "mfma", "achieved": round(fc1_tops, 1), "peak": PEAK_INT8_TOPS,
                 "unit": "TOP/s", "frac": round(fc1_tops / PEAK_INT8_TOPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(fc1_ms, 4), "ops_per_launch": fc1.gemm_ops,

@@ -330,6 +330,24 @@ __device__ __forceinline__ void expand_one(Operands<MT, NT>& dst, const Frags<MT
 // MT * NT matrix instructions on `cur`, spread over MT + NT bundles, each with the
 // expansion of one fragment of operand set EXP_SET from `f` into `nxt` and with
 // mem(b), at most one memory instruction.
+// One half (HALF = 0: words x / z -> elements 0, 1; HALF = 1: words y / w -> elements
+// 2, 3) of the expansion of fragment e: three vector operations.
+template <int SET, int HALF, int MT, int NT>
+__device__ __forceinline__ void expand_half(Operands<MT, NT>& dst, const Frags<MT, NT>& f, int e,
+                                            u32 hi) {
+  const uint4& q = e < MT ? f.a[e] : f.b[e - MT];
+  const u32 w = SET == 0 ? (HALF == 0 ? q.x : q.y) : (HALF == 0 ? q.z : q.w);
+  v4i& d = e < MT ? dst.a[e] : dst.b[e - MT];
+  d[2 * HALF] = (int)((w << 4) & hi);      // even codes of w, times 16
+  d[2 * HALF + 1] = (int)(w & hi);         // odd codes of w, times 16
+}
+
+// MT * NT matrix instructions on `cur`, spread over MT + NT bundles, each with the
+// expansion of one fragment of operand set EXP_SET from `f` into `nxt` and with
+// mem(b), at most one memory instruction.  A wavefront issues in order, and a matrix
+// instruction cannot start before the previous one has left the matrix pipe, so the
+// vector work of a bundle is split between the shadows of its matrix instructions
+// (matrix, three vector, matrix, three vector + memory) rather than queued behind both.
 template <int EXP_SET, int MT, int NT, typename MEM>
 __device__ __forceinline__ void half_slab(v16i (&acc)[MT][NT], const Operands<MT, NT>& cur,
                                           Operands<MT, NT>& nxt, const Frags<MT, NT>& f, u32 hi,
@@ -337,12 +355,20 @@ __device__ __forceinline__ void half_slab(v16i (&acc)[MT][NT], const Operands<MT
   constexpr int NB = MT + NT, NM = MT * NT;
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
+    const int lo = (b * NM) / NB, up = ((b + 1) * NM) / NB, mid = lo + (up - lo + 1) / 2;
 #pragma unroll
-    for (int m = (b * NM) / NB; m < ((b + 1) * NM) / NB; ++m) {
+    for (int m = lo; m < mid; ++m) {
       const int i = m / NT, j = m % NT;
       acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
     }
-    expand_one<EXP_SET>(nxt, f, b, hi);
+    expand_half<EXP_SET, 0>(nxt, f, b, hi);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = mid; m < up; ++m) {
+      const int i = m / NT, j = m % NT;
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+    }
+    expand_half<EXP_SET, 1>(nxt, f, b, hi);
     mem(b);
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -353,6 +379,105 @@ __device__ __forceinline__ void dma16(const uint8_t* gptr, unsigned lds_base) {
                :
                : "v"(gptr), "s"(lds_base)
                : "memory");
+}
+
+// Epilogue of the pipelined kernels.  Register r of a 32x32 accumulator fragment held
+// by lane l is element (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
+template <typename OUT, int MT, int NT>
+__device__ __forceinline__ void pipe_epilogue(v16i (&acc)[MT][NT], const float* sRow,
+                                              const float* sCol, const float* sBias, int lane,
+                                              int wm, int wn, int m0, int n0, int M, int N,
+                                              const float* __restrict__ bias, OUT* __restrict__ Y,
+                                              long long ld_y, int* __restrict__ acc_dump) {
+  constexpr int BM = 64 * MT, BN = 64 * NT;
+  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+  const bool inside = m0 + BM <= M && n0 + BN <= N;
+  if (inside && !acc_dump && (long long)(BM + 8) * ld_y < (1ll << 31) / (long long)sizeof(OUT)) {
+    // Fast path: whole tile inside Y.  Every address is a wavefront-uniform row pointer
+    // plus one per-lane 32-bit offset, and the bias branch is taken once, not per element.
+    const unsigned lane_offu = (unsigned)(rquad * (int)ld_y + ccol);
+    auto body = [&](auto with_bias) {
+      float ws[NT], bs[NT];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        ws[j] = sCol[wn * 32 * NT + j * 32 + ccol];
+        bs[j] = sBias[wn * 32 * NT + j * 32 + ccol];
+      }
+      OUT* wtile = Y + (long long)(m0 + wm * 32 * MT) * ld_y + (n0 + wn * 32 * NT);
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 rs4 =
+              *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
+          const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
+          // Two rows at a time.  The NT column blocks of one row are stored back to
+          // back: together they cover whole cache lines of Y, written within a few
+          // instructions of each other.
+#pragma unroll
+          for (int t = 0; t < 4; t += 2) {
+            OUT* row0 = wtile + (long long)(i * 32 + q * 8 + t) * ld_y + lane_offu;   // uniform + lane
+            OUT* row1 = row0 + ld_y;
+            float y0[NT], y1[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+              y0[j] = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws[j];
+              y1[j] = ((float)acc[i][j][4 * q + t + 1] * rsv[t + 1]) * ws[j];
+              if (decltype(with_bias)::value) {
+                y0[j] = y0[j] + bs[j];
+                y1[j] = y1[j] + bs[j];
+              }
+            }
+            if constexpr (sizeof(OUT) == 2) {
+              // one packed conversion rounds the two rows' binary32 results to binary16
+              h2v p[NT];
+#pragma unroll
+              for (int j = 0; j < NT; ++j) p[j] = round_pair_to_half(y0[j], y1[j]);
+#pragma unroll
+              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][0], row0 + j * 32);
+#pragma unroll
+              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][1], row1 + j * 32);
+            } else {
+#pragma unroll
+              for (int j = 0; j < NT; ++j) store_out<OUT>(row0 + j * 32, y0[j]);
+#pragma unroll
+              for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
+            }
+          }
+        }
+      }
+    };
+    if (bias)
+      body(std::true_type{});
+    else
+      body(std::false_type{});
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int cl = wn * 32 * NT + j * 32 + ccol;
+      const int n = n0 + cl;
+      const float ws = sCol[cl], bs = sBias[cl];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = wm * 32 * MT + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
+        const int m = m0 + rl;
+        if (m < M && n < N) {
+          float y;
+          if (acc_dump) {
+            const int a = acc[i][j][r] >> 8;          // exact: accumulator is 256 * acc
+            acc_dump[(long long)m * N + n] = a;
+            y = ((float)a * sRow[rl]) * ws;
+          } else {
+            y = ((float)acc[i][j][r] * sRow[rl]) * ws;
+          }
+          if (bias) y = y + bs;
+          store_out<OUT>(Y + (long long)m * ld_y + n, y);
+        }
+      }
+    }
 }
 
 template <typename OUT, int MT, int NT>
@@ -505,96 +630,159 @@ __global__ __launch_bounds__(GEMM_THREADS, (MT * NT >= 16 ? 1 : 2)) void k_w4a4_
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing of ours may still be landing
 #undef TDQ_STAGE
 
-  // Epilogue.  Register r of a 32x32 accumulator fragment held by lane l is
-  // element (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
-  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
-  const bool inside = m0 + BM <= M && n0 + BN <= N;
-  if (inside && !acc_dump && (long long)(BM + 8) * ld_y < (1ll << 31) / (long long)sizeof(OUT)) {
-    // Fast path: whole tile inside Y.  Every address is a wavefront-uniform row pointer
-    // plus one per-lane 32-bit offset, and the bias branch is taken once, not per element.
-    const unsigned lane_offu = (unsigned)(rquad * (int)ld_y + ccol);
-    auto body = [&](auto with_bias) {
-      float ws[NT], bs[NT];
+  pipe_epilogue<OUT, MT, NT>(acc, sRow, sCol, sBias, lane, wm, wn, m0, n0, M, N, bias, Y, ld_y,
+                             acc_dump);
+}
+
+// ---------------------------------------------------------------------------
+// Wide-stage variant of the pipelined kernel (K a multiple of 256 codes): a stage is
+// 128 bytes = one whole cache line of every operand row, so a line is fetched once
+// (the 64-byte stages above fetch each line twice, two stages apart, and the L1
+// cannot hold 512 lines in between), and the workgroup meets at one barrier per 256
+// codes instead of two.  256 x 256 tile, 2 x 2 wavefronts of 4 x 4 blocks, two LDS
+// slots of 64 KiB.  Per stage (4 slabs of 64 codes; Xs/Ys as above):
+//   X0 | LDS reads of slab 1        Y0 | loads 8..15 of stage + 1
+//   X1 | LDS reads of slab 2        Y1
+//   X2 | LDS reads of slab 3        Y2
+//   wait for stage + 1 (all of this thread's loads), barrier
+//   X3 | LDS reads of slab 0 of stage + 1      Y3 | loads 0..7 of stage + 2
+// The loads of stage + 2 go into the slot of the stage that is ending: its last
+// fragment reads (slab 3) were issued before the barrier, and every wavefront drains
+// its LDS reads before it arrives there.  LDS rows are 128 bytes, piece c of row r at
+// position c ^ ((r >> 1) & 7): 16 consecutive rows fall on 16 different bank groups.
+// ---------------------------------------------------------------------------
+template <typename OUT>
+__global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_wide(
+    const uint8_t* __restrict__ Qx, long long ld_q, const int* __restrict__ gid,
+    const float* __restrict__ scale, int M, int T, int K, int N, int G,
+    const uint8_t* __restrict__ Qw, long long ld_w, const float* __restrict__ w_scale,
+    const float* __restrict__ bias, OUT* __restrict__ Y, long long ld_y, int* __restrict__ acc_dump,
+    int m_tiles, int n_tiles) {
+  constexpr int MT = 4, NT = 4, BM = 256, BN = 256, NB = MT + NT;
+  constexpr int BKW = 128;                     // packed bytes of K per stage (256 codes)
+  constexpr int SLOT = (BM + BN) * BKW;        // 64 KiB: A rows then B rows, 128 B each
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[2 * SLOT];
+  __shared__ __attribute__((aligned(16))) float sRow[BM], sCol[BN], sBias[BN];
+
+  const int bid = blockIdx.x;
+  const int xcd = bid % XCDS, idx = bid / XCDS;
+  const int m_tile = (idx / n_tiles) * XCDS + xcd;
+  const int n_tile = idx % n_tiles;
+  if (m_tile >= m_tiles) return;
+  const int m0 = m_tile * BM, n0 = n_tile * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int k_tiles = (K / 2) / BKW;                // host guarantees K % 256 == 0
+
+  const int my_m = m0 + tid < M ? m0 + tid : M - 1;
+  const int my_g = gid ? gid[my_m] : 0;
+
+  // global source of this lane's piece of load i: rows 32 i + 8 w + (l >> 3), 8 per load
+  const uint8_t* pa[2 * MT];
+  const uint8_t* pb[2 * NT];
+  {
+    const int rl0 = 8 * wave + (lane >> 3);
+    const int c = (lane & 7) ^ ((rl0 >> 1) & 7);      // logical piece stored at position l & 7
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        ws[j] = sCol[wn * 32 * NT + j * 32 + ccol];
-        bs[j] = sBias[wn * 32 * NT + j * 32 + ccol];
-      }
-      OUT* wtile = Y + (long long)(m0 + wm * 32 * MT) * ld_y + (n0 + wn * 32 * NT);
+    for (int i = 0; i < 2 * MT; ++i) {
+      int r = m0 + 32 * i + rl0;
+      r = r < M ? r : M - 1;
+      pa[i] = Qx + (long long)r * ld_q + c * 16;
+    }
 #pragma unroll
-      for (int i = 0; i < MT; ++i) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float4 rs4 =
-              *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
-          const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
-          // Two rows at a time.  The NT column blocks of one row are stored back to
-          // back: together they cover whole cache lines of Y, written within a few
-          // instructions of each other.
-#pragma unroll
-          for (int t = 0; t < 4; t += 2) {
-            OUT* row0 = wtile + (long long)(i * 32 + q * 8 + t) * ld_y + lane_offu;   // uniform + lane
-            OUT* row1 = row0 + ld_y;
-            float y0[NT], y1[NT];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-              y0[j] = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws[j];
-              y1[j] = ((float)acc[i][j][4 * q + t + 1] * rsv[t + 1]) * ws[j];
-              if (decltype(with_bias)::value) {
-                y0[j] = y0[j] + bs[j];
-                y1[j] = y1[j] + bs[j];
-              }
-            }
-            if constexpr (sizeof(OUT) == 2) {
-              // one packed conversion rounds the two rows' binary32 results to binary16
-              h2v p[NT];
-#pragma unroll
-              for (int j = 0; j < NT; ++j) p[j] = round_pair_to_half(y0[j], y1[j]);
-#pragma unroll
-              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][0], row0 + j * 32);
-#pragma unroll
-              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][1], row1 + j * 32);
-            } else {
-#pragma unroll
-              for (int j = 0; j < NT; ++j) store_out<OUT>(row0 + j * 32, y0[j]);
-#pragma unroll
-              for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
-            }
-          }
-        }
-      }
-    };
-    if (bias)
-      body(std::true_type{});
-    else
-      body(std::false_type{});
-    return;
+    for (int i = 0; i < 2 * NT; ++i) {
+      int n = n0 + 32 * i + rl0;
+      n = n < N ? n : N - 1;
+      pb[i] = Qw + (long long)n * ld_w + c * 16;
+    }
   }
+  const unsigned ring_base =
+      (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)ring;
+  const unsigned dma_base = __builtin_amdgcn_readfirstlane(ring_base + wave * 1024);
+  auto dma_piece = [&](int slot, int kt, int e) {     // slot, e compile-time; e = 0 .. 15
+    const int kc = kt < k_tiles ? kt : k_tiles - 1;    // past the end: harmless re-load
+    const long long ko = (long long)kc * BKW;
+    if (e < 2 * MT)
+      dma16(pa[e] + ko, dma_base + slot * SLOT + e * 4096);
+    else
+      dma16(pb[e - 2 * MT] + ko, dma_base + slot * SLOT + BM * BKW + (e - 2 * MT) * 4096);
+  };
+
+  // fragment reads: lane (row r' = l & 31, half h = l >> 5) of fragment e reads piece
+  // 2 ks + h of row 32 e + r' (+ the wavefront's offset); the swizzle only depends on r'
+  const int frow = lane & 31, fh = lane >> 5, swz = (frow >> 1) & 7;
+  const int a_row = (wm * 128 + frow) * BKW, b_row = BM * BKW + (wn * 128 + frow) * BKW;
+  const int off0 = ((0 + fh) ^ swz) * 16, off1 = ((2 + fh) ^ swz) * 16;
+  const int off2 = ((4 + fh) ^ swz) * 16, off3 = ((6 + fh) ^ swz) * 16;
+  auto read_piece = [&](Frags<MT, NT>& f, int slot, int ks, int e) {   // slot, ks, e compile-time
+    const int off = ks == 0 ? off0 : ks == 1 ? off1 : ks == 2 ? off2 : off3;
+    if (e < MT)
+      f.a[e] = *reinterpret_cast<const uint4*>(&ring[slot * SLOT + a_row + e * 4096 + off]);
+    else
+      f.b[e - MT] =
+          *reinterpret_cast<const uint4*>(&ring[slot * SLOT + b_row + (e - MT) * 4096 + off]);
+  };
+
+  v16i acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int cl = wn * 32 * NT + j * 32 + ccol;
-      const int n = n0 + cl;
-      const float ws = sCol[cl], bs = sBias[cl];
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rl = wm * 32 * MT + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
-        const int m = m0 + rl;
-        if (m < M && n < N) {
-          float y;
-          if (acc_dump) {
-            const int a = acc[i][j][r] >> 8;          // exact: accumulator is 256 * acc
-            acc_dump[(long long)m * N + n] = a;
-            y = ((float)a * sRow[rl]) * ws;
-          } else {
-            y = ((float)acc[i][j][r] * sRow[rl]) * ws;
-          }
-          if (bias) y = y + bs;
-          store_out<OUT>(Y + (long long)m * ld_y + n, y);
-        }
-      }
-    }
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+  Frags<MT, NT> f0, f1;
+  Operands<MT, NT> s0, s1;
+  u32 hi;                                   // 0xF0F0F0F0 in a scalar register
+  asm volatile("s_mov_b32 %0, 0xf0f0f0f0" : "=s"(hi));
+#pragma unroll
+  for (int e = 0; e < 2 * NB; ++e) dma_piece(0, 0, e);
+#pragma unroll
+  for (int e = 0; e < NB; ++e) dma_piece(1, 1, e);
+  {
+    const float rs = scale[(long long)(my_m / T) * G + my_g];
+    // the accumulators carry a factor 256; folding 2^-8 into the row scale is exact
+    sRow[tid] = acc_dump ? rs : rs * 0.00390625f;
+    const int n = n0 + tid;
+    sCol[tid] = n < N ? w_scale[n] : 0.f;
+    sBias[tid] = (bias && n < N) ? bias[n] : 0.f;
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NB) : "memory");      // stage 0 has landed
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < NB; ++e) read_piece(f0, 0, 0, e);
+#pragma unroll
+  for (int e = 0; e < NB; ++e) expand_one<0>(s0, f0, e, hi);
+
+#define TDQ_WSTAGE(kt, CUR, OTH)                                                                 \
+  do {                                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    half_slab<1>(acc, s0, s1, f0, hi, [&](int b) { read_piece(f1, CUR, 1, b); });       /* X0 */ \
+    half_slab<0>(acc, s1, s0, f1, hi, [&](int b) { dma_piece(OTH, (kt) + 1, NB + b); }); /* Y0 */ \
+    half_slab<1>(acc, s0, s1, f1, hi, [&](int b) { read_piece(f0, CUR, 2, b); });       /* X1 */ \
+    half_slab<0>(acc, s1, s0, f0, hi, [&](int) {});                                     /* Y1 */ \
+    half_slab<1>(acc, s0, s1, f0, hi, [&](int b) { read_piece(f1, CUR, 3, b); });       /* X2 */ \
+    half_slab<0>(acc, s1, s0, f1, hi, [&](int) {});                                     /* Y2 */ \
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                  \
+    __syncthreads();                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    half_slab<1>(acc, s0, s1, f1, hi, [&](int b) { read_piece(f0, OTH, 0, b); });       /* X3 */ \
+    half_slab<0>(acc, s1, s0, f0, hi, [&](int b) { dma_piece(CUR, (kt) + 2, b); });     /* Y3 */ \
+  } while (0)
+
+  int kt = 0;
+  for (; kt + 1 < k_tiles; kt += 2) {
+    TDQ_WSTAGE(kt, 0, 1);
+    TDQ_WSTAGE(kt + 1, 1, 0);
+  }
+  if (kt < k_tiles) TDQ_WSTAGE(kt, 0, 1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing of ours may still be landing
+#undef TDQ_WSTAGE
+
+  pipe_epilogue<OUT, MT, NT>(acc, sRow, sCol, sBias, lane, wm, wn, m0, n0, M, N, bias, Y, ld_y,
+                             acc_dump);
 }
 
 template <typename OUT, int MT, int NT>
@@ -625,19 +813,36 @@ static void launch_pipe(const uint8_t* Qx, long long ld_q, const int* gid, const
                      ld_y, acc_dump, m_tiles, n_tiles);
 }
 
+template <typename OUT>
+static void launch_wide(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale, int M,
+                        int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
+                        const float* w_scale, const float* bias, void* Y, long long ld_y,
+                        int* acc_dump, hipStream_t st) {
+  const int m_tiles = (M + 255) / 256, n_tiles = (N + 255) / 256;
+  const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
+  const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
+  hipLaunchKernelGGL((k_w4a4_gemm_wide<OUT>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q, gid,
+                     scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, static_cast<OUT*>(Y), ld_y,
+                     acc_dump, m_tiles, n_tiles);
+}
+
 hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale,
                             int M, int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
                             const float* w_scale, const float* bias, void* Y, tdq_dtype y_dt,
                             long long ld_y, int* acc_dump, hipStream_t st) {
-  // big tiles once they can fill the 256 CUs at least twice over; the pipelined kernel
-  // needs whole 128-code steps of K
   const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-  const int mode = big_tiles >= 512 ? (K % 128 == 0 ? 2 : 1) : 0;
+  // big tiles once they can fill the 256 CUs at least twice over; the pipelined kernels
+  // need whole stages of K: 256 codes (measured 2 to 3 % faster), else 128
+  const int mode = big_tiles >= 512 ? (K % 256 == 0 ? 3 : K % 128 == 0 ? 2 : 1) : 0;
 #define TDQ_GEMM(OUT, MT, NT)                                                                   \
   launch_tile<OUT, MT, NT>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, \
                            acc_dump, st)
 #define TDQ_GEMM_MODES(OUT)                                                                      \
   switch (mode) {                                                                                \
+    case 3:                                                                                      \
+      launch_wide<OUT>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y,    \
+                       acc_dump, st);                                                            \
+      break;                                                                                     \
     case 2:                                                                                      \
       launch_pipe<OUT, 4, 4>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y,    \
                              ld_y, acc_dump, st);                                                \

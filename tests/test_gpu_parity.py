@@ -344,10 +344,14 @@ def test_cfg4_full_size_sampled():
                                                           (torch.float16, True, 8, 256),
                                                           (torch.float32, False, 2, 256),
                                                           (torch.float32, True, 0, 320),
-                                                          (torch.float16, False, 6, 200)])
+                                                          (torch.float16, False, 6, 200),
+                                                          (torch.float32, True, 0, 384),
+                                                          (torch.float16, True, 0, 128),
+                                                          (torch.float16, False, 0, 768)])
 def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad, K):
     """Shapes that take the large-tile kernels (many 256x256 tiles; K a multiple of
-    128 for the pipelined one, K = 320 and 200 for the generic one with its K tail)
+    256 for the wide-stage pipelined one, K = 384 and 128 for the 128-code-stage one,
+    K = 320 and 200 for the generic one with its K tail; 768 = three wide stages)
     without the accumulator dump, so interior tiles take the epilogue's fast
     path and the ragged last row of tiles the bounds-checked one.  ld_pad gives Y a
     padded leading dimension, whose padding must stay untouched.  The oracle checks
