@@ -242,6 +242,18 @@ def quality(L, torch, tdq):
         return res
 
     out = {"tdq": measure(L.gid, L.scale, L.Q)}
+    # which term of the projection set each token set's radius (Eq. dcrp), and the
+    # step-to-dispersion ratio eta = Delta / sigma of the sets (Eq. cg_Delta_eta)
+    _, _, _, stats, _ = tdq.tdq_calibrate_groups(L.X, L.p, want_stats=True)
+    st = tdq.stats_to_numpy(stats)
+    names = ("base", "c1_tau", "c2_zr", "eps_floor", "empty")
+    out["tdq"]["bind_counts"] = {n: int((st["bind"] == i).sum()) for i, n in enumerate(names)}
+    used = st["n"] > 0
+    out["tdq"]["eta_max"] = round(float((st["scale"][used] / st["sigma"][used]).max()), 4)
+    # range disparity D(X) = max |x| / median over tokens of the per-token median |x|
+    ax = L.X.reshape(lc.M, lc.C).abs().float()
+    out["range_disparity"] = round(float(ax.max() / ax.median(dim=1).values.median()), 1)
+    del ax
     p1 = tdq.default_params(1, flags=0)
     gid1, clip1, scale1, _, _ = tdq.tdq_calibrate_groups(L.X, p1)
     Q1 = tdq.tdq_quantize_act(L.X, p1, gid1, clip1, scale1)

@@ -147,6 +147,20 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
                      const float* scale, uint8_t* Qx, int64_t ld_q, void* stream);
 
 /*
+ * Diagnostics of the paper's Sec. 3.2 per (image, token set), as exact element counts
+ * for the radii and steps given: zero_count = elements whose code is 0 (zero-bin mass
+ * rho_0 = zero_count / n, Eq. rho0_def; the code is computed exactly as
+ * tdq_quantize_act computes it), clipped_count = elements with |x| > c.  The
+ * step-to-dispersion ratio eta = Delta / sigma (Eq. cg_Delta_eta) follows from
+ * tdq_group_stats.  One sweep of X.  zero_count, clipped_count [B*G] out, 8-byte
+ * aligned; they need not be cleared.
+ */
+int tdq_group_diagnostics(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                          const tdq_params* p, const int32_t* group_id, const float* clip,
+                          const float* scale, uint64_t* zero_count, uint64_t* clipped_count,
+                          void* stream);
+
+/*
  * W4A4 contraction with the dequantizing epilogue (Supp. Algorithm 1, step 10,
  * written on the integer codes):
  *   acc[m, n] = sum_i Qx[m, i] * Qw[n, i]                      (int32, exact)

@@ -774,6 +774,90 @@ hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, lon
 }
 
 // ---------------------------------------------------------------------------
+// Diagnostics of Sec. 3.2 per (image, token set), as exact counts: elements whose code
+// is 0 (zero-bin mass rho_0 = count / n, Eq. rho0_def) and elements clipped by the
+// radius (|x| > c).  The code is computed exactly as K_c computes it.  One sweep of X.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_group_diag(const T* __restrict__ X, long long ld, int T_, int C,
+                                                    int G, const int* __restrict__ gid,
+                                                    const float* __restrict__ clip,
+                                                    const float* __restrict__ scale,
+                                                    unsigned long long* __restrict__ zero_count,
+                                                    unsigned long long* __restrict__ clipped_count,
+                                                    int rows_per_block) {
+  extern __shared__ u32 diag_lds[];              // [G] zero codes, [G] clipped
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < 2 * G; i += 256) diag_lds[i] = 0;
+  __syncthreads();
+  const int row0 = blockIdx.x * rows_per_block;
+  int nrows = T_ - row0;
+  nrows = nrows < rows_per_block ? nrows : rows_per_block;
+  for (int rr = wave; rr < nrows; rr += 4) {     // one wavefront per row
+    const long long row = (long long)b * T_ + row0 + rr;
+    const int g = gid ? gid[row] : 0;
+    const float c = clip[(long long)b * G + g];
+    const float d = scale[(long long)b * G + g];
+    const float rcp = 1.0f / d;
+    const T* xp = X + row * ld;
+    u32 nz = 0, nc = 0;
+    for (int ch = lane; ch < C; ch += 64) {
+      const float x = Elem<T>::val(xp[ch]);
+      nz += quant_nibble(x, c, d, rcp) == 0u ? 1u : 0u;
+      nc += fabsf(x) > c ? 1u : 0u;
+    }
+    nz = group_sum_u32<64>(nz);
+    nc = group_sum_u32<64>(nc);
+    if (lane == 63) {
+      atomicAdd(&diag_lds[g], nz);
+      atomicAdd(&diag_lds[G + g], nc);
+    }
+  }
+  __syncthreads();
+  for (int g = tid; g < G; g += 256) {
+    if (diag_lds[g]) atomicAdd(&zero_count[(long long)b * G + g], (unsigned long long)diag_lds[g]);
+    if (diag_lds[G + g])
+      atomicAdd(&clipped_count[(long long)b * G + g], (unsigned long long)diag_lds[G + g]);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_zero_u64(unsigned long long* __restrict__ a,
+                                                  unsigned long long* __restrict__ b2, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    a[i] = 0;
+    b2[i] = 0;
+  }
+}
+
+hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
+                             const int* gid, const float* clip, const float* scale,
+                             unsigned long long* zero_count, unsigned long long* clipped_count,
+                             hipStream_t st) {
+  const long long total = (long long)B * G;
+  hipLaunchKernelGGL(k_zero_u64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, zero_count,
+                     clipped_count, total);
+  // a workgroup's counters are 32-bit: at most 2^31 elements per workgroup
+  long long rpb = (1ll << 20) / (C > 0 ? C : 1);
+  rpb = rpb < 4 ? 4 : rpb;
+  if (rpb * C >= (1ll << 31)) rpb = ((1ll << 31) - 1) / C;
+  if (rpb < 1) rpb = 1;
+  if (rpb > T) rpb = T;
+  const unsigned chunks = (unsigned)((T + rpb - 1) / rpb);
+  const size_t lds = (size_t)2 * G * sizeof(u32);
+  if (dt == TDQ_F16)
+    hipLaunchKernelGGL((k_group_diag<u16>), dim3(chunks, B), dim3(256), lds, st,
+                       static_cast<const u16*>(X), ld, T, C, G, gid, clip, scale, zero_count,
+                       clipped_count, (int)rpb);
+  else
+    hipLaunchKernelGGL((k_group_diag<float>), dim3(chunks, B), dim3(256), lds, st,
+                       static_cast<const float*>(X), ld, T, C, G, gid, clip, scale, zero_count,
+                       clipped_count, (int)rpb);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Offline weight quantizer (Eq. weight_quant): one wavefront per output channel.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_quantize_weight(const float* __restrict__ W, int K,

@@ -238,6 +238,29 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
   return TDQ_OK;
 }
 
+int tdq_group_diagnostics(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                          const tdq_params* p, const int32_t* group_id, const float* clip,
+                          const float* scale, uint64_t* zero_count, uint64_t* clipped_count,
+                          void* stream) {
+  if (!X || !p || !clip || !scale || !zero_count || !clipped_count) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  if (!group_id && p->n_groups != 1) return TDQ_ERR_NULL;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(zero_count) | reinterpret_cast<uintptr_t>(clipped_count)) & 7)
+    return TDQ_ERR_ALIGN;
+  if (launch_group_diag(X, dt, B, T, C, ld_x, p->n_groups, group_id, clip, scale,
+                        reinterpret_cast<unsigned long long*>(zero_count),
+                        reinterpret_cast<unsigned long long*>(clipped_count),
+                        static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
 int tdq_w4a4_linear(const uint8_t* Qx, int64_t ld_q, const int32_t* group_id, const float* scale,
                     int32_t B, int32_t T, int32_t K, int32_t N, int32_t G, const uint8_t* Qw,
                     int64_t ld_w, const float* w_scale, const float* bias, void* Y,

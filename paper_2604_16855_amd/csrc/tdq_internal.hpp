@@ -139,6 +139,10 @@ hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, boo
 hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                            const int* gid, const float* clip, const float* scale, uint8_t* Q,
                            long long ld_q, hipStream_t st);
+hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
+                             const int* gid, const float* clip, const float* scale,
+                             unsigned long long* zero_count, unsigned long long* clipped_count,
+                             hipStream_t st);
 hipError_t launch_quantize_weight(const float* W, int N, int K, long long ld_in, uint8_t* Qw,
                                   long long ld_w, float* w_scale, hipStream_t st);
 hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale,

@@ -78,6 +78,9 @@ def lib() -> C.CDLL:
     L.tdq_w4a4_linear.restype = C.c_int
     L.tdq_w4a4_linear.argtypes = [vp, i64, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp, vp, vp,
                                   C.c_int, i64, vp, vp]
+    L.tdq_group_diagnostics.restype = C.c_int
+    L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
+                                        vp, vp, vp, vp]
     L.tdq_quantize_weight.restype = C.c_int
     L.tdq_quantize_weight.argtypes = [vp, i32, i32, i64, vp, i64, vp, vp]
     _lib = L
@@ -201,6 +204,22 @@ def tdq_quantize_act(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],
                                 _stream())
     _check(rc, "tdq_quantize_act")
     return out
+
+
+def tdq_group_diagnostics(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],
+                          clip: torch.Tensor, scale: torch.Tensor
+                          ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """-> (zero_count[B, G], clipped_count[B, G]) int64: elements of every token set
+    whose code is 0, and elements with |x| above the set's clip radius."""
+    B, T, Cc, ld = _btc(X)
+    G = p.n_groups
+    zero = torch.empty((B, G), dtype=torch.int64, device=X.device)
+    clipped = torch.empty((B, G), dtype=torch.int64, device=X.device)
+    rc = lib().tdq_group_diagnostics(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p), _ptr(gid),
+                                     clip.data_ptr(), scale.data_ptr(), zero.data_ptr(),
+                                     clipped.data_ptr(), _stream())
+    _check(rc, "tdq_group_diagnostics")
+    return zero, clipped
 
 
 def tdq_quantize_weight(W: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -463,3 +463,33 @@ def test_percentile_base_radius(case, pct, flags, extra):
     exact = np.array_equal(g["scale"], scale) and np.array_equal(g["clip"], clip)
     U.assert_codes_match(U.unpack_device_codes(Q, lc.C), q_ref, X, clip[rows, gid].reshape(-1),
                          scale[rows, gid].reshape(-1), exact)
+
+
+# ------------------------------------------------------- device diagnostics
+@pytest.mark.parametrize("case,ld_pad", [("cfg0", 0), ("cfg1", 0), ("cfg2_fc2", 0), ("cfg2_qkv", 4)])
+def test_group_diagnostics(case, ld_pad):
+    """Zero-bin and clipped counts per token set (Eq. rho0_def) against the oracle's
+    codes, exactly; with the projected radii nothing exceeds the base radius, so a
+    second call uses halved radii to make the clipped count non-trivial."""
+    lc = I.case(case) if case in ("cfg0", "cfg1") else I.case(case, B=3)
+    X, _ = I.make_activations(lc)
+    p = tdq.default_params(lc.G)
+    g = U.gpu_calibrate(X, p, ld_pad)
+    gid, clip, scale = g["gid"], g["clip"], g["scale"]
+    for shrink in (1.0, 0.5):
+        c = (clip * shrink).astype(np.float32)
+        cd = torch.from_numpy(c).to(U.dev())
+        zero, clipped = tdq.tdq_group_diagnostics(g["Xd"], p, g["gid_d"], cd, g["scale_d"])
+        torch.cuda.synchronize()
+        q = O.quantize_act(X, gid, c, scale, U.oracle_params(p))
+        zr = np.zeros((lc.B, lc.G), np.int64)
+        cr = np.zeros((lc.B, lc.G), np.int64)
+        for b in range(lc.B):
+            for j in range(lc.G):
+                m = gid[b] == j
+                zr[b, j] = int((q[b][m] == 0).sum())
+                cr[b, j] = int((np.abs(X[b][m].astype(np.float32)) > c[b, j]).sum())
+        assert np.array_equal(zero.cpu().numpy(), zr)
+        assert np.array_equal(clipped.cpu().numpy(), cr)
+        if shrink == 0.5:
+            assert cr.sum() > 0
