@@ -55,7 +55,7 @@ typedef enum {
 #define TDQ_FLAG_C1 1u /* constraint C1: Delta <= tau * sigma   (Eq. tau_constraint) */
 #define TDQ_FLAG_C2 2u /* constraint C2: Delta/2 <= Q_zr(|x|)   (Eq. zr_constraint)  */
 /* Validation switch, no effect on the result: resolve the zr rank of every token set
- * of a binary16 input by the multi-level radix select alone (the route that is
+ * of a binary16 input by the per-set radix select alone (the route that is
  * otherwise taken only by a set whose sampled key interval missed the rank). */
 #define TDQ_FLAG_EXACT_SELECT 256u
 
@@ -97,7 +97,7 @@ typedef struct tdq_group_stats {
 #define TDQ_DEV_NONFINITE 1u /* X holds an Inf or NaN: results undefined          */
 /* The second uint32 of the workspace is a diagnostic: after a calibration of
  * binary16 input, the number of (image, token set) pairs whose zr rank was resolved
- * by the multi-level radix select because the sampled key interval missed it (or
+ * by the per-set radix select because the sampled key interval missed it (or
  * because TDQ_FLAG_EXACT_SELECT was set).  It has no bearing on the results. */
 
 int tdq_version(void);

@@ -412,11 +412,9 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
                                                        const int* __restrict__ gid,
                                                        const GroupWork* __restrict__ grp,
                                                        u32* __restrict__ hist, int shift, int bits,
-                                                       int rows_per_block,
-                                                       const u32* __restrict__ missed) {
+                                                       int rows_per_block) {
   extern __shared__ u32 lds[];
   constexpr int V = Elem<T>::V;
-  if (missed && *missed == 0) return;      // nothing left to resolve (uniform over the grid)
   // The top level walks X backwards: it runs right after the forward statistics sweep,
   // so the end of X is what the last-level cache still holds.
   const int b = FIRST ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
@@ -437,8 +435,7 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
   for (int rr = slot; rr < nrows; rr += SLOTS) {
     const long long row = (long long)b * T_ + row0 + rr;
     const int g = gid[row];
-    const u32 prefix = (FIRST && !missed) ? 0u : grp[(long long)b * G + g].prefix;
-    if (missed && prefix == kResolved) continue;          // this row's set is done
+    const u32 prefix = FIRST ? 0u : grp[(long long)b * G + g].prefix;
     u32* h = lds + (g << bits);
     const T* xp = X + row * ld;
 #pragma unroll 2
@@ -478,8 +475,7 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const T* __restrict__ X, 
 
 template <typename T>
 static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, const int* gid,
-                         const GroupWork* grp, u32* hist, int shift, int bits, const u32* missed,
-                         hipStream_t st) {
+                         const GroupWork* grp, u32* hist, int shift, int bits, hipStream_t st) {
   constexpr int V = Elem<T>::V;
   const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % V == 0) ? 1 : 0;
   const int L = lanes_per_row(C, V);
@@ -501,12 +497,10 @@ static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, 
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<T, LL, true>),         \
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
       hipLaunchKernelGGL((k_hist<T, LL, true>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, \
-                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb,   \
-                         missed);                                                              \
+                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);  \
     } else {                                                                                   \
       hipLaunchKernelGGL((k_hist<T, LL, false>), dim3(chunks, B), dim3(kHistThreads), lds_bytes, \
-                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb,   \
-                         missed);                                                              \
+                         st, X, ld, T_, C, G, vec_ok, gid, grp, hist, shift, bits, (int)rpb);  \
     }                                                                                          \
     break;
   switch (L) {
@@ -518,12 +512,12 @@ static hipError_t hist_t(const T* X, int B, int T_, int C, long long ld, int G, 
 
 hipError_t launch_hist(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                        const int* gid, const GroupWork* grp, unsigned* hist_level, int shift,
-                       int bits, const unsigned* missed, hipStream_t st) {
+                       int bits, hipStream_t st) {
   if (dt == TDQ_F16)
     return hist_t<u16>(static_cast<const u16*>(X), B, T, C, ld, G, gid, grp, hist_level, shift,
-                       bits, missed, st);
+                       bits, st);
   return hist_t<float>(static_cast<const float*>(X), B, T, C, ld, G, gid, grp, hist_level, shift,
-                       bits, missed, st);
+                       bits, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -537,12 +531,10 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
                                                float* __restrict__ clip, float* __restrict__ scale,
                                                tdq_group_stats* __restrict__ stats,
                                                const u32* __restrict__ img_flag, int B,
-                                               u32* __restrict__ status,
-                                               const u32* __restrict__ missed, int pass) {
+                                               u32* __restrict__ status, int pass) {
   const int idx = blockIdx.x;
   const int lane = threadIdx.x;
-  if (missed && (*missed == 0 || grp[idx].prefix == kResolved)) return;   // already resolved
-  if (last && idx == 0 && !missed && pass == kPassZr) {   // fold the per-image flags into the status word
+  if (last && idx == 0 && pass == kPassZr) {   // fold the per-image flags into the status word
     u32 f = 0;
     for (int b = lane; b < B; b += 64) f |= img_flag[b];
     const unsigned long long any = __ballot(f != 0);
@@ -596,7 +588,6 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
   if (lane != 0) return;
   if (pass == kPassBase) {       // the order statistic found is the set's base radius Q_p(|x|)
     if (w.tokens != 0) grp[idx].c_base = is_f16 ? h2f(prefix) : __uint_as_float(prefix);
-    grp[idx].prefix = kResolved;
     return;
   }
   project_store(idx, w, prefix, is_f16 != 0, sc, clip, scale, stats);
@@ -605,10 +596,9 @@ __global__ __launch_bounds__(64) void k_select(const u32* __restrict__ hist, int
 hipError_t launch_select(unsigned* hist_level, int B, int G, int, int bits, bool last, tdq_dtype dt,
                          const Scalars& sc, GroupWork* grp, float* clip, float* scale,
                          tdq_group_stats* stats, const unsigned* img_flag, unsigned* status,
-                         const unsigned* missed, int pass, hipStream_t st) {
+                         int pass, hipStream_t st) {
   hipLaunchKernelGGL(k_select, dim3(B * G), dim3(64), 0, st, hist_level, bits, last ? 1 : 0,
-                     dt == TDQ_F16 ? 1 : 0, sc, grp, clip, scale, stats, img_flag, B, status,
-                     missed, pass);
+                     dt == TDQ_F16 ? 1 : 0, sc, grp, clip, scale, stats, img_flag, B, status, pass);
   return hipGetLastError();
 }
 

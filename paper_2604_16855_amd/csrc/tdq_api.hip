@@ -175,9 +175,9 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
 
   // One rank select per rank wanted of every set: first the base radius Q_p(|x|) when a
   // percentile is asked for (Eq. DSTG_clip), then Q_zr(|x|) with the projection.
-  // binary16 input: one sweep resolves the rank of (nearly) every set exactly; the radix
-  // levels then run restricted to the sets it missed, and return at once when there are
-  // none.  binary32 input, or too many sets for the interval histogram: radix levels only.
+  // binary16 input: one sweep resolves the rank of (nearly) every set exactly, and the
+  // kernel that verifies it resolves the others.  binary32 input, or too many sets for
+  // the interval histogram: radix levels.
   const int W = bracket_bins(G);
   const bool single_sweep = dt == TDQ_F16 && W > 0 && (long long)T * C < (1ll << 32);
   const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
@@ -186,11 +186,10 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
   const bool two_passes = sc.base_pct > 0.0;
   for (int pass = two_passes ? kPassBase : kPassZr; pass >= kPassZr; --pass) {
     const bool keep_base = two_passes && pass == kPassZr;
-    const unsigned* missed = nullptr;
     if (single_sweep) {
       if (!exact_only) {
         if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, part, sc, pass, keep_base, grp, br,
-                           bhist, hist, lp, st) != hipSuccess)
+                           bhist, st) != hipSuccess)
           return TDQ_ERR_HIP;
         if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
           return TDQ_ERR_HIP;
@@ -198,21 +197,21 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
                  hipSuccess) {
         return TDQ_ERR_HIP;
       }
-      if (launch_bracket_select(bhist, B, G, W, exact_only, sc, pass, grp, br, clip, scale, stats,
-                                img_flag, status, st) != hipSuccess)
+      if (launch_bracket_finish(X, B, T, C, ld_x, G, W, group_id, bhist, exact_only, sc, pass, grp,
+                                br, clip, scale, stats, img_flag, status, st) != hipSuccess)
         return TDQ_ERR_HIP;
-      missed = status + 1 + pass;
-    } else if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
-               hipSuccess) {
-      return TDQ_ERR_HIP;
+      continue;
     }
+    if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
+        hipSuccess)
+      return TDQ_ERR_HIP;
     for (int l = 0; l < lp.n_levels; ++l) {
       unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
-      if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], missed,
-                      st) != hipSuccess)
+      if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], st) !=
+          hipSuccess)
         return TDQ_ERR_HIP;
       if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
-                        scale, stats, img_flag, status, missed, pass, st) != hipSuccess)
+                        scale, stats, img_flag, status, pass, st) != hipSuccess)
         return TDQ_ERR_HIP;
     }
   }

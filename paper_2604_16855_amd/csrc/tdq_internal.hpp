@@ -41,9 +41,6 @@ constexpr int kBracketLdsWords = 16384;   // 64 KiB of LDS histogram per workgro
 // bins / 2 keys, 1024 keys per octave) misses too often and the radix levels, which
 // then run anyway, are the cheaper route from the start.
 constexpr int kBracketMinBins = 256;
-// GroupWork::prefix of a set whose rank the single-sweep select has resolved (and
-// projected); the radix levels that follow skip such sets.
-constexpr unsigned kResolved = 0xFFFFFFFFu;
 
 // Bins per set of the interval histogram: the LDS budget shared out to G sets, rounded
 // down to a power of two, at most 2048 (0 = too many sets: use the multi-level radix
@@ -64,7 +61,7 @@ LevelPlan make_level_plan(tdq_dtype dt, int G);
 struct WorkspaceLayout {
   size_t status;     // uint32[64]; word 0 = device status word, words 1 and 2 = sets whose
                      // rank the last binary16 calibration's sampled key interval missed in
-                     // pass kPassZr and pass kPassBase
+                     // pass kPassZr and pass kPassBase (resolved by the per-set radix select)
   size_t img_flag;   // uint32[B]     per-image non-finite flag
   size_t r;          // float[M]      per-token range
   size_t s1;         // double[M]     per-token sum x
@@ -115,24 +112,23 @@ hipError_t launch_assign(const float* r, const double* s1, const double* s2, int
 hipError_t launch_finalize_groups(const void* part, int B, int T, int C, int G, const Scalars& sc,
                                   int pass, bool keep_base, GroupWork* grp, unsigned* hist,
                                   const LevelPlan& lp, hipStream_t st);
-// `missed` = device counter of sets still to resolve, or null.  With a counter the
-// kernels return at once when it is zero and skip every set marked kResolved.  The last
-// level of pass kPassZr projects, that of pass kPassBase stores the base radius.
+// The last level of pass kPassZr projects, that of pass kPassBase stores the base radius.
 hipError_t launch_hist(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                        const int* gid, const GroupWork* grp, unsigned* hist_level, int shift,
-                       int bits, const unsigned* missed, hipStream_t st);
+                       int bits, hipStream_t st);
 hipError_t launch_select(unsigned* hist_level, int B, int G, int shift, int bits, bool last,
                          tdq_dtype dt, const Scalars& sc, GroupWork* grp, float* clip,
                          float* scale, tdq_group_stats* stats, const unsigned* img_flag,
-                         unsigned* status, const unsigned* missed, int pass, hipStream_t st);
+                         unsigned* status, int pass, hipStream_t st);
 // single-sweep rank select for binary16 input
 hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
                           const int* gid, const void* part, const Scalars& sc, int pass,
                           bool keep_base, GroupWork* grp, Bracket* br, unsigned* bhist,
-                          unsigned* hist, const LevelPlan& lp, hipStream_t st);
+                          hipStream_t st);
 hipError_t launch_bracket_hist(const void* X, int B, int T, int C, long long ld, int G, int W,
                                const int* gid, Bracket* br, unsigned* bhist, hipStream_t st);
-hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,
+hipError_t launch_bracket_finish(const void* X, int B, int T, int C, long long ld, int G, int W,
+                                 const int* gid, const unsigned* bhist, bool force_miss,
                                  const Scalars& sc, int pass, GroupWork* grp, const Bracket* br,
                                  float* clip, float* scale, tdq_group_stats* stats,
                                  const unsigned* img_flag, unsigned* status, hipStream_t st);

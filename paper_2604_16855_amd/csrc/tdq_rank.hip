@@ -14,13 +14,12 @@
 //                     sample is off by more than W/2 keys.
 //   k_bracket_hist    one sweep of X: per set, the number of keys below lo and an LDS
 //                     histogram, one bin per key, of the keys inside the interval.
-//   k_bracket_select  one wavefront per set: if below < k <= below + inside, the
+//   k_bracket_finish  one workgroup per set: if below < k <= below + inside, the
 //                     answer is the bin where the running count reaches k - below --
 //                     the exact k-th smallest, no matter how the interval was chosen --
-//                     and the set is projected and marked resolved.  Otherwise the set
-//                     is counted as missed, and the host-side sequence that follows
-//                     (the multi-level radix select, restricted to missed sets, whose
-//                     kernels return at once when the count is zero) resolves it.
+//                     and the set is projected.  Otherwise the set is counted as missed
+//                     and the same workgroup resolves it with a two-level radix select
+//                     over the set's own rows (exact as well, and rare).
 //
 // The result is therefore always the exact order statistic; the sample only decides
 // which of the two routes computes it, i.e. how long it takes.
@@ -44,8 +43,8 @@ constexpr int kSweepThreads = 1024;
 __global__ __launch_bounds__(kSampleThreads) void k_bracket(
     const u16* __restrict__ X, long long ld, int T, int C, int G, int W,
     const int* __restrict__ gid, const SetAcc* __restrict__ part, int S, Scalars sc, int pass,
-    int keep_base, GroupWork* __restrict__ grp, Bracket* __restrict__ br, u32* __restrict__ bhist,
-    u32* __restrict__ hist, LevelPlan lp) {
+    int keep_base, GroupWork* __restrict__ grp, Bracket* __restrict__ br,
+    u32* __restrict__ bhist) {
   __shared__ int sel[kSampleTokens];                 // drawn token of every stratum
   __shared__ long long run_base[kSampleRuns];        // element offset of every run's first channel
   __shared__ int run_len[kSampleRuns];               // channels of the run (<= kRunLen)
@@ -63,10 +62,8 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
                                                  // field is read; thread 0 rewrites it unchanged)
   if (tid == 0) grp[idx] = w;
 
-  // the sweep adds into this set's histogram and counter, the radix levels (should the
-  // interval miss) into theirs: clear them here
+  // the sweep adds into this set's histogram and counter: clear them here
   for (int i = tid; i < W; i += kSampleThreads) bhist[(size_t)idx * W + i] = 0;
-  clear_level_hists(hist, lp, gridDim.x, idx, tid, kSampleThreads);
   if (w.tokens == 0) {
     if (tid == 0) {
       Bracket e;
@@ -222,11 +219,11 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
 hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int G, int W,
                           const int* gid, const void* part, const Scalars& sc, int pass,
                           bool keep_base, GroupWork* grp, Bracket* br, unsigned* bhist,
-                          unsigned* hist, const LevelPlan& lp, hipStream_t st) {
+                          hipStream_t st) {
   hipLaunchKernelGGL(k_bracket, dim3(B * G), dim3(kSampleThreads), 0, st,
                      static_cast<const u16*>(X), ld, T, C, G, W, gid,
                      static_cast<const SetAcc*>(part), assign_split(T), sc, pass,
-                     keep_base ? 1 : 0, grp, br, bhist, hist, lp);
+                     keep_base ? 1 : 0, grp, br, bhist);
   return hipGetLastError();
 }
 
@@ -339,79 +336,162 @@ hipError_t launch_bracket_hist(const void* Xv, int B, int T_, int C, long long l
 }
 
 // ---------------------------------------------------------------------------
-// k_bracket_select
+// k_bracket_finish: one workgroup per set.  Its first wavefront verifies the interval
+// and, on a hit, finishes the set; on a miss the whole workgroup runs the exact
+// two-level radix select (8 + 7 key bits, LDS histogram) over the set's own rows.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_bracket_select(
-    const u32* __restrict__ bhist, int W, int force_miss, Scalars sc, int pass,
-    GroupWork* __restrict__ grp, const Bracket* __restrict__ br, float* __restrict__ clip,
-    float* __restrict__ scale, tdq_group_stats* __restrict__ stats,
+constexpr int kFinishThreads = 256;
+
+__global__ __launch_bounds__(kFinishThreads) void k_bracket_finish(
+    const u16* __restrict__ X, long long ld, int T, int C, int G, int vec_ok,
+    const int* __restrict__ gid, const u32* __restrict__ bhist, int W, int force_miss, Scalars sc,
+    int pass, GroupWork* __restrict__ grp, const Bracket* __restrict__ br,
+    float* __restrict__ clip, float* __restrict__ scale, tdq_group_stats* __restrict__ stats,
     const u32* __restrict__ img_flag, int B, u32* __restrict__ status) {
+  __shared__ u32 h[256];
+  __shared__ int list[kFinishThreads];
+  __shared__ u32 wtot[kFinishThreads / 64];
+  __shared__ u32 s_ok, s_digit;
+  __shared__ unsigned long long s_rem;
   const int idx = blockIdx.x;
-  const int lane = threadIdx.x;
-  if (idx == 0 && pass == kPassZr) {   // fold the per-image flags into the status word
+  const int b = idx / G, j = idx - b * G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (idx == 0 && wave == 0 && pass == kPassZr) {   // fold the per-image flags into the status word
     u32 f = 0;
-    for (int b = lane; b < B; b += 64) f |= img_flag[b];
+    for (int bb = lane; bb < B; bb += 64) f |= img_flag[bb];
     const unsigned long long any = __ballot(f != 0);
     if (lane == 0) status[0] = any ? TDQ_DEV_NONFINITE : 0u;
   }
   const GroupWork w = grp[idx];
   if (w.tokens == 0) {
-    if (lane == 0) {
-      if (pass == kPassZr) project_store(idx, w, 0u, true, sc, clip, scale, stats);
-      grp[idx].prefix = kResolved;
-    }
+    if (tid == 0 && pass == kPassZr) project_store(idx, w, 0u, true, sc, clip, scale, stats);
     return;
   }
-  bool ok = false;
-  unsigned long long need = 0, mine = 0, incl = 0;
-  const u32* h = bhist + (size_t)idx * W;
-  const int per = W / 64;                     // W is a multiple of 64
-  const int first = lane * per;
-  Bracket e;
-  e.lo = 0; e.width = 0; e.below = 0; e.pad = 0;
-  if (!force_miss) {
-    e = br[idx];
-    const unsigned long long k = (unsigned long long)w.k_rem;
-    for (int i = 0; i < per; ++i) mine += h[first + i];
-    incl = mine;                              // inclusive scan over lanes
+  if (wave == 0) {
+    bool ok = false;
+    unsigned long long need = 0, mine = 0, incl = 0;
+    const u32* hb = bhist + (size_t)idx * W;
+    const int per = W / 64;                     // W is a multiple of 64
+    const int first = lane * per;
+    Bracket e;
+    e.lo = 0; e.width = 0; e.below = 0; e.pad = 0;
+    if (!force_miss) {
+      e = br[idx];
+      const unsigned long long k = (unsigned long long)w.k_rem;
+      for (int i = 0; i < per; ++i) mine += hb[first + i];
+      incl = mine;                              // inclusive scan over lanes
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const unsigned long long o = __shfl_up(incl, d, 64);
-      if (lane >= d) incl += o;
+      for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+      }
+      const unsigned long long inside = __shfl(incl, 63, 64);
+      ok = k > e.below && k - e.below <= inside;
+      need = k - e.below;
     }
-    const unsigned long long inside = __shfl(incl, 63, 64);
-    ok = k > e.below && k - e.below <= inside;
-    need = k - e.below;
-  }
-  if (!ok) {                                  // wavefront-uniform
-    if (lane == 0) atomicAdd(&status[1 + pass], 1u);   // prefix stays 0, k_rem = k: radix levels take over
-    return;
-  }
-  const unsigned long long hit = __ballot(incl >= need);
-  const int src = __ffsll((long long)hit) - 1;          // hit != 0 because need <= inside
-  if (lane == src) {
-    unsigned long long cum = incl - mine;
-    int i = 0;
-    for (; i < per - 1; ++i) {
-      const unsigned long long c = h[first + i];
-      if (cum + c >= need) break;
-      cum += c;
+    if (ok) {                                   // wavefront-uniform
+      const unsigned long long hit = __ballot(incl >= need);
+      const int src = __ffsll((long long)hit) - 1;        // hit != 0 because need <= inside
+      if (lane == src) {
+        unsigned long long cum = incl - mine;
+        int i = 0;
+        for (; i < per - 1; ++i) {
+          const unsigned long long c = hb[first + i];
+          if (cum + c >= need) break;
+          cum += c;
+        }
+        const u32 key = e.lo + (u32)(first + i);
+        if (pass == kPassBase)
+          grp[idx].c_base = h2f(key);            // the set's base radius Q_p(|x|)
+        else
+          project_store(idx, w, key, true, sc, clip, scale, stats);
+      }
     }
-    const u32 key = e.lo + (u32)(first + i);
+    if (lane == 0) s_ok = ok ? 1u : 0u;
+  }
+  __syncthreads();
+  if (s_ok) return;
+
+  // The interval missed rank k (or the validation switch asked for this route).
+  if (tid == 0) atomicAdd(&status[1 + pass], 1u);
+  const int* gb = gid + (long long)b * T;
+  unsigned long long k = (unsigned long long)w.k_rem;
+  u32 prefix = 0;
+  const int nvec = vec_ok ? C / 8 : 0;
+  for (int level = 0; level < 2; ++level) {
+    const int shift = level == 0 ? 7 : 0;
+    const u32 mask = level == 0 ? 255u : 127u;
+    h[tid] = 0;                                 // kFinishThreads == 256 bins
+    __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += kFinishThreads) {
+      // the set's tokens among t0 .. t0 + 255, compacted into `list`
+      const int t = t0 + tid;
+      const bool match = t < T && gb[t] == j;
+      const unsigned long long m = __ballot(match);
+      if (lane == 0) wtot[wave] = (u32)__popcll(m);
+      __syncthreads();
+      u32 before = 0, n_list = 0;
+#pragma unroll
+      for (int w2 = 0; w2 < kFinishThreads / 64; ++w2) {
+        before += w2 < wave ? wtot[w2] : 0u;
+        n_list += wtot[w2];
+      }
+      if (match) list[before + (u32)__popcll(m & ((1ull << lane) - 1ull))] = t;
+      __syncthreads();
+      for (u32 i = wave; i < n_list; i += kFinishThreads / 64) {     // one wavefront per row
+        const u16* xp = X + ((long long)b * T + list[i]) * ld;
+        for (int v = lane; v < nvec; v += 64) {
+          const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * 8);
+          const u32 wd[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const u32 k0 = wd[c] & 0x7FFFu, k1 = (wd[c] >> 16) & 0x7FFFu;
+            if (level == 0 || (k0 >> 7) == prefix) atomicAdd(&h[(k0 >> shift) & mask], 1u);
+            if (level == 0 || (k1 >> 7) == prefix) atomicAdd(&h[(k1 >> shift) & mask], 1u);
+          }
+        }
+        for (int c = nvec * 8 + lane; c < C; c += 64) {
+          const u32 k0 = xp[c] & 0x7FFFu;
+          if (level == 0 || (k0 >> 7) == prefix) atomicAdd(&h[(k0 >> shift) & mask], 1u);
+        }
+      }
+      __syncthreads();                          // `list` and `wtot` are reused
+    }
+    if (tid == 0) {
+      unsigned long long cum = 0;
+      const int nb = level == 0 ? 256 : 128;
+      int bin = 0;
+      for (; bin < nb - 1; ++bin) {
+        if (cum + h[bin] >= k) break;
+        cum += h[bin];
+      }
+      s_digit = (u32)bin;
+      s_rem = k - cum;
+    }
+    __syncthreads();
+    prefix = level == 0 ? s_digit : ((prefix << 7) | s_digit);
+    k = s_rem;
+    __syncthreads();
+  }
+  if (tid == 0) {
     if (pass == kPassBase)
-      grp[idx].c_base = h2f(key);              // the set's base radius Q_p(|x|)
+      grp[idx].c_base = h2f(prefix);
     else
-      project_store(idx, w, key, true, sc, clip, scale, stats);
-    grp[idx].prefix = kResolved;
+      project_store(idx, w, prefix, true, sc, clip, scale, stats);
   }
 }
 
-hipError_t launch_bracket_select(const unsigned* bhist, int B, int G, int W, bool force_miss,
+hipError_t launch_bracket_finish(const void* Xv, int B, int T, int C, long long ld, int G, int W,
+                                 const int* gid, const unsigned* bhist, bool force_miss,
                                  const Scalars& sc, int pass, GroupWork* grp, const Bracket* br,
                                  float* clip, float* scale, tdq_group_stats* stats,
                                  const unsigned* img_flag, unsigned* status, hipStream_t st) {
-  hipLaunchKernelGGL(k_bracket_select, dim3(B * G), dim3(64), 0, st, bhist, W, force_miss ? 1 : 0,
-                     sc, pass, grp, br, clip, scale, stats, img_flag, B, status);
+  const u16* X = static_cast<const u16*>(Xv);
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0) ? 1 : 0;
+  hipLaunchKernelGGL(k_bracket_finish, dim3(B * G), dim3(kFinishThreads), 0, st, X, ld, T, C, G,
+                     vec_ok, gid, bhist, W, force_miss ? 1 : 0, sc, pass, grp, br, clip, scale, stats,
+                     img_flag, B, status);
   return hipGetLastError();
 }
 

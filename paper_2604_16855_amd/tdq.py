@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libtdq.so")
 
 TDQ_F16, TDQ_F32 = 0, 1
 FLAG_C1, FLAG_C2 = 1, 2
-FLAG_EXACT_SELECT = 256     # validation switch: rank select by the radix levels only
+FLAG_EXACT_SELECT = 256     # validation switch: rank select by the per-set radix select only
 DEV_NONFINITE = 1
 BIND_NAMES = ("base", "C1", "C2", "eps", "empty")
 
@@ -174,7 +174,7 @@ def device_status(workspace: torch.Tensor) -> int:
 
 def exact_select_sets(workspace: torch.Tensor) -> int:
     """How many token sets the last binary16 tdq_calibrate_groups resolved by the
-    radix levels because the sampled key interval missed their rank (synchronises)."""
+    per-set radix select because the sampled key interval missed their rank (synchronises)."""
     return int(workspace[4:12].view(torch.int32).sum().item())
 
 
