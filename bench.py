@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
 # HBM bytes per launch of the fc1 contraction on the default workload, from the
 # FETCH_SIZE + WRITE_SIZE counters (see profiles/bench_cfg4_hbm_traffic_pmc.txt)
-GEMM_FC1_TRAFFIC_BYTES = 1180809996
+GEMM_FC1_TRAFFIC_BYTES = 1181145339
 
 
 def parse():

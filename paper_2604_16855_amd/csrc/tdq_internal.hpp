@@ -38,8 +38,8 @@ struct Bracket {
 constexpr int kBracketLdsWords = 16384;   // 64 KiB of LDS histogram per workgroup (128 KiB, one
                                           // workgroup per CU, made the sweep 30 % slower)
 // Fewest one-key bins per set worth sampling for: with fewer the interval (half-width
-// bins / 2 keys, 1024 keys per octave) misses too often and the radix levels, which
-// then run anyway, are the cheaper route from the start.
+// bins / 2 keys, 1024 keys per octave) misses too often, and the multi-level radix
+// select over all sets at once is the cheaper route from the start.
 constexpr int kBracketMinBins = 256;
 
 // Bins per set of the interval histogram: the LDS budget shared out to G sets, rounded
