@@ -323,6 +323,26 @@ def w4a4_linear(qx: np.ndarray, row_scale: np.ndarray, qw: np.ndarray,
     return acc, Y
 
 
+def blocks_linear(codes: np.ndarray, block_scale: np.ndarray, g: int, qw: np.ndarray,
+                  w_scale: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """Algorithm 1, step 10, in the paper-literal setting: y = Linear(x_hat, W_hat)
+    with x_hat[m, i] = Delta[m, i // g] * q_x[m, i] (Eq. dequant, one step per block of
+    g channels of every token) and W_hat[n, i] = s_n * q_w[n, i] (Eq. weight_quant),
+    evaluated in binary64.
+
+    codes[M, K] int8, block_scale[M, ceil(K/g)] f32, qw[N, K] int8, w_scale[N] f32.
+    Returns Y[M, N] float64."""
+    codes = np.asarray(codes)
+    M, K = codes.shape
+    d = np.repeat(np.asarray(block_scale, dtype=np.float64), g, axis=1)[:, :K]
+    xhat = d * codes.astype(np.float64)
+    what = np.asarray(w_scale, dtype=np.float64)[:, None] * np.asarray(qw).astype(np.float64)
+    Y = xhat @ what.T
+    if bias is not None:
+        Y = Y + np.asarray(bias, dtype=np.float64)[None, :]
+    return Y
+
+
 def row_scales(gid: np.ndarray, scale: np.ndarray) -> np.ndarray:
     """Step of every row: scale[b, gid[b, t]] flattened to [B*T]."""
     B = gid.shape[0]

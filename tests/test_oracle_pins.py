@@ -382,6 +382,40 @@ def test_paper_literal_blocks():
     assert np.array_equal(clip0, base.astype(np.float32))
 
 
+def test_blocks_linear_against_scalar_loops_and_float_linear():
+    """Paper-literal linear: the vectorised binary64 form against (i) scalar triple loops
+    over the integer block sums, y = s_n sum_k Delta_mk sum_{i in k} q_x q_w, and (ii)
+    a plain float linear on the dequantized tensors that dstg_dcrp_blocks returns."""
+    rng = _rng(71)
+    X = rng.laplace(0, 1, (5, 80)).astype(np.float32)
+    W = rng.normal(0, 0.02, (6, 80)).astype(np.float32)
+    bias = rng.normal(0, 0.1, 6).astype(np.float32)
+    xhat, codes, clip, scale = O.dstg_dcrp_blocks(X, 32, P0)
+    qw, sw = O.quantize_weight(W)
+    Y = O.blocks_linear(codes, scale, 32, qw, sw, bias)
+    ref = np.zeros((5, 6))
+    for m in range(5):
+        for n in range(6):
+            tot = 0.0
+            for k in range(3):
+                acc = 0
+                for i in range(32 * k, min(32 * k + 32, 80)):
+                    acc += int(codes[m, i]) * int(qw[n, i])
+                tot += float(scale[m, k]) * acc
+            ref[m, n] = float(sw[n]) * tot + float(bias[n])
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-15)
+    what = sw[:, None].astype(np.float64) * qw
+    mag = np.abs(xhat).astype(np.float64) @ np.abs(what).T + np.abs(bias)   # x_hat is rounded to binary32
+    assert (np.abs(Y - (xhat.astype(np.float64) @ what.T + bias)) <= 2e-7 * mag).all()
+    # one block per row and a whole-row step: the hot-path form of the same linear
+    X1 = rng.laplace(0, 1, (4, 32)).astype(np.float32)
+    _, c1, _, s1 = O.dstg_dcrp_blocks(X1, 32, P0)
+    q1, w1 = O.quantize_weight(rng.normal(0, 0.02, (3, 32)).astype(np.float32))
+    _, Yhot = O.w4a4_linear(c1, s1[:, 0], q1, w1)
+    Yb = O.blocks_linear(c1, s1, 32, q1, w1)
+    assert (np.abs(Yb - Yhot) <= 2e-7 * np.abs(Yb) + 1e-30).all()
+
+
 def test_degenerate_groups():
     z = O.dcrp_group(np.zeros(16, np.float32), P0)
     assert z["clip"] == np.float32(1e-8) and z["scale"] == np.float32(1e-8)
