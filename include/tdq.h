@@ -60,11 +60,13 @@ typedef enum {
 #define TDQ_FLAG_EXACT_SELECT 256u
 
 #define TDQ_MAX_GROUPS 256
+#define TDQ_BLOCK 32 /* channel block g of the per-(token, block) entry points (Sec. 5 setup) */
 
 /* Hyper-parameters (Supp. "Default Hyperparameters": tau = 1.0, zr = 0.2). */
 typedef struct tdq_params {
   int32_t n_groups;   /* G token sets per image, 1..TDQ_MAX_GROUPS                */
-  int32_t chan_group; /* channel block g; 0 = whole row (the only value built)    */
+  int32_t chan_group; /* channel block g: 0 = whole row (token-set entry points),  */
+                      /* TDQ_BLOCK = the *_blocks entry points; else UNSUPPORTED   */
   int32_t act_bits;   /* 4                                                        */
   uint32_t flags;     /* TDQ_FLAG_C1 | TDQ_FLAG_C2 = DCRP; 0 = base radius only   */
   double tau;         /* > 0                                                      */
@@ -145,6 +147,26 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
 int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
                      const tdq_params* p, const int32_t* group_id, const float* clip,
                      const float* scale, uint8_t* Qx, int64_t ld_q, void* stream);
+
+/*
+ * The paper's own granularity (Sec. 4.2, Eq. direct_sum; Supp. Algorithm 1, steps 1-9) in
+ * one sweep of X: the channel axis of every token is zero-padded to KB = ceil(C / 32)
+ * blocks of g = TDQ_BLOCK channels and every (token, block) is a group of its own:
+ *   c_base = max |x| of the block (or the ceil(32 p)-th smallest for base_pct = p),
+ *   sigma  = population std of the block's 32 values + eps_std,
+ *   thr    = the ceil(32 zr)-th smallest |x| of the block,
+ *   c, Delta by Eq. (dcrp) and the eps floors, codes by Eqs. (clipx, dequant)
+ * with the arithmetic of tdq_calibrate_groups / tdq_quantize_act; the padding zeros count
+ * as values of the last block, as in Algorithm 1, and get no code.  p->chan_group must be
+ * TDQ_BLOCK; n_groups is ignored.  X must be finite (not checked here).
+ *
+ * X [B*T, ld_x] of dt.  Qx [B*T, ld_q] bytes out, ld_q >= ceil(C/2), bytes past
+ * ceil(C/2) of a row are not written.  block_scale [B*T, ld_s] out (Delta), block_clip
+ * [B*T, ld_s] out or NULL (c), ld_s >= KB in floats.  B*T*KB < 2^31.
+ */
+int tdq_quantize_act_blocks(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                            int64_t ld_x, const tdq_params* p, uint8_t* Qx, int64_t ld_q,
+                            float* block_scale, float* block_clip, int64_t ld_s, void* stream);
 
 /*
  * Diagnostics of the paper's Sec. 3.2 per (image, token set), as exact element counts

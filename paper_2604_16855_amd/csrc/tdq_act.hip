@@ -603,58 +603,8 @@ hipError_t launch_select(unsigned* hist_level, int B, int G, int, int bits, bool
 }
 
 // ---------------------------------------------------------------------------
-// K_c: quantize + pack.  q = clamp(rint(clip(x, +-c) / Delta), -8, 7).
-// The quotient is the correctly rounded binary32 one, obtained per element as
-//   y0 = x~ * r,  e = fma(-y0, Delta, x~),  y = fma(e, r, y0),   r = RN(1 / Delta)
-// (one reciprocal per row instead of one division per element).  Adding
-// 1.5 * 2^23 rounds y to an integer with ties to even and leaves its two's
-// complement in the low mantissa bits.
+// K_c: quantize + pack (the per-element arithmetic is in tdq_device.hpp).
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ u32 quant_nibble(float x, float c, float d, float rcp) {
-  const float xt = fminf(fmaxf(x, -c), c);
-  const float y0 = xt * rcp;
-  const float e = __builtin_fmaf(-y0, d, xt);
-  float y = __builtin_fmaf(e, rcp, y0);
-  y = fminf(fmaxf(y, (float)kQMin), (float)kQMax);
-  const float m = y + 12582912.0f;
-  return __float_as_uint(m) & 0xFu;
-}
-
-// Rounded quotient of one element as a float bit pattern whose low 4 bits are the
-// two's-complement code (see above).  CLAMP adds the clamp to [-8, 7], needed only
-// when the radii are not a projection's (c > 7.25 * Delta).
-template <bool CLAMP>
-__device__ __forceinline__ u32 quant_bits(float x, float c, float d, float rcp) {
-  const float xt = __builtin_amdgcn_fmed3f(x, -c, c);
-  const float y0 = xt * rcp;
-  const float e = __builtin_fmaf(-y0, d, xt);
-  float y = __builtin_fmaf(e, rcp, y0);
-  if (CLAMP) y = __builtin_amdgcn_fmed3f(y, (float)kQMin, (float)kQMax);
-  return __float_as_uint(y + 12582912.0f);
-}
-
-// Eight fp16 elements (one 16-byte load) -> eight packed codes.  The low bytes of
-// the eight results are gathered with byte permutes into a word of the even and a
-// word of the odd elements, which are then merged nibble-wise.
-template <bool CLAMP>
-__device__ __forceinline__ u32 quant8_f16(const uint4& q, float c, float d, float rcp) {
-  const u32 w[4] = {q.x, q.y, q.z, q.w};
-  u32 m[8];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const h2 h = __builtin_bit_cast(h2, w[j]);
-    m[2 * j] = quant_bits<CLAMP>((float)h[0], c, d, rcp);
-    m[2 * j + 1] = quant_bits<CLAMP>((float)h[1], c, d, rcp);
-  }
-  // v_perm_b32(s0, s1, sel): selector bytes 0-3 pick bytes of s1, 4-7 bytes of s0, 0x0c is zero
-  const u32 e02 = __builtin_amdgcn_perm(m[2], m[0], 0x0c0c0400u);   // [m0.b0, m2.b0, 0, 0]
-  const u32 e46 = __builtin_amdgcn_perm(m[6], m[4], 0x04000c0cu);   // [0, 0, m4.b0, m6.b0]
-  const u32 o13 = __builtin_amdgcn_perm(m[3], m[1], 0x0c0c0400u);
-  const u32 o57 = __builtin_amdgcn_perm(m[7], m[5], 0x04000c0cu);
-  const u32 ev = e02 | e46, od = (o13 | o57) << 4;
-  return (ev & 0x0F0F0F0Fu) | (od & 0xF0F0F0F0u);
-}
-
 // 16 bytes of X that nobody reads again after this sweep: a non-temporal load keeps
 // them from displacing the packed codes, which the contraction reads next (measured on
 // the 4096-channel layer of the largest configuration: this sweep 244 -> 205 us, and the

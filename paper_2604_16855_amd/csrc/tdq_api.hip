@@ -60,7 +60,9 @@ WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {
   return w;
 }
 
-static int check_params(const tdq_params* p) {
+// blocks = false: the token-set entry points (chan_group must be 0); true: the
+// per-(token, 32-channel block) entry points (chan_group must be 32).
+static int check_params(const tdq_params* p, bool blocks = false) {
   if (!p) return TDQ_ERR_NULL;
   if (p->n_groups < 1 || p->n_groups > TDQ_MAX_GROUPS) return TDQ_ERR_PARAM;
   if (p->act_bits != 4) return p->act_bits == 8 ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
@@ -68,7 +70,8 @@ static int check_params(const tdq_params* p) {
   if (!(p->tau > 0.0) || !isfinite(p->tau)) return TDQ_ERR_PARAM;
   if (!(p->zr > 0.0 && p->zr < 1.0)) return TDQ_ERR_PARAM;
   if (!(p->eps_scale > 0.f) || !(p->eps_std >= 0.f)) return TDQ_ERR_PARAM;
-  if (p->chan_group != 0) return p->chan_group > 0 ? TDQ_ERR_UNSUPPORTED : TDQ_ERR_PARAM;
+  if (p->chan_group < 0) return TDQ_ERR_PARAM;
+  if (p->chan_group != (blocks ? TDQ_BLOCK : 0)) return TDQ_ERR_UNSUPPORTED;
   if (!(p->base_pct >= 0.0 && p->base_pct <= 1.0)) return TDQ_ERR_PARAM;
   return TDQ_OK;
 }
@@ -233,6 +236,36 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
   if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
   if (launch_quantize(X, dt, B, T, C, ld_x, p->n_groups, group_id, clip, scale, Qx, ld_q,
                       static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+int tdq_quantize_act_blocks(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                            int64_t ld_x, const tdq_params* p, uint8_t* Qx, int64_t ld_q,
+                            float* block_scale, float* block_clip, int64_t ld_s, void* stream) {
+  if (!X || !p || !Qx || !block_scale) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p, true);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  const int64_t KB = ((int64_t)C + TDQ_BLOCK - 1) / TDQ_BLOCK;
+  if (ld_q < (C + 1) / 2 || ld_s < KB) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T * KB >= (int64_t)1 << 31) return TDQ_ERR_SHAPE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(block_scale) | reinterpret_cast<uintptr_t>(block_clip)) & 3)
+    return TDQ_ERR_ALIGN;
+  // ranks among the g values of a block, padding zeros included (binary64, as everywhere)
+  auto rank_of = [](double frac) {
+    long long k = (long long)ceil(frac * (double)TDQ_BLOCK);
+    return (int)(k < 1 ? 1 : (k > TDQ_BLOCK ? TDQ_BLOCK : k));
+  };
+  const int kq = rank_of(p->zr);
+  const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? rank_of(p->base_pct) : TDQ_BLOCK;
+  if (launch_quantize_blocks(X, dt, (long long)B * T, C, ld_x, kq, kp, make_scalars(p), Qx, ld_q,
+                             block_scale, block_clip, ld_s,
+                             static_cast<hipStream_t>(stream)) != hipSuccess)
     return TDQ_ERR_HIP;
   return TDQ_OK;
 }

@@ -135,6 +135,9 @@ hipError_t launch_bracket_finish(const void* X, int B, int T, int C, long long l
 hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                            const int* gid, const float* clip, const float* scale, uint8_t* Q,
                            long long ld_q, hipStream_t st);
+hipError_t launch_quantize_blocks(const void* X, tdq_dtype dt, long long M, int C, long long ld,
+                                  int kq, int kp, const Scalars& sc, uint8_t* Q, long long ld_q,
+                                  float* bscale, float* bclip, long long ld_s, hipStream_t st);
 hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                              const int* gid, const float* clip, const float* scale,
                              unsigned long long* zero_count, unsigned long long* clipped_count,

@@ -78,6 +78,9 @@ def lib() -> C.CDLL:
     L.tdq_w4a4_linear.restype = C.c_int
     L.tdq_w4a4_linear.argtypes = [vp, i64, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp, vp, vp,
                                   C.c_int, i64, vp, vp]
+    L.tdq_quantize_act_blocks.restype = C.c_int
+    L.tdq_quantize_act_blocks.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp,
+                                          i64, vp, vp, i64, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -204,6 +207,35 @@ def tdq_quantize_act(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],
                                 _stream())
     _check(rc, "tdq_quantize_act")
     return out
+
+
+BLOCK = 32                  # TDQ_BLOCK: channel block of the per-(token, block) entry points
+
+
+def block_params(tau: float = 1.0, zr: float = 0.2, flags: int = FLAG_C1 | FLAG_C2,
+                 base_pct: float = 0.0) -> Params:
+    """tdq_params for the *_blocks entry points (chan_group = TDQ_BLOCK)."""
+    p = default_params(1, tau, zr, flags)
+    p.chan_group, p.base_pct = BLOCK, base_pct
+    return p
+
+
+def tdq_quantize_act_blocks(X: torch.Tensor, p: Params, want_clip: bool = False,
+                            out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+    """-> (Qx[B*T, ld_q] uint8 packed codes, block_scale[B*T, KB] f32, block_clip or None),
+    KB = ceil(C / 32): one step per (token, 32-channel block)."""
+    B, T, Cc, ld = _btc(X)
+    KB = (Cc + BLOCK - 1) // BLOCK
+    if out is None:
+        Qx = torch.zeros((B * T, packed_row_bytes(Cc)), dtype=torch.uint8, device=X.device)
+        bs = torch.empty((B * T, KB), dtype=torch.float32, device=X.device)
+    else:
+        Qx, bs = out
+    bc = torch.empty((B * T, KB), dtype=torch.float32, device=X.device) if want_clip else None
+    rc = lib().tdq_quantize_act_blocks(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p), Qx.data_ptr(),
+                                       Qx.stride(0), bs.data_ptr(), _ptr(bc), bs.stride(0), _stream())
+    _check(rc, "tdq_quantize_act_blocks")
+    return Qx, bs, bc
 
 
 def tdq_group_diagnostics(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],

@@ -24,6 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
+            "tdq_quantize_act_blocks",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -123,6 +124,35 @@ def test_quantize_and_linear_reject_bad_arguments():
     assert w(None, 8, 8, 8, FAKE, 4, FAKE, None) == tdq.ERR_NULL
     assert w(FAKE, 8, 8, 4, FAKE, 4, FAKE, None) == tdq.ERR_SHAPE
     assert w(FAKE, 8, 8, 8, FAKE, 3, FAKE, None) == tdq.ERR_SHAPE
+
+
+def test_block_quantizer_rejects_bad_arguments():
+    L = tdq.lib()
+    f = L.tdq_quantize_act_blocks
+    p = tdq.block_params()
+
+    def call(q=None, X=FAKE, dt=0, B=1, T=8, Cc=40, ld=40, Q=FAKE, ld_q=20, bs=FAKE, bc=None,
+             ld_s=2):
+        return f(X, dt, B, T, Cc, ld, C.byref(q or p), Q, ld_q, bs, bc, ld_s, None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(Q=None) == tdq.ERR_NULL
+    assert call(bs=None) == tdq.ERR_NULL
+    assert call(dt=3) == tdq.ERR_DTYPE
+    assert call(T=0) == tdq.ERR_SHAPE
+    assert call(ld=39) == tdq.ERR_SHAPE
+    assert call(ld_q=19) == tdq.ERR_SHAPE          # 40 codes need 20 bytes
+    assert call(ld_s=1) == tdq.ERR_SHAPE           # 40 channels are 2 blocks
+    assert call(B=1 << 15, T=1 << 15, Cc=64, ld=64, ld_q=32) == tdq.ERR_SHAPE   # 2^31 blocks
+    assert call(X=FAKE + 1) == tdq.ERR_ALIGN
+    assert call(bs=FAKE + 2) == tdq.ERR_ALIGN
+    assert call(q=tdq.default_params()) == tdq.ERR_UNSUPPORTED       # chan_group 0: the token-set path
+    for field, val, err in (("chan_group", 16, tdq.ERR_UNSUPPORTED), ("chan_group", -1, tdq.ERR_PARAM),
+                            ("zr", 0.0, tdq.ERR_PARAM), ("tau", -1.0, tdq.ERR_PARAM),
+                            ("base_pct", 2.0, tdq.ERR_PARAM), ("act_bits", 8, tdq.ERR_UNSUPPORTED)):
+        q = tdq.block_params()
+        setattr(q, field, val)
+        assert call(q=q) == err, (field, val)
 
 
 def test_bench_refuses_more_than_one_gpu():

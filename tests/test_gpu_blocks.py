@@ -1,0 +1,159 @@
+"""GPU parity of the paper-literal granularity (one group per token and block of 32
+channels; Sec. 4.2, Supp. Algorithm 1) against the CPU oracle: the fused block quantizer
+and the block-scaled contraction, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tdq_oracle as O
+from paper_2604_16855_amd import inputs as I
+from paper_2604_16855_amd import tdq
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+G_BLK = 32
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _oracle_params(p):
+    return O.Params(n_groups=1, flags=p.flags & 3, tau=p.tau, zr=p.zr, base_pct=p.base_pct)
+
+
+def _blocks_view(a, C):
+    """[M, C] -> [M * KB, 32], the channel axis zero-padded to whole blocks."""
+    M = a.shape[0]
+    KB = -(-C // G_BLK)
+    out = np.zeros((M, KB * G_BLK), dtype=a.dtype)
+    out[:, :C] = a
+    return out.reshape(M * KB, G_BLK)
+
+
+def _check_block_quantizer(X, p, ld_pad=0):
+    """X[B, T, C]: radii, steps and codes of every (token, block) against the oracle."""
+    B, T, C = X.shape
+    KB = -(-C // G_BLK)
+    _say(f"[blocks] B={B} T={T} C={C} dtype={X.dtype} flags={p.flags} tau={p.tau} zr={p.zr} "
+         f"base_pct={p.base_pct} ld_pad={ld_pad}")
+    Xd = U.to_device(X, ld_pad)
+    Q, bs, bc = tdq.tdq_quantize_act_blocks(Xd, p, want_clip=True)
+    torch.cuda.synchronize()
+    _, q_ref, clip, scale = O.dstg_dcrp_blocks(X.reshape(B * T, C), G_BLK, _oracle_params(p))
+    clip_g, scale_g = bc.cpu().numpy(), bs.cpu().numpy()
+    assert clip_g.shape == (B * T, KB)
+    if not (p.flags & tdq.FLAG_C1):
+        # without the dispersion bound every radius is an element of the data times an
+        # exact constant: bit-exact, and so are the steps and the codes
+        assert np.array_equal(clip_g, clip), "clip radii differ (order statistics)"
+        assert np.array_equal(scale_g, scale)
+    assert np.allclose(clip_g, clip, rtol=U.SCALE_RTOL, atol=0), "clip radii differ"
+    assert np.allclose(scale_g, scale, rtol=U.SCALE_RTOL, atol=0), "steps differ"
+    q_gpu = U.unpack_device_codes(Q, C)
+    exact = np.array_equal(clip_g, clip) and np.array_equal(scale_g, scale)
+    flips = U.assert_codes_match(_blocks_view(q_gpu, C), _blocks_view(q_ref, C),
+                                 _blocks_view(X.reshape(B * T, C).astype(np.float32), C),
+                                 clip.reshape(-1), scale.reshape(-1), exact)
+    if C % 2:      # the pad nibble of an odd row is zero
+        assert not (Q.cpu().numpy()[:, C // 2] >> 4).any()
+    _say(f"  scales bit-identical: {exact}; code flips: {flips}")
+    return Q, bs, q_gpu, scale_g
+
+
+def _acts(name, B, T, C=None, dtype=None):
+    """Activations of a named workload cut to [B, T, C]."""
+    kw = dict(B=B)
+    if dtype:
+        kw["dtype"] = dtype
+    lc = I.case(name, **kw)
+    X, _ = I.make_activations(lc)
+    C = C or lc.C
+    return np.ascontiguousarray(X[:, :T, :C])
+
+
+@pytest.mark.parametrize("name,B,T,C", [("cfg2_fc2", 2, 300, None), ("cfg2_qkv", 1, 484, None),
+                                        ("cfg4_fc1_h10", 1, 150, 1024), ("cfg4_fc2_h10", 1, 40, 4096)])
+def test_block_quantizer_on_workloads(name, B, T, C):
+    _check_block_quantizer(_acts(name, B, T, C), tdq.block_params())
+
+
+@pytest.mark.parametrize("B,T,C,dtype,ld_pad", [
+    (1, 77, 80, np.float16, 0),      # last block half padding
+    (1, 1000, 33, np.float16, 0),    # odd C, one real channel in the last block
+    (1, 5, 7, np.float16, 0),        # less than one lane's share
+    (3, 50, 4100, np.float16, 0),    # rows not a multiple of 16 bytes apart -> scalar loads
+    (2, 64, 1024, np.float16, 8),    # padded row stride, still aligned
+    (2, 33, 96, np.float16, 3),      # padded row stride, unaligned
+    (1, 1, 32, np.float16, 0),       # one block
+    (1, 200, 96, np.float32, 0),
+    (2, 64, 1000, np.float32, 0),
+    (1, 31, 45, np.float32, 5),
+])
+def test_block_quantizer_ragged_shapes(B, T, C, dtype, ld_pad):
+    rng = np.random.Generator(np.random.PCG64([B, T, C, 5]))
+    # heavy-tailed rows: Gaussian bulk, a few large channels, per-token range spread
+    X = rng.standard_normal((B, T, C)) * np.exp(rng.normal(0, 1.5, (B, T, 1)))
+    X[rng.random((B, T, C)) < 0.02] *= 30.0
+    _check_block_quantizer(X.astype(dtype), tdq.block_params(), ld_pad)
+
+
+@pytest.mark.parametrize("flags,tau,zr,base_pct", [
+    (0, 1.0, 0.2, 0.0),       # DSTG only: max-abs radii
+    (1, 0.3, 0.2, 0.0),       # C1 only
+    (2, 1.0, 0.2, 0.0),       # C2 only: every radius an order statistic (rank 7)
+    (2, 1.0, 0.01, 0.0),      # rank 1: the block minimum
+    (2, 1.0, 0.25, 0.0),      # rank 8: last rank of the sorting-network route
+    (2, 1.0, 0.26, 0.0),      # rank 9: first rank of the bisection route
+    (2, 1.0, 0.6, 0.0),       # rank 20
+    (2, 1.0, 0.99, 0.0),      # rank 32: the maximum
+    (3, 2.0, 0.1, 0.0),
+    (0, 1.0, 0.2, 0.9),       # percentile base radius, rank 29
+    (3, 1.0, 0.2, 0.5),       # rank 16 base with both bounds
+])
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_block_quantizer_variants(flags, tau, zr, base_pct, dtype):
+    X = _acts("cfg2_fc2", 1, 160).astype(dtype)
+    _check_block_quantizer(X, tdq.block_params(tau, zr, flags, base_pct))
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_block_quantizer_degenerate_blocks(dtype):
+    """All-zero blocks (eps floors), constant blocks (sigma = eps_std), ties at the rank,
+    a single non-zero, subnormal magnitudes, the largest finite values."""
+    rng = np.random.Generator(np.random.PCG64(11))
+    T, C = 64, 256
+    X = rng.standard_normal((1, T, C)).astype(np.float32)
+    X[0, 0] = 0.0
+    X[0, 1] = 3.25
+    X[0, 2] = 0.0
+    X[0, 2, 5::32] = -2.5                                  # one non-zero per block
+    X[0, 3] = np.where(rng.random(C) < 0.5, 1.0, -1.0)     # all magnitudes tie
+    X[0, 4] = rng.integers(-2, 3, C)                       # many ties around the rank
+    tiny = 6e-8 if dtype == np.float16 else 1e-40
+    X[0, 5] = tiny * rng.integers(-5, 6, C)                # subnormals
+    big = 65504.0 if dtype == np.float16 else 1.0e37
+    X[0, 6, ::7] = big
+    X[0, 7, :32] = 0.0
+    X[0, 7, 31] = 1.0
+    for flags in (3, 2, 0):
+        _check_block_quantizer(X.astype(dtype), tdq.block_params(flags=flags))
+
+
+def test_block_quantizer_repeatable_and_order_free():
+    """Bitwise repeatable, and a block's result does not depend on where the block sits:
+    permuting tokens permutes the outputs."""
+    X = _acts("cfg2_fc2", 2, 200)
+    p = tdq.block_params()
+    Xd = U.to_device(X)
+    Q1, s1, _ = tdq.tdq_quantize_act_blocks(Xd, p)
+    Q2, s2, _ = tdq.tdq_quantize_act_blocks(Xd, p)
+    perm = torch.randperm(X.shape[1], generator=torch.Generator().manual_seed(3)).to(U.dev())
+    Q3, s3, _ = tdq.tdq_quantize_act_blocks(Xd[:, perm].contiguous(), p)
+    torch.cuda.synchronize()
+    assert torch.equal(Q1, Q2) and torch.equal(s1, s2)
+    T = X.shape[1]
+    idx = torch.cat([perm + b * T for b in range(X.shape[0])])
+    assert torch.equal(Q1[idx], Q3) and torch.equal(s1[idx], s3)
