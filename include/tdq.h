@@ -201,6 +201,24 @@ int tdq_w4a4_linear(const uint8_t* Qx, int64_t ld_q, const int32_t* group_id, co
                     tdq_dtype y_dt, int64_t ld_y, int32_t* acc_dump, void* stream);
 
 /*
+ * The linear of Supp. Algorithm 1, step 10, on the codes of tdq_quantize_act_blocks:
+ *   acc_kb[m, n] = sum over the 32 codes i of block kb of Qx[m, i] * Qw[n, i]   (exact)
+ *   f[m, n]      = sum_kb float(acc_kb[m, n]) * Delta[m, kb]
+ *   Y[m, n]      = f[m, n] * w_scale[n] (+ bias[n])
+ * f is accumulated in binary32 with one fused multiply-add per block, kb ascending, so
+ * the result is repeatable bit for bit and differs from the exact sum by at most
+ * (KB + 2) 2^-24 sum_kb |acc_kb Delta| w_scale.
+ *
+ * Qx [M, ld_q], Qw [N, ld_w] packed codes with the alignment rules of tdq_w4a4_linear;
+ * block_scale [M, ld_s] floats, ld_s >= KB = ceil(K / 32); Y [M, ld_y] of y_dt;
+ * bias [N] or NULL.
+ */
+int tdq_w4a4_linear_blocks(const uint8_t* Qx, int64_t ld_q, const float* block_scale, int64_t ld_s,
+                           int64_t M, int32_t K, int32_t N, const uint8_t* Qw, int64_t ld_w,
+                           const float* w_scale, const float* bias, void* Y, tdq_dtype y_dt,
+                           int64_t ld_y, void* stream);
+
+/*
  * Static symmetric per-output-channel weight quantization (Eq. weight_quant),
  * done once offline:  s_o = max(max_i |W_oi|, 1e-8) / 7,
  * Qw = clamp(rint(W / s_o), -8, 7) packed.  W [N, K] fp32 (device),

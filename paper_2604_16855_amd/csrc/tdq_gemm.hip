@@ -856,4 +856,230 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Block-scaled contraction for the paper-literal granularity (Supp. Algorithm 1, step 10
+// with one step Delta[m, kb] per token m and block kb of g = 32 channels):
+//   Y[m, n] = s_w[n] * sum_kb Delta[m, kb] * acc_kb[m, n],
+//   acc_kb[m, n] = sum_{i in block kb} Qx[m, i] * Qw[n, i]   (|acc_kb| <= 32 * 64)
+// The int32 accumulation cannot run over the whole of K any more: one matrix
+// instruction (K = 32) is exactly one block, and its 16 results per lane are converted
+// and folded into a binary32 accumulator with the block's step,
+//   f <- fma(float(acc_kb), Delta[m, kb], f),   kb ascending,
+// i.e. 32 vector operations per matrix instruction: this kernel is bound by the vector
+// unit, not by the matrix cores (which idle three quarters of the time).  The factor 256
+// of the nibble expansion is taken out once at the end (a power of two: exact).
+//
+// Workgroup = 2 x 2 wavefronts, wavefront tile 64 x 64, 128 x 128 per workgroup; a stage
+// is 64 packed bytes (4 blocks) of K per row, register-staged and double-buffered.
+// LDS rows are 72 bytes apart: the 8-byte fragment reads of 32 consecutive rows then
+// fall on 32 different bank pairs.  The steps of a stage sit in LDS block-major so
+// that the 4 consecutive rows a lane owns are one 16-byte read.
+// ---------------------------------------------------------------------------
+constexpr int BLK_STRIDE = BKB + 8;
+
+template <typename OUT>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
+    const uint8_t* __restrict__ Qx, long long ld_q, const float* __restrict__ bscale, long long ld_s,
+    int M, int K, int N, const uint8_t* __restrict__ Qw, long long ld_w,
+    const float* __restrict__ w_scale, const float* __restrict__ bias, OUT* __restrict__ Y,
+    long long ld_y, int m_tiles, int n_tiles) {
+  constexpr int MT = 2, NT = 2, BM = 128, BN = 128, SB = BKB / 16;   // SB blocks per stage
+  __shared__ __attribute__((aligned(16))) uint8_t sA[2][BM * BLK_STRIDE];
+  __shared__ __attribute__((aligned(16))) uint8_t sB[2][BN * BLK_STRIDE];
+  __shared__ __attribute__((aligned(16))) float sD[2][SB][BM];
+  __shared__ float sCol[BN], sBias[BN];
+
+  const int bid = blockIdx.x;
+  const int xcd = bid % XCDS, idx = bid / XCDS;
+  const int m_tile = (idx / n_tiles) * XCDS + xcd;
+  const int n_tile = idx % n_tiles;
+  if (m_tile >= m_tiles) return;
+  const int m0 = m_tile * BM, n0 = n_tile * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int kbytes = (K + 1) / 2;
+  const int KB = (K + 31) / 32;
+  const int k_tiles = (kbytes + BKB - 1) / BKB;
+
+  for (int j = tid; j < BN; j += GEMM_THREADS) {
+    const int n = n0 + j;
+    sCol[j] = n < N ? w_scale[n] : 0.f;
+    sBias[j] = (bias && n < N) ? bias[n] : 0.f;
+  }
+
+  // staging: thread t owns the 16-byte piece (t & 3) of rows (t >> 2) + 64 i of both
+  // operands, and threads 0..127 the SB steps of row t
+  const int pr0 = tid >> 2, pc = (tid & 3) * 16;
+  const uint8_t* pa[MT];
+  const uint8_t* pb[NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int r = m0 + pr0 + 64 * i;
+    r = r < M ? r : M - 1;
+    pa[i] = Qx + (long long)r * ld_q + pc;
+  }
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    int r = n0 + pr0 + 64 * j;
+    r = r < N ? r : N - 1;
+    pb[j] = Qw + (long long)r * ld_w + pc;
+  }
+  const bool d_owner = tid < BM;
+  const bool d_row_ok = d_owner && m0 + tid < M;
+  const float* pd = bscale + (long long)(m0 + (d_row_ok ? tid : 0)) * ld_s;
+
+  uint4 ga[MT], gb[NT];
+  float gd[SB];
+  auto load_stage = [&](int kt) {
+    const int kb = kt * BKB + pc;          // first packed byte of this piece
+    if (kb < kbytes) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        ga[i] = *reinterpret_cast<const uint4*>(pa[i] + (long long)kt * BKB);
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        gb[j] = *reinterpret_cast<const uint4*>(pb[j] + (long long)kt * BKB);
+      if (kb + 16 > kbytes) {              // piece straddles the end of the row: zero the rest
+        const int keep = kbytes - kb;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) mask_piece(ga[i], keep);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) mask_piece(gb[j], keep);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) ga[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) gb[j] = make_uint4(0, 0, 0, 0);
+    }
+    if (d_owner) {
+      // Four 4-byte loads, not one of 16 bytes: every lane reads its own row here, and a
+      // 16-byte load whose 64 lanes fall on 64 different 128-byte lines was measured to
+      // slow the whole kernel down tenfold on this chip.
+      const int b0 = kt * SB;              // first block of the stage
+#pragma unroll
+      for (int j = 0; j < SB; ++j) gd[j] = (d_row_ok && b0 + j < KB) ? pd[b0 + j] : 0.f;
+    }
+  };
+  auto store_stage = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      uint2* d = reinterpret_cast<uint2*>(&sA[buf][(pr0 + 64 * i) * BLK_STRIDE + pc]);
+      d[0] = make_uint2(ga[i].x, ga[i].y);
+      d[1] = make_uint2(ga[i].z, ga[i].w);
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      uint2* d = reinterpret_cast<uint2*>(&sB[buf][(pr0 + 64 * j) * BLK_STRIDE + pc]);
+      d[0] = make_uint2(gb[j].x, gb[j].y);
+      d[1] = make_uint2(gb[j].z, gb[j].w);
+    }
+    if (d_owner) {
+#pragma unroll
+      for (int j = 0; j < SB; ++j) sD[buf][j][tid] = gd[j];
+    }
+  };
+
+  float accf[MT][NT][16];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) accf[i][j][r] = 0.f;
+
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+
+  // Lane l feeds row (l & 31) of a 32-row fragment and, of each 16-byte block of K, the
+  // 8 bytes at offset 8 (l >> 5); it owns column l & 31 and rows 8 q + 4 (l >> 5) + 0..3,
+  // q = 0..3, of every 32 x 32 result.
+  const int frow = lane & 31, fhalf = (lane >> 5) * 8;
+  const int a_off = (wm * 32 * MT + frow) * BLK_STRIDE + fhalf;
+  const int b_off = (wn * 32 * NT + frow) * BLK_STRIDE + fhalf;
+  const int d_off = wm * 32 * MT + (lane >> 5) * 4;
+  const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  for (int kt = 0; kt < k_tiles; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < k_tiles) load_stage(kt + 1);
+    // one block at a time: unrolled further, the loads of all four blocks are hoisted and
+    // the accumulators spill
+#pragma unroll 1
+    for (int kb = 0; kb < SB; ++kb) {
+      v4i a[MT], b[NT];
+      float dl[MT][16];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const uint2 f = *reinterpret_cast<const uint2*>(&sA[cur][a_off + i * 32 * BLK_STRIDE + kb * 16]);
+        a[i] = expand(f.x, f.y);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 d4 = *reinterpret_cast<const float4*>(&sD[cur][kb][d_off + i * 32 + q * 8]);
+          dl[i][4 * q] = d4.x; dl[i][4 * q + 1] = d4.y; dl[i][4 * q + 2] = d4.z; dl[i][4 * q + 3] = d4.w;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const uint2 f = *reinterpret_cast<const uint2*>(&sB[cur][b_off + j * 32 * BLK_STRIDE + kb * 16]);
+        b[j] = expand(f.x, f.y);
+      }
+      v16i t[MT][NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          t[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], zero, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            accf[i][j][r] = __builtin_fmaf((float)t[i][j][r], dl[i][r], accf[i][j][r]);
+    }
+    if (kt + 1 < k_tiles) store_stage(cur ^ 1);
+    __syncthreads();
+  }
+
+  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rl = wm * 32 * MT + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
+      const int m = m0 + rl;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int cl = wn * 32 * NT + j * 32 + ccol;
+        const int n = n0 + cl;
+        if (m < M && n < N) {
+          float y = (accf[i][j][r] * 0.00390625f) * sCol[cl];
+          if (bias) y = y + sBias[cl];
+          store_out<OUT>(Y + (long long)m * ld_y + n, y);
+        }
+      }
+    }
+}
+
+hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const float* bscale,
+                                   long long ld_s, int M, int K, int N, const uint8_t* Qw,
+                                   long long ld_w, const float* w_scale, const float* bias, void* Y,
+                                   tdq_dtype y_dt, long long ld_y, hipStream_t st) {
+  const int m_tiles = (M + 127) / 128, n_tiles = (N + 127) / 128;
+  const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
+  const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
+  if (y_dt == TDQ_F32)
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks<float>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q,
+                       bscale, ld_s, M, K, N, Qw, ld_w, w_scale, bias, static_cast<float*>(Y), ld_y,
+                       m_tiles, n_tiles);
+  else
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks<_Float16>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx,
+                       ld_q, bscale, ld_s, M, K, N, Qw, ld_w, w_scale, bias,
+                       static_cast<_Float16*>(Y), ld_y, m_tiles, n_tiles);
+  return hipGetLastError();
+}
+
 }  // namespace tdq

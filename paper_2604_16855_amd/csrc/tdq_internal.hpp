@@ -138,6 +138,10 @@ hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, lon
 hipError_t launch_quantize_blocks(const void* X, tdq_dtype dt, long long M, int C, long long ld,
                                   int kq, int kp, const Scalars& sc, uint8_t* Q, long long ld_q,
                                   float* bscale, float* bclip, long long ld_s, hipStream_t st);
+hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const float* bscale,
+                                   long long ld_s, int M, int K, int N, const uint8_t* Qw,
+                                   long long ld_w, const float* w_scale, const float* bias, void* Y,
+                                   tdq_dtype y_dt, long long ld_y, hipStream_t st);
 hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                              const int* gid, const float* clip, const float* scale,
                              unsigned long long* zero_count, unsigned long long* clipped_count,

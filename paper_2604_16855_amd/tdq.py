@@ -81,6 +81,9 @@ def lib() -> C.CDLL:
     L.tdq_quantize_act_blocks.restype = C.c_int
     L.tdq_quantize_act_blocks.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp,
                                           i64, vp, vp, i64, vp]
+    L.tdq_w4a4_linear_blocks.restype = C.c_int
+    L.tdq_w4a4_linear_blocks.argtypes = [vp, i64, vp, i64, i64, i32, i32, vp, i64, vp, vp, vp,
+                                         C.c_int, i64, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -236,6 +239,22 @@ def tdq_quantize_act_blocks(X: torch.Tensor, p: Params, want_clip: bool = False,
                                        Qx.stride(0), bs.data_ptr(), _ptr(bc), bs.stride(0), _stream())
     _check(rc, "tdq_quantize_act_blocks")
     return Qx, bs, bc
+
+
+def tdq_w4a4_linear_blocks(Qx: torch.Tensor, block_scale: torch.Tensor, K: int, Qw: torch.Tensor,
+                           w_scale: torch.Tensor, bias: Optional[torch.Tensor] = None,
+                           out_dtype=torch.float32, out: Optional[torch.Tensor] = None
+                           ) -> torch.Tensor:
+    """-> Y[M, N] from block-quantized activations: one step per (row, 32-code block)."""
+    M, N = Qx.shape[0], Qw.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=Qx.device)
+    rc = lib().tdq_w4a4_linear_blocks(Qx.data_ptr(), Qx.stride(0), block_scale.data_ptr(),
+                                      block_scale.stride(0), M, K, N, Qw.data_ptr(), Qw.stride(0),
+                                      w_scale.data_ptr(), _ptr(bias), out.data_ptr(), _dt(out),
+                                      out.stride(0), _stream())
+    _check(rc, "tdq_w4a4_linear_blocks")
+    return out
 
 
 def tdq_group_diagnostics(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],

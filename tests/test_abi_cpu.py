@@ -24,7 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
-            "tdq_quantize_act_blocks",
+            "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -153,6 +153,29 @@ def test_block_quantizer_rejects_bad_arguments():
         q = tdq.block_params()
         setattr(q, field, val)
         assert call(q=q) == err, (field, val)
+
+
+def test_block_linear_rejects_bad_arguments():
+    g = tdq.lib().tdq_w4a4_linear_blocks
+    ok = dict(Qx=FAKE, ld_q=32, bs=FAKE, ld_s=2, M=8, K=64, N=8, Qw=FAKE, ld_w=32, ws=FAKE,
+              bias=None, Y=FAKE, ydt=1, ld_y=8, st=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return g(a["Qx"], a["ld_q"], a["bs"], a["ld_s"], a["M"], a["K"], a["N"], a["Qw"], a["ld_w"],
+                 a["ws"], a["bias"], a["Y"], a["ydt"], a["ld_y"], a["st"])
+
+    assert call(Qx=None) == tdq.ERR_NULL
+    assert call(bs=None) == tdq.ERR_NULL
+    assert call(M=0) == tdq.ERR_SHAPE
+    assert call(K=200000) == tdq.ERR_SHAPE
+    assert call(ld_s=1) == tdq.ERR_SHAPE           # 64 codes are 2 blocks
+    assert call(ld_q=16) == tdq.ERR_SHAPE
+    assert call(ld_w=40) == tdq.ERR_ALIGN
+    assert call(bs=FAKE + 2) == tdq.ERR_ALIGN
+    assert call(Qx=FAKE + 8) == tdq.ERR_ALIGN
+    assert call(ld_y=7) == tdq.ERR_SHAPE
+    assert call(ydt=2) == tdq.ERR_DTYPE
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -157,3 +157,155 @@ def test_block_quantizer_repeatable_and_order_free():
     T = X.shape[1]
     idx = torch.cat([perm + b * T for b in range(X.shape[0])])
     assert torch.equal(Q1[idx], Q3) and torch.equal(s1[idx], s3)
+
+
+# ---------------------------------------------------------------- block-scaled contraction
+def _blocks_linear_bound(codes, bscale, qw, w_scale, bias, KB):
+    """Error bound of the binary32 evaluation: one rounding per block and three in the
+    epilogue, each relative to sum_kb |acc_kb Delta| s_n (+ |bias|)."""
+    M, K = codes.shape
+    S = np.zeros((M, qw.shape[0]))
+    for kb in range(KB):
+        sl = slice(kb * G_BLK, min((kb + 1) * G_BLK, K))
+        acc = codes[:, sl].astype(np.int64) @ qw[:, sl].astype(np.int64).T
+        S += np.abs(acc) * bscale[:, kb].astype(np.float64)[:, None]
+    S *= w_scale.astype(np.float64)[None, :]
+    if bias is not None:
+        S += np.abs(bias.astype(np.float64))[None, :]
+    return (KB + 3) * 2.0 ** -24 * S + 1e-37
+
+
+def _check_blocks_linear(codes, bscale, qw, w_scale, bias, out_dtype=torch.float32, ld_s_pad=0):
+    M, K = codes.shape
+    N = qw.shape[0]
+    KB = -(-K // G_BLK)
+    _say(f"[blocks-linear] M={M} K={K} N={N} bias={bias is not None} out={out_dtype} "
+         f"ld_s_pad={ld_s_pad}")
+    Qx_d = U.pack_to_device(codes)
+    Qw_d = U.pack_to_device(qw)
+    bs_buf = torch.full((M, KB + ld_s_pad), float("nan"), dtype=torch.float32)
+    bs_buf[:, :KB] = torch.from_numpy(bscale)
+    bs_d = bs_buf.to(U.dev())[:, :KB]
+    ws_d = torch.from_numpy(w_scale).to(U.dev())
+    bias_d = None if bias is None else torch.from_numpy(bias).to(U.dev())
+    Y = tdq.tdq_w4a4_linear_blocks(Qx_d, bs_d, K, Qw_d, ws_d, bias_d, out_dtype)
+    Y2 = tdq.tdq_w4a4_linear_blocks(Qx_d, bs_d, K, Qw_d, ws_d, bias_d, out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2), "not repeatable"
+    Y = Y.cpu().numpy().astype(np.float64)
+    Yref = O.blocks_linear(codes, bscale, G_BLK, qw, w_scale, bias)
+    tol = _blocks_linear_bound(codes, bscale, qw, w_scale, bias, KB)
+    assert KB > 160 or (KB + 3) * 2.0 ** -24 <= U.OUT_RTOL
+    if out_dtype == torch.float16:
+        tol = tol + 2.0 ** -11 * np.abs(Yref) + 2.0 ** -25
+    err = np.abs(Y - Yref)
+    assert (err <= tol).all(), f"worst error / bound = {(err / tol).max()}"
+    return Y
+
+
+def _random_block_operands(M, K, N, seed, spread=6.0):
+    rng = np.random.Generator(np.random.PCG64([seed, M, K, N]))
+    KB = -(-K // G_BLK)
+    codes = I.random_codes((M, K), seed)
+    qw = I.random_codes((N, K), seed + 1)
+    # steps over many octaves within one row, as outlier channels make them
+    bscale = np.exp(rng.normal(-3.0, spread, (M, KB))).astype(np.float32)
+    w_scale = np.exp(rng.normal(-6.0, 0.5, N)).astype(np.float32)
+    bias = rng.normal(0, 0.02, N).astype(np.float32)
+    return codes, bscale, qw, w_scale, bias
+
+
+@pytest.mark.parametrize("M,K,N,with_bias,ld_s_pad", [
+    (1, 1, 1, False, 0), (5, 31, 3, True, 0), (64, 33, 64, False, 1), (129, 64, 130, True, 0),
+    (300, 320, 200, False, 0), (256, 1280, 320, True, 0), (130, 4100, 140, False, 3),
+    (200, 128, 129, True, 4), (77, 96, 300, False, 0)])
+def test_blocks_linear_shapes(M, K, N, with_bias, ld_s_pad):
+    codes, bscale, qw, w_scale, bias = _random_block_operands(M, K, N, 21)
+    _check_blocks_linear(codes, bscale, qw, w_scale, bias if with_bias else None,
+                         ld_s_pad=ld_s_pad)
+
+
+def test_blocks_linear_fp16_output():
+    codes, bscale, qw, w_scale, bias = _random_block_operands(140, 256, 150, 22, spread=1.0)
+    _check_blocks_linear(codes, bscale, qw, w_scale, bias, out_dtype=torch.float16)
+
+
+def test_blocks_linear_extreme_codes():
+    """Every product at its largest magnitude, alternating block signs: block sums of
+    +-2048 with steps that differ by 2^20 between neighbours."""
+    M, K, N = 64, 512, 64
+    codes = np.full((M, K), -8, dtype=np.int8)
+    qw = np.full((N, K), -8, dtype=np.int8)
+    qw[:, 32:64] = 7
+    qw[1::2] = -qw[1::2] - 1
+    KB = K // G_BLK
+    bscale = np.where(np.arange(KB) % 2 == 0, 1.0, 2.0 ** -20).astype(np.float32)[None, :].repeat(M, 0)
+    w_scale = np.full(N, 0.5, dtype=np.float32)
+    _check_blocks_linear(codes, bscale, qw, w_scale, None)
+
+
+def test_blocks_linear_equal_steps_reduces_to_the_token_set_linear():
+    """With one step for all blocks of a row and sums that stay exact in binary32 the
+    result is the whole-K contraction's, bit for bit."""
+    M, K, N = 96, 256, 80
+    codes = I.random_codes((M, K), 31)
+    qw = I.random_codes((N, K), 32)
+    rng = np.random.Generator(np.random.PCG64(33))
+    row = (2.0 ** rng.integers(-12, 4, M)).astype(np.float32)        # powers of two: exact
+    KB = K // G_BLK
+    bscale = np.repeat(row[:, None], KB, axis=1)
+    w_scale = np.exp(rng.normal(-6.0, 0.5, N)).astype(np.float32)
+    Y = _check_blocks_linear(codes, bscale, qw, w_scale, None)
+    _, Yt = O.w4a4_linear(codes, row, qw, w_scale)
+    assert np.array_equal(Y.astype(np.float32), Yt)
+
+
+@pytest.mark.parametrize("name,B,T", [("cfg2_fc2", 1, 300), ("cfg2_qkv", 2, 200)])
+def test_blocks_path_end_to_end(name, B, T):
+    """X -> block quantizer -> block-scaled linear on the GPU against the oracle's
+    Algorithm 1 (steps 1-10)."""
+    lc = I.case(name, B=B)
+    X = _acts(name, B, T)
+    W = I.make_weight(lc)
+    bias = I.make_bias(lc)
+    p = tdq.block_params()
+    Q, bs, q_gpu, scale_g = _check_block_quantizer(X, p)
+    Wd = torch.from_numpy(W).to(U.dev())
+    Qw_d, ws_d = tdq.tdq_quantize_weight(Wd)
+    Y = tdq.tdq_w4a4_linear_blocks(Q, bs, lc.C, Qw_d, ws_d, torch.from_numpy(bias).to(U.dev()))
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy().astype(np.float64)
+    qw, sw = O.quantize_weight(W)
+    # the GPU contraction on the GPU's own codes and steps
+    KB = -(-lc.C // G_BLK)
+    Yself = O.blocks_linear(q_gpu, scale_g, G_BLK, qw, sw, bias)
+    tol = _blocks_linear_bound(q_gpu, scale_g, qw, sw, bias, KB)
+    assert (np.abs(Y - Yself) <= tol).all()
+    # and the whole path against the oracle's own codes and steps
+    _, q_ref, _, scale = O.dstg_dcrp_blocks(X.reshape(B * T, lc.C), G_BLK, _oracle_params(p))
+    if np.array_equal(q_ref, q_gpu):
+        Yref = O.blocks_linear(q_ref, scale, G_BLK, qw, sw, bias)
+        tol = _blocks_linear_bound(q_ref, scale, qw, sw, bias, KB) + \
+            2 * U.SCALE_RTOL * (tol / ((KB + 3) * 2.0 ** -24))
+        assert (np.abs(Y - Yref) <= tol).all()
+
+
+@pytest.mark.timeout(600)
+def test_blocks_linear_full_size_sampled():
+    """The 131072 x 1024 -> 4096 shape of the largest configuration in the launch that the
+    measurement times, checked on sampled rows."""
+    M, K, N = 131072, 1024, 4096
+    codes, bscale, qw, w_scale, bias = _random_block_operands(M, K, N, 41, spread=2.0)
+    _say(f"[blocks-linear] full size M={M} K={K} N={N}")
+    Qx_d = U.pack_to_device(codes)
+    Qw_d = U.pack_to_device(qw)
+    Y = tdq.tdq_w4a4_linear_blocks(Qx_d, torch.from_numpy(bscale).to(U.dev()), K, Qw_d,
+                                   torch.from_numpy(w_scale).to(U.dev()), None, torch.float16)
+    torch.cuda.synchronize()
+    rows = np.concatenate([np.arange(0, 130), np.arange(M - 130, M),
+                           np.random.Generator(np.random.PCG64(5)).integers(0, M, 256)])
+    Ys = Y[torch.from_numpy(rows).to(U.dev())].cpu().numpy().astype(np.float64)
+    Yref = O.blocks_linear(codes[rows], bscale[rows], G_BLK, qw, w_scale, None)
+    tol = _blocks_linear_bound(codes[rows], bscale[rows], qw, w_scale, None, K // G_BLK)
+    tol = tol + 2.0 ** -11 * np.abs(Yref) + 2.0 ** -25
+    assert (np.abs(Ys - Yref) <= tol).all()
