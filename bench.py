@@ -23,6 +23,9 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
+# vector lane operations per second: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (one fp32
+# FMA per lane per clock is the published 78.6 TFLOP/s of unpacked fp32)
+PEAK_VALU_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM bytes per launch of the fc1 contraction on the default workload, from the
 # FETCH_SIZE + WRITE_SIZE counters (see profiles/bench_cfg4_hbm_traffic_pmc.txt)
 GEMM_FC1_TRAFFIC_BYTES = 1181145339
@@ -43,6 +46,8 @@ def parse():
                     help="also launch one plain device copy of 1 GiB (a kernel of known traffic, "
                          "used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-quality", action="store_true")
+    ap.add_argument("--no-blocks", action="store_true",
+                    help="skip the paper-literal (token, 32-channel block) leg")
     return ap.parse_args()
 
 
@@ -211,11 +216,60 @@ def main():
         "rooflines": rooflines,
     }
     out["rank_select_missed_sets"] = [tdq.exact_select_sets(L.ws) for L in layers]
+    if not args.no_blocks:
+        out["paper_literal_blocks"] = blocks_leg(layers, torch, tdq)
     if not args.no_quality:
         out["quality"] = quality(fc1, torch, tdq)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, np)
     print(json.dumps(out), flush=True)
+
+
+def blocks_leg(layers, torch, tdq, iters=10, warm=5):
+    """The paper's own granularity (one group per token and block of 32 channels) on the
+    same inputs, outside the timed steps: tdq_quantize_act_blocks -> tdq_w4a4_linear_blocks
+    per linear, HIP events on the launching stream.  The quantizer is one sweep of X (bytes:
+    X read, codes and steps written); the contraction rescales every 32-wide block of K in
+    binary32, 2 vector operations (convert, fused multiply-add) per output element and
+    block, which bounds it by the vector unit rather than by the matrix cores."""
+    res = {"layers": []}
+    tot = 0.0
+    for L in layers:
+        lc = L.lc
+        p = tdq.block_params()
+        KB = (lc.C + 31) // 32
+        bs = torch.empty((lc.M, KB), dtype=torch.float32, device=L.X.device)
+        Q = torch.zeros_like(L.Q)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tq = tl = 0.0
+        for it in range(warm + iters):
+            ev[0].record()
+            tdq.tdq_quantize_act_blocks(L.X, p, out=(Q, bs))
+            ev[1].record()
+            tdq.tdq_w4a4_linear_blocks(Q, bs, lc.C, L.Qw, L.w_scale, None, out=L.Y)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it >= warm:
+                tq += ev[0].elapsed_time(ev[1])
+                tl += ev[1].elapsed_time(ev[2])
+        tq, tl = tq / iters, tl / iters
+        e = lc.M * lc.C
+        qbytes = e * (2 if lc.dtype == "f16" else 4) + e // 2 + lc.M * KB * 4
+        lane_ops = 2.0 * lc.M * lc.N * KB
+        res["layers"].append({
+            "layer": lc.name, "quantize_ms": round(tq, 4), "linear_ms": round(tl, 4),
+            "quantize": {"bound": "hbm", "achieved": round(qbytes / (tq * 1e-3) / 1e9, 1),
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": round(qbytes / (tq * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+            "linear": {"bound": "alu", "achieved": round(lane_ops / (tl * 1e-3) / 1e12, 2),
+                       "peak": round(PEAK_VALU_TLOPS, 1), "unit": "T vector lane-ops/s",
+                       "frac": round(lane_ops / (tl * 1e-3) / 1e12 / PEAK_VALU_TLOPS, 4),
+                       "tops_int8": round(L.gemm_ops / (tl * 1e-3) / 1e12, 1)}})
+        tot += tq + tl
+        del bs, Q
+    res["ms_per_pass"] = round(tot, 4)
+    # the token-set path overwrote nothing it needs: L.Y is rewritten by the next step
+    return res
 
 
 def quality(L, torch, tdq):

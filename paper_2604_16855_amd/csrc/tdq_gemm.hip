@@ -869,23 +869,27 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
 // unit, not by the matrix cores (which idle three quarters of the time).  The factor 256
 // of the nibble expansion is taken out once at the end (a power of two: exact).
 //
-// Workgroup = 2 x 2 wavefronts, wavefront tile 64 x 64, 128 x 128 per workgroup; a stage
-// is 64 packed bytes (4 blocks) of K per row, register-staged and double-buffered.
-// LDS rows are 72 bytes apart: the 8-byte fragment reads of 32 consecutive rows then
-// fall on 32 different bank pairs.  The steps of a stage sit in LDS block-major so
-// that the 4 consecutive rows a lane owns are one 16-byte read.
+// Workgroup = 2 x 2 wavefronts, wavefront tile 64 x 64, 128 x 128 per workgroup, two
+// workgroups per CU; a stage is SBY packed bytes (SBY / 16 blocks) of K per row,
+// register-staged and double-buffered.  LDS rows are SBY + 8 bytes apart: the 8-byte
+// fragment reads of 32 consecutive rows then fall on 32 different bank pairs.  The steps
+// of a stage sit in LDS block-major so that the 4 consecutive rows a lane owns are one
+// 16-byte read.
 // ---------------------------------------------------------------------------
-constexpr int BLK_STRIDE = BKB + 8;
-
-template <typename OUT>
+template <typename OUT, int SBY>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
     const uint8_t* __restrict__ Qx, long long ld_q, const float* __restrict__ bscale, long long ld_s,
     int M, int K, int N, const uint8_t* __restrict__ Qw, long long ld_w,
     const float* __restrict__ w_scale, const float* __restrict__ bias, OUT* __restrict__ Y,
     long long ld_y, int m_tiles, int n_tiles) {
-  constexpr int MT = 2, NT = 2, BM = 128, BN = 128, SB = BKB / 16;   // SB blocks per stage
-  __shared__ __attribute__((aligned(16))) uint8_t sA[2][BM * BLK_STRIDE];
-  __shared__ __attribute__((aligned(16))) uint8_t sB[2][BN * BLK_STRIDE];
+  constexpr int MT = 2, NT = 2, BM = 128, BN = 128;
+  constexpr int SB = SBY / 16;                         // blocks (= 16-byte pieces) per stage
+  constexpr int STRIDE = SBY + 8;
+  constexpr int RPP = GEMM_THREADS / SB;               // rows per staging pass
+  constexpr int PASSES = BM / RPP;
+  constexpr int DPT = SB / 2;                          // steps per thread and stage
+  __shared__ __attribute__((aligned(16))) uint8_t sA[2][BM * STRIDE];
+  __shared__ __attribute__((aligned(16))) uint8_t sB[2][BN * STRIDE];
   __shared__ __attribute__((aligned(16))) float sD[2][SB][BM];
   __shared__ float sCol[BN], sBias[BN];
 
@@ -901,7 +905,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
   const int wm = wave >> 1, wn = wave & 1;
   const int kbytes = (K + 1) / 2;
   const int KB = (K + 31) / 32;
-  const int k_tiles = (kbytes + BKB - 1) / BKB;
+  const int k_tiles = (kbytes + SBY - 1) / SBY;
 
   for (int j = tid; j < BN; j += GEMM_THREADS) {
     const int n = n0 + j;
@@ -909,77 +913,74 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
     sBias[j] = (bias && n < N) ? bias[n] : 0.f;
   }
 
-  // staging: thread t owns the 16-byte piece (t & 3) of rows (t >> 2) + 64 i of both
-  // operands, and threads 0..127 the SB steps of row t
-  const int pr0 = tid >> 2, pc = (tid & 3) * 16;
-  const uint8_t* pa[MT];
-  const uint8_t* pb[NT];
+  // staging: thread t owns the 16-byte piece t % SB of rows t / SB + RPP i of both
+  // operands, and DPT consecutive steps of row t / 2
+  const int pr0 = tid / SB, pc = (tid % SB) * 16;
+  const uint8_t* pa[PASSES];
+  const uint8_t* pb[PASSES];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    int r = m0 + pr0 + 64 * i;
+  for (int i = 0; i < PASSES; ++i) {
+    int r = m0 + pr0 + RPP * i;
     r = r < M ? r : M - 1;
     pa[i] = Qx + (long long)r * ld_q + pc;
-  }
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    int r = n0 + pr0 + 64 * j;
+    r = n0 + pr0 + RPP * i;
     r = r < N ? r : N - 1;
-    pb[j] = Qw + (long long)r * ld_w + pc;
+    pb[i] = Qw + (long long)r * ld_w + pc;
   }
-  const bool d_owner = tid < BM;
-  const bool d_row_ok = d_owner && m0 + tid < M;
-  const float* pd = bscale + (long long)(m0 + (d_row_ok ? tid : 0)) * ld_s;
+  const int drow = tid >> 1, dcol = (tid & 1) * DPT;
+  const bool d_row_ok = m0 + drow < M;
+  const float* pd = bscale + (long long)(m0 + (d_row_ok ? drow : 0)) * ld_s + dcol;
 
-  uint4 ga[MT], gb[NT];
-  float gd[SB];
+  uint4 ga[PASSES], gb[PASSES];
+  float gd[DPT];
   auto load_stage = [&](int kt) {
-    const int kb = kt * BKB + pc;          // first packed byte of this piece
-    if (kb < kbytes) {
+    const int kb = kt * SBY + pc;          // first packed byte of this piece
+    if ((kt + 1) * SBY <= kbytes) {        // a whole stage inside the rows (uniform)
 #pragma unroll
-      for (int i = 0; i < MT; ++i)
-        ga[i] = *reinterpret_cast<const uint4*>(pa[i] + (long long)kt * BKB);
+      for (int i = 0; i < PASSES; ++i) {
+        ga[i] = *reinterpret_cast<const uint4*>(pa[i] + (long long)kt * SBY);
+        gb[i] = *reinterpret_cast<const uint4*>(pb[i] + (long long)kt * SBY);
+      }
+    } else if (kb < kbytes) {
 #pragma unroll
-      for (int j = 0; j < NT; ++j)
-        gb[j] = *reinterpret_cast<const uint4*>(pb[j] + (long long)kt * BKB);
+      for (int i = 0; i < PASSES; ++i) {
+        ga[i] = *reinterpret_cast<const uint4*>(pa[i] + (long long)kt * SBY);
+        gb[i] = *reinterpret_cast<const uint4*>(pb[i] + (long long)kt * SBY);
+      }
       if (kb + 16 > kbytes) {              // piece straddles the end of the row: zero the rest
         const int keep = kbytes - kb;
 #pragma unroll
-        for (int i = 0; i < MT; ++i) mask_piece(ga[i], keep);
-#pragma unroll
-        for (int j = 0; j < NT; ++j) mask_piece(gb[j], keep);
+        for (int i = 0; i < PASSES; ++i) {
+          mask_piece(ga[i], keep);
+          mask_piece(gb[i], keep);
+        }
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < MT; ++i) ga[i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < NT; ++j) gb[j] = make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < PASSES; ++i) {
+        ga[i] = make_uint4(0, 0, 0, 0);
+        gb[i] = make_uint4(0, 0, 0, 0);
+      }
     }
-    if (d_owner) {
-      // Four 4-byte loads, not one of 16 bytes: every lane reads its own row here, and a
-      // 16-byte load whose 64 lanes fall on 64 different 128-byte lines was measured to
-      // slow the whole kernel down tenfold on this chip.
-      const int b0 = kt * SB;              // first block of the stage
+    // 4-byte loads, not 16-byte ones: every lane pair reads its own row here, and a
+    // 16-byte load whose 64 lanes fall on 64 different 128-byte lines was measured to
+    // slow the whole kernel down tenfold on this chip.
+    const int b0 = kt * SB + dcol;         // first block of this thread's steps
 #pragma unroll
-      for (int j = 0; j < SB; ++j) gd[j] = (d_row_ok && b0 + j < KB) ? pd[b0 + j] : 0.f;
-    }
+    for (int j = 0; j < DPT; ++j) gd[j] = (d_row_ok && b0 + j < KB) ? pd[kt * SB + j] : 0.f;
   };
   auto store_stage = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      uint2* d = reinterpret_cast<uint2*>(&sA[buf][(pr0 + 64 * i) * BLK_STRIDE + pc]);
+    for (int i = 0; i < PASSES; ++i) {
+      uint2* d = reinterpret_cast<uint2*>(&sA[buf][(pr0 + RPP * i) * STRIDE + pc]);
       d[0] = make_uint2(ga[i].x, ga[i].y);
       d[1] = make_uint2(ga[i].z, ga[i].w);
+      d = reinterpret_cast<uint2*>(&sB[buf][(pr0 + RPP * i) * STRIDE + pc]);
+      d[0] = make_uint2(gb[i].x, gb[i].y);
+      d[1] = make_uint2(gb[i].z, gb[i].w);
     }
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      uint2* d = reinterpret_cast<uint2*>(&sB[buf][(pr0 + 64 * j) * BLK_STRIDE + pc]);
-      d[0] = make_uint2(gb[j].x, gb[j].y);
-      d[1] = make_uint2(gb[j].z, gb[j].w);
-    }
-    if (d_owner) {
-#pragma unroll
-      for (int j = 0; j < SB; ++j) sD[buf][j][tid] = gd[j];
-    }
+    for (int j = 0; j < DPT; ++j) sD[buf][dcol + j][drow] = gd[j];
   };
 
   float accf[MT][NT][16];
@@ -998,14 +999,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
   // 8 bytes at offset 8 (l >> 5); it owns column l & 31 and rows 8 q + 4 (l >> 5) + 0..3,
   // q = 0..3, of every 32 x 32 result.
   const int frow = lane & 31, fhalf = (lane >> 5) * 8;
-  const int a_off = (wm * 32 * MT + frow) * BLK_STRIDE + fhalf;
-  const int b_off = (wn * 32 * NT + frow) * BLK_STRIDE + fhalf;
+  const int a_off = (wm * 32 * MT + frow) * STRIDE + fhalf;
+  const int b_off = (wn * 32 * NT + frow) * STRIDE + fhalf;
   const int d_off = wm * 32 * MT + (lane >> 5) * 4;
   const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   for (int kt = 0; kt < k_tiles; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < k_tiles) load_stage(kt + 1);
-    // one block at a time: unrolled further, the loads of all four blocks are hoisted and
+    // one block at a time: unrolled further, the loads of all blocks are hoisted and
     // the accumulators spill
 #pragma unroll 1
     for (int kb = 0; kb < SB; ++kb) {
@@ -1013,7 +1014,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
       float dl[MT][16];
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
-        const uint2 f = *reinterpret_cast<const uint2*>(&sA[cur][a_off + i * 32 * BLK_STRIDE + kb * 16]);
+        const uint2 f = *reinterpret_cast<const uint2*>(&sA[cur][a_off + i * 32 * STRIDE + kb * 16]);
         a[i] = expand(f.x, f.y);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -1023,7 +1024,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        const uint2 f = *reinterpret_cast<const uint2*>(&sB[cur][b_off + j * 32 * BLK_STRIDE + kb * 16]);
+        const uint2 f = *reinterpret_cast<const uint2*>(&sB[cur][b_off + j * 32 * STRIDE + kb * 16]);
         b[j] = expand(f.x, f.y);
       }
       v16i t[MT][NT];
@@ -1045,6 +1046,56 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
   }
 
   const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+  if (m0 + BM <= M && n0 + BN <= N && (long long)(BM + 8) * ld_y < (1ll << 31) / (long long)sizeof(OUT)) {
+    // whole tile inside Y: a wavefront-uniform row pointer plus one per-lane offset, two
+    // rows at a time, the NT column blocks of a row back to back (whole lines of Y)
+    const unsigned lane_offu = (unsigned)(rquad * (int)ld_y + ccol);
+    auto body = [&](auto with_bias) {
+      float ws[NT], bs[NT];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        ws[j] = sCol[wn * 32 * NT + j * 32 + ccol];
+        bs[j] = sBias[wn * 32 * NT + j * 32 + ccol];
+      }
+      OUT* wtile = Y + (long long)(m0 + wm * 32 * MT) * ld_y + (n0 + wn * 32 * NT);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          OUT* row0 = wtile + (long long)(i * 32 + (r >> 2) * 8 + (r & 3)) * ld_y + lane_offu;
+          OUT* row1 = row0 + ld_y;
+          float y0[NT], y1[NT];
+#pragma unroll
+          for (int j = 0; j < NT; ++j) {
+            y0[j] = (accf[i][j][r] * 0.00390625f) * ws[j];
+            y1[j] = (accf[i][j][r + 1] * 0.00390625f) * ws[j];
+            if (decltype(with_bias)::value) {
+              y0[j] = y0[j] + bs[j];
+              y1[j] = y1[j] + bs[j];
+            }
+          }
+          if constexpr (sizeof(OUT) == 2) {
+            h2v p[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) p[j] = round_pair_to_half(y0[j], y1[j]);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][0], row0 + j * 32);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][1], row1 + j * 32);
+          } else {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) store_out<OUT>(row0 + j * 32, y0[j]);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
+          }
+        }
+    };
+    if (bias)
+      body(std::true_type{});
+    else
+      body(std::false_type{});
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -1064,6 +1115,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
     }
 }
 
+#ifndef TDQ_BLK_SBY
+#define TDQ_BLK_SBY 128
+#endif
 hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const float* bscale,
                                    long long ld_s, int M, int K, int N, const uint8_t* Qw,
                                    long long ld_w, const float* w_scale, const float* bias, void* Y,
@@ -1072,11 +1126,11 @@ hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const floa
   const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
   const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
   if (y_dt == TDQ_F32)
-    hipLaunchKernelGGL((k_w4a4_gemm_blocks<float>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q,
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks<float, TDQ_BLK_SBY>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q,
                        bscale, ld_s, M, K, N, Qw, ld_w, w_scale, bias, static_cast<float*>(Y), ld_y,
                        m_tiles, n_tiles);
   else
-    hipLaunchKernelGGL((k_w4a4_gemm_blocks<_Float16>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx,
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks<_Float16, TDQ_BLK_SBY>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx,
                        ld_q, bscale, ld_s, M, K, N, Qw, ld_w, w_scale, bias,
                        static_cast<_Float16*>(Y), ld_y, m_tiles, n_tiles);
   return hipGetLastError();
