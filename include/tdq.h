@@ -149,6 +149,20 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
                      const float* scale, uint8_t* Qx, int64_t ld_q, void* stream);
 
 /*
+ * Convolutional feature maps as tokens (Supp. implementation details: the dynamic path
+ * maps X[B, C, H, W] to X'[B, HW, C] and applies DSTG + DCRP along the channels).
+ * Exact re-layout, element (b, c, t) of X -> row b*T + t, column c of Xt, T = H*W; every
+ * token-major entry point then applies to Xt.  The paper restores the 4-D layout after its
+ * quantize-dequantize; here the codes feed the contraction (a 1 x 1 convolution is
+ * tdq_w4a4_linear over the channels), so nothing is restored.
+ *
+ * X: element (b, c, t) at X[b*ld_b + c*ld_c + t], ld_c >= T, ld_b >= (C-1)*ld_c + T.
+ * Xt [B*T, ld_xt] out, ld_xt >= C; must not overlap X.  B <= 65535.
+ */
+int tdq_tokenize_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T, int64_t ld_c,
+                     int64_t ld_b, void* Xt, int64_t ld_xt, void* stream);
+
+/*
  * The paper's own granularity (Sec. 4.2, Eq. direct_sum; Supp. Algorithm 1, steps 1-9) in
  * one sweep of X: the channel axis of every token is zero-padded to KB = ceil(C / 32)
  * blocks of g = TDQ_BLOCK channels and every (token, block) is a group of its own:

@@ -280,6 +280,15 @@ def dstg_dcrp_blocks(X: np.ndarray, g: int, p: Params):
     return xhat, codes, clip.reshape(lead + (K,)), scale.reshape(lead + (K,))
 
 
+def tokenize_chw(X: np.ndarray) -> np.ndarray:
+    """The 4-D branch of the dynamic activation path (Supp. "Implementation details"):
+    a feature map X[B, C, H, W] becomes tokens X'[B, H*W, C], token t = h*W + w, and
+    DSTG + DCRP then run along the channel axis of X'."""
+    X = np.asarray(X)
+    B, C = X.shape[0], X.shape[1]
+    return np.ascontiguousarray(X.reshape(B, C, -1).transpose(0, 2, 1))
+
+
 # --------------------------------------------------------------------------
 # weights (Eq. weight_quant) and the quantized linear (Algorithm 1, step 10)
 # --------------------------------------------------------------------------

@@ -240,6 +240,22 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
   return TDQ_OK;
 }
 
+int tdq_tokenize_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T, int64_t ld_c,
+                     int64_t ld_b, void* Xt, int64_t ld_xt, void* stream) {
+  if (!X || !Xt) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  if (B < 1 || T < 1 || C < 1 || B > 65535) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
+  if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T || ld_xt < C) return TDQ_ERR_SHAPE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz || reinterpret_cast<uintptr_t>(Xt) % esz)
+    return TDQ_ERR_ALIGN;
+  if (launch_tokenize_chw(X, dt, B, C, T, ld_c, ld_b, Xt, ld_xt,
+                          static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
 int tdq_quantize_act_blocks(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
                             int64_t ld_x, const tdq_params* p, uint8_t* Qx, int64_t ld_q,
                             float* block_scale, float* block_clip, int64_t ld_s, void* stream) {

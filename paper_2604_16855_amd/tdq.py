@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
     L.tdq_w4a4_linear_blocks.restype = C.c_int
     L.tdq_w4a4_linear_blocks.argtypes = [vp, i64, vp, i64, i64, i32, i32, vp, i64, vp, vp, vp,
                                          C.c_int, i64, vp]
+    L.tdq_tokenize_chw.restype = C.c_int
+    L.tdq_tokenize_chw.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64, vp, i64, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -209,6 +211,26 @@ def tdq_quantize_act(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],
                                 clip.data_ptr(), scale.data_ptr(), out.data_ptr(), out.stride(0),
                                 _stream())
     _check(rc, "tdq_quantize_act")
+    return out
+
+
+def tdq_tokenize_chw(X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """X[B, C, H, W] (or [B, C, T]) with contiguous spatial axes -> Xt[B, H*W, C]."""
+    if X.dim() == 4:
+        if X.stride(3) != 1 or X.stride(2) != X.shape[3]:
+            raise ValueError("the spatial axes of X must be contiguous")
+        B, Cc, T = X.shape[0], X.shape[1], X.shape[2] * X.shape[3]
+    elif X.dim() == 3 and X.stride(2) == 1:
+        B, Cc, T = X.shape
+    else:
+        raise ValueError("X must be [B, C, H, W] or [B, C, T] with contiguous tokens")
+    ld_c = X.stride(1) if Cc > 1 else T
+    ld_b = X.stride(0) if B > 1 else max((Cc - 1) * ld_c + T, 1)
+    if out is None:
+        out = torch.empty((B, T, Cc), dtype=X.dtype, device=X.device)
+    rc = lib().tdq_tokenize_chw(X.data_ptr(), _dt(X), B, Cc, T, ld_c, ld_b, out.data_ptr(),
+                                out.stride(1), _stream())
+    _check(rc, "tdq_tokenize_chw")
     return out
 
 

@@ -24,7 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
-            "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks",
+            "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -176,6 +176,23 @@ def test_block_linear_rejects_bad_arguments():
     assert call(Qx=FAKE + 8) == tdq.ERR_ALIGN
     assert call(ld_y=7) == tdq.ERR_SHAPE
     assert call(ydt=2) == tdq.ERR_DTYPE
+
+
+def test_tokenize_rejects_bad_arguments():
+    f = tdq.lib().tdq_tokenize_chw
+
+    def call(X=FAKE, dt=0, B=2, Cc=8, T=12, ld_c=12, ld_b=96, Xt=FAKE, ld_xt=8):
+        return f(X, dt, B, Cc, T, ld_c, ld_b, Xt, ld_xt, None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(Xt=None) == tdq.ERR_NULL
+    assert call(dt=2) == tdq.ERR_DTYPE
+    assert call(Cc=0) == tdq.ERR_SHAPE
+    assert call(B=70000, T=1, ld_c=1, ld_b=8) == tdq.ERR_SHAPE
+    assert call(ld_c=11) == tdq.ERR_SHAPE
+    assert call(ld_b=95) == tdq.ERR_SHAPE          # (C-1)*ld_c + T = 96
+    assert call(ld_xt=7) == tdq.ERR_SHAPE
+    assert call(X=FAKE + 1) == tdq.ERR_ALIGN
 
 
 def test_bench_refuses_more_than_one_gpu():

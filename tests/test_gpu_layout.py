@@ -1,0 +1,88 @@
+"""GPU parity of the conv-layout front end: X[B, C, H, W] -> tokens X'[B, HW, C]
+(Supp. implementation details, the 4-D branch) against the oracle's re-layout, and the
+token paths run on the tokenized map."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tdq_oracle as O
+from paper_2604_16855_amd import tdq
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _feature_map(B, C, H, W, dtype, seed):
+    rng = np.random.Generator(np.random.PCG64([seed, B, C, H, W]))
+    X = rng.standard_normal((B, C, H, W)) * np.exp(rng.normal(0, 1.0, (B, 1, H, W)))
+    X[rng.random((B, C, H, W)) < 0.01] *= 25.0
+    return X.astype(dtype)
+
+
+@pytest.mark.parametrize("B,C,H,W,dtype", [
+    (2, 64, 16, 8, np.float16),       # exactly one tile per image
+    (1, 320, 22, 22, np.float16),     # 484 tokens: ragged token tiles
+    (3, 100, 7, 9, np.float16),       # nothing aligned: scalar loads and stores
+    (1, 1, 1, 1, np.float16),
+    (2, 72, 12, 16, np.float16),      # ragged channel tile, aligned rows
+    (2, 64, 8, 8, np.float32),
+    (1, 130, 11, 13, np.float32),
+    (1, 1024, 64, 64, np.float16),    # a 4096-token, 1024-channel map
+])
+def test_tokenize_chw_is_an_exact_relayout(B, C, H, W, dtype):
+    _say(f"[tokenize] B={B} C={C} H={H} W={W} dtype={dtype.__name__}")
+    X = _feature_map(B, C, H, W, dtype, 3)
+    Xt = tdq.tdq_tokenize_chw(torch.from_numpy(X).to(U.dev()))
+    torch.cuda.synchronize()
+    assert np.array_equal(Xt.cpu().numpy().view(np.uint8), O.tokenize_chw(X).view(np.uint8))
+
+
+def test_tokenize_chw_strided_views():
+    """Channel and image strides larger than the data (a crop of a wider buffer), and an
+    output with a padded row stride: junk around the data is neither read into the result
+    nor overwritten."""
+    B, C, H, W = 2, 48, 6, 10
+    X = _feature_map(B, C + 5, H + 2, W, np.float16, 4)
+    Xd = torch.from_numpy(X).to(U.dev())[:, 2:2 + C, 1:1 + H, :]      # spatial axes stay contiguous
+    out = torch.full((B, H * W, C + 8), 9.0, dtype=torch.float16, device=U.dev())
+    tdq.tdq_tokenize_chw(Xd, out=out[:, :, :C])
+    torch.cuda.synchronize()
+    ref = O.tokenize_chw(X[:, 2:2 + C, 1:1 + H, :])
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:, :, :C], ref)
+    assert (got[:, :, C:] == 9.0).all()
+
+
+def test_conv_layout_through_both_token_paths():
+    """A feature map through tokenize -> token-set path and -> per-block path gives what
+    the oracle gives on the oracle's tokens."""
+    B, C, H, W = 2, 96, 12, 12
+    X = _feature_map(B, C, H, W, np.float16, 5)
+    Xt_ref = O.tokenize_chw(X)
+    Xt = tdq.tdq_tokenize_chw(torch.from_numpy(X).to(U.dev()))
+    # token sets
+    p = tdq.default_params(4)
+    gid, clip, scale, _, ws = tdq.tdq_calibrate_groups(Xt, p)
+    Q = tdq.tdq_quantize_act(Xt, p, gid, clip, scale)
+    torch.cuda.synchronize()
+    og, oc, osc, _ = O.calibrate_groups(Xt_ref, U.oracle_params(p))
+    assert np.array_equal(gid.cpu().numpy(), og)
+    assert np.allclose(scale.cpu().numpy(), osc, rtol=U.SCALE_RTOL, atol=0)
+    q_ref = O.quantize_act(Xt_ref, og, oc, osc, U.oracle_params(p)).reshape(B * H * W, C)
+    rows = np.arange(B)[:, None]
+    U.assert_codes_match(U.unpack_device_codes(Q, C), q_ref, Xt_ref,
+                         oc[rows, og].reshape(-1), osc[rows, og].reshape(-1),
+                         np.array_equal(scale.cpu().numpy(), osc))
+    # blocks of 32 channels per pixel (the paper's 4-D branch)
+    pb = tdq.block_params(flags=2)
+    Qb, bs, bc = tdq.tdq_quantize_act_blocks(Xt, pb, want_clip=True)
+    torch.cuda.synchronize()
+    _, qb_ref, cb, sb = O.dstg_dcrp_blocks(Xt_ref.reshape(B * H * W, C), 32,
+                                           O.Params(n_groups=1, flags=2))
+    assert np.array_equal(bc.cpu().numpy(), cb) and np.array_equal(bs.cpu().numpy(), sb)
+    assert np.array_equal(U.unpack_device_codes(Qb, C), qb_ref)

@@ -482,3 +482,22 @@ def test_linear_equals_float_linear_on_dequantized_operands():
     assert (np.abs(out["Y"] - ref) <= 1e-5 * noise + 1e-30).all()
     # and x_hat is the paper's quantize-dequantize of X with those radii
     assert np.abs(out["acc"]).max() <= 56 * 48
+
+
+def test_tokenize_chw_by_explicit_index_loops():
+    """X[b, c, h, w] lands at X'[b, h*W + w, c] (the 4-D branch of the supplementary
+    implementation details), checked element by element, and the per-block radii of the
+    tokenized map are those of each pixel's channel vector."""
+    rng = np.random.Generator(np.random.PCG64(71))
+    B, C, H, W = 2, 40, 3, 5
+    X = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    Xt = O.tokenize_chw(X)
+    assert Xt.shape == (B, H * W, C)
+    for b in range(B):
+        for c in range(C):
+            for h in range(H):
+                for w in range(W):
+                    assert Xt[b, h * W + w, c] == X[b, c, h, w]
+    _, _, clip, _ = O.dstg_dcrp_blocks(Xt, 32, O.Params(flags=0))
+    assert clip[1, 7, 0] == np.abs(X[1, :32, 1, 2]).max()
+    assert clip[1, 7, 1] == np.abs(X[1, 32:, 1, 2]).max()
