@@ -183,6 +183,18 @@ int tdq_quantize_act_blocks(const void* X, tdq_dtype dt, int32_t B, int32_t T, i
                             float* block_scale, float* block_clip, int64_t ld_s, void* stream);
 
 /*
+ * tdq_quantize_act_blocks reading a convolutional feature map directly (the paper's 4-D
+ * branch fused into the sweep): X in the layout of tdq_tokenize_chw (element (b, c, t) at
+ * X[b*ld_b + c*ld_c + t]); a group is the block of 32 channels of one pixel.  Outputs as
+ * from tdq_quantize_act_blocks on the tokenized map, bit for bit: Qx [B*T, ld_q],
+ * block_scale / block_clip [B*T, ld_s], row b*T + t.  B <= 65535.
+ */
+int tdq_quantize_act_blocks_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
+                                int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx,
+                                int64_t ld_q, float* block_scale, float* block_clip, int64_t ld_s,
+                                void* stream);
+
+/*
  * Diagnostics of the paper's Sec. 3.2 per (image, token set), as exact element counts
  * for the radii and steps given: zero_count = elements whose code is 0 (zero-bin mass
  * rho_0 = zero_count / n, Eq. rho0_def; the code is computed exactly as

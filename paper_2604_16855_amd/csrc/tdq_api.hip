@@ -83,6 +83,13 @@ static int check_shape(int32_t B, int32_t T, int32_t C, int64_t ld_x) {
   return TDQ_OK;
 }
 
+// Rank ceil(frac g) among the g values of a block, padding zeros included (binary64, as
+// everywhere).
+static int block_rank(double frac) {
+  long long k = (long long)ceil(frac * (double)TDQ_BLOCK);
+  return (int)(k < 1 ? 1 : (k > TDQ_BLOCK ? TDQ_BLOCK : k));
+}
+
 static Scalars make_scalars(const tdq_params* p) {
   Scalars s;
   s.qmax = (float)kQMax;
@@ -272,16 +279,37 @@ int tdq_quantize_act_blocks(const void* X, tdq_dtype dt, int32_t B, int32_t T, i
   if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(block_scale) | reinterpret_cast<uintptr_t>(block_clip)) & 3)
     return TDQ_ERR_ALIGN;
-  // ranks among the g values of a block, padding zeros included (binary64, as everywhere)
-  auto rank_of = [](double frac) {
-    long long k = (long long)ceil(frac * (double)TDQ_BLOCK);
-    return (int)(k < 1 ? 1 : (k > TDQ_BLOCK ? TDQ_BLOCK : k));
-  };
-  const int kq = rank_of(p->zr);
-  const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? rank_of(p->base_pct) : TDQ_BLOCK;
+  const int kq = block_rank(p->zr);
+  const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? block_rank(p->base_pct) : TDQ_BLOCK;
   if (launch_quantize_blocks(X, dt, (long long)B * T, C, ld_x, kq, kp, make_scalars(p), Qx, ld_q,
                              block_scale, block_clip, ld_s,
                              static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+int tdq_quantize_act_blocks_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
+                                int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx,
+                                int64_t ld_q, float* block_scale, float* block_clip, int64_t ld_s,
+                                void* stream) {
+  if (!X || !p || !Qx || !block_scale) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p, true);
+  if (rc != TDQ_OK) return rc;
+  if (B < 1 || T < 1 || C < 1 || B > 65535) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
+  if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T) return TDQ_ERR_SHAPE;
+  const int64_t KB = ((int64_t)C + TDQ_BLOCK - 1) / TDQ_BLOCK;
+  if (ld_q < (C + 1) / 2 || ld_s < KB) return TDQ_ERR_SHAPE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(block_scale) | reinterpret_cast<uintptr_t>(block_clip)) & 3)
+    return TDQ_ERR_ALIGN;
+  const int kq = block_rank(p->zr);
+  const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? block_rank(p->base_pct) : TDQ_BLOCK;
+  if (launch_quantize_blocks_chw(X, dt, B, C, T, ld_c, ld_b, kq, kp, make_scalars(p), Qx, ld_q,
+                                 block_scale, block_clip, ld_s,
+                                 static_cast<hipStream_t>(stream)) != hipSuccess)
     return TDQ_ERR_HIP;
   return TDQ_OK;
 }

@@ -153,60 +153,19 @@ __device__ __forceinline__ u32 kth_by_bisection(const u32 (&key)[8], u32 rank) {
 }
 
 // ---------------------------------------------------------------------------
-// the sweep
+// One block per quad (two for binary16, in the halves of the key registers): raw[s] holds
+// this lane's 8 values of block s as loaded.  Returns the 8 packed codes of each block
+// and, in every lane of the quad, its clip radius and step.  Every lane of the wavefront
+// must take part (quad exchanges).
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void k_quantize_blocks(
-    const T* __restrict__ X, long long ld, u32 total, int C, int KB, int vec_ok, int q_vec_ok,
-    int kq, int kp, Scalars sc, uint8_t* __restrict__ Q, long long ld_q, float* __restrict__ bscale,
-    float* __restrict__ bclip, long long ld_s) {
+__device__ __forceinline__ void block_core(const u32 (&raw)[sizeof(T) == 2 ? 2 : 1][sizeof(T) == 2 ? 4 : 8],
+                                           int ql, int kq, int kp, const Scalars& sc,
+                                           u32 (&word)[sizeof(T) == 2 ? 2 : 1],
+                                           float (&cs)[sizeof(T) == 2 ? 2 : 1],
+                                           float (&ds)[sizeof(T) == 2 ? 2 : 1]) {
   constexpr bool PK = sizeof(T) == 2;
-  constexpr int NB = PK ? 2 : 1;                           // blocks per lane
-  constexpr int W = PK ? 4 : 8;                            // 32-bit words of 8 elements
-  const u32 wave_first =
-      (u32)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * 4u + (threadIdx.x >> 6)) * (16u * NB)));
-  if (wave_first >= total) return;                         // whole wavefronts only
-  const int lane = threadIdx.x & 63, quad = lane >> 2, ql = lane & 3;
-  const u32 row0 = wave_first / (u32)KB, kb0 = wave_first - row0 * (u32)KB;
-
-  bool live[NB];
-  long long row[NB];
-  int kb[NB];
-  u32 raw[NB][W];
-#pragma unroll
-  for (int s = 0; s < NB; ++s) {
-    const u32 off = (u32)quad + 16u * s;
-    live[s] = wave_first + off < total;
-    // a quad without a block works on the wavefront's first block and stores nothing
-    const u32 t = kb0 + (live[s] ? off : 0u);
-    u32 wrap;
-    if (KB >= 16 * NB) wrap = t >= (u32)KB ? 1u : 0u;      // t < KB + 16 NB <= 2 KB
-    else wrap = t / (u32)KB;
-    row[s] = (long long)(row0 + wrap);
-    kb[s] = (int)(t - wrap * (u32)KB);
-    const int c0 = kb[s] * kBlk + ql * 8;                  // first channel of this lane
-    const T* xp = X + row[s] * ld + c0;
-    if (vec_ok && c0 + 8 <= C) {
-      const uint4 q0 = *reinterpret_cast<const uint4*>(xp);
-      raw[s][0] = q0.x; raw[s][1] = q0.y; raw[s][2] = q0.z; raw[s][3] = q0.w;
-      if constexpr (!PK) {
-        const uint4 q1 = *reinterpret_cast<const uint4*>(xp + 4);
-        raw[s][4] = q1.x; raw[s][5] = q1.y; raw[s][6] = q1.z; raw[s][7] = q1.w;
-      }
-    } else {
-      // row tail or unaligned rows; channels at and beyond C are the zero padding
-#pragma unroll
-      for (int w = 0; w < W; ++w) raw[s][w] = 0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (c0 + i < C) {
-          if constexpr (PK) raw[s][i >> 1] |= (u32)xp[i] << (16 * (i & 1));
-          else raw[s][i] = __float_as_uint(xp[i]);
-        }
-      }
-    }
-  }
-
+  constexpr int NB = PK ? 2 : 1;
   // values, moments (binary64, as the set statistics of the token-set path)
   float v[NB][8];
   double s1[NB], s2[NB];
@@ -307,7 +266,7 @@ __global__ __launch_bounds__(256) void k_quantize_blocks(
   d = d > sc.eps_scale ? d : sc.eps_scale;
   const float rcp = 1.0f / d;                                      // correctly rounded
 
-  float cs[NB], ds[NB], rs[NB];
+  float rs[NB];
   cs[0] = quad_f32<kQuadLane0>(c);
   ds[0] = quad_f32<kQuadLane0>(d);
   rs[0] = quad_f32<kQuadLane0>(rcp);
@@ -319,31 +278,103 @@ __global__ __launch_bounds__(256) void k_quantize_blocks(
 
 #pragma unroll
   for (int s = 0; s < NB; ++s) {
-    if (!live[s]) continue;
-    if (ql == s) {
-      bscale[row[s] * ld_s + kb[s]] = ds[s];
-      if (bclip) bclip[row[s] * ld_s + kb[s]] = cs[s];
-    }
-    u32 word;
     if constexpr (PK) {
       // c <= 7 Delta (1 + 2^-24) by construction: the clamp of the code is implied
-      word = quant8_f16<false>(make_uint4(raw[s][0], raw[s][1], raw[s][2], raw[s][3]), cs[s], ds[s],
-                               rs[s]);
+      word[s] = quant8_f16<false>(make_uint4(raw[s][0], raw[s][1], raw[s][2], raw[s][3]), cs[s], ds[s],
+                                  rs[s]);
     } else {
-      word = 0;
+      word[s] = 0;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) word |= quant_nibble(v[s][i], cs[s], ds[s], rs[s]) << (4 * i);
-    }
-    // 8 codes = 4 bytes at byte 16 kb + 4 ql of the row; a row holds ceil(C / 2) bytes
-    const int b0 = kb[s] * (kBlk / 2) + ql * 4;
-    uint8_t* qp = Q + row[s] * ld_q + b0;
-    const int nbytes = (C + 1) / 2 - b0;                           // bytes of the row from here on
-    if (q_vec_ok && nbytes >= 4) {
-      *reinterpret_cast<u32*>(qp) = word;
-    } else {
-      for (int i = 0; i < 4 && i < nbytes; ++i) qp[i] = (uint8_t)(word >> (8 * i));
+      for (int i = 0; i < 8; ++i) word[s] |= quant_nibble(v[s][i], cs[s], ds[s], rs[s]) << (4 * i);
     }
   }
+}
+
+// Stores the 8 codes of one lane (4 bytes at byte b0 of the row) and, from lane `owner`
+// of the quad, the block's step and radius.
+__device__ __forceinline__ void block_store(u32 word, float c, float d, bool owner, long long row,
+                                            int kb, int ql, int C, int q_vec_ok,
+                                            uint8_t* __restrict__ Q, long long ld_q,
+                                            float* __restrict__ bscale, float* __restrict__ bclip,
+                                            long long ld_s) {
+  if (owner) {
+    bscale[row * ld_s + kb] = d;
+    if (bclip) bclip[row * ld_s + kb] = c;
+  }
+  // 8 codes = 4 bytes at byte 16 kb + 4 ql of the row; a row holds ceil(C / 2) bytes
+  const int b0 = kb * (kBlk / 2) + ql * 4;
+  uint8_t* qp = Q + row * ld_q + b0;
+  const int nbytes = (C + 1) / 2 - b0;                             // bytes of the row from here on
+  if (q_vec_ok && nbytes >= 4) {
+    *reinterpret_cast<u32*>(qp) = word;
+  } else {
+    for (int i = 0; i < 4 && i < nbytes; ++i) qp[i] = (uint8_t)(word >> (8 * i));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// the sweep
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_quantize_blocks(
+    const T* __restrict__ X, long long ld, u32 total, int C, int KB, int vec_ok, int q_vec_ok,
+    int kq, int kp, Scalars sc, uint8_t* __restrict__ Q, long long ld_q, float* __restrict__ bscale,
+    float* __restrict__ bclip, long long ld_s) {
+  constexpr bool PK = sizeof(T) == 2;
+  constexpr int NB = PK ? 2 : 1;                           // blocks per lane
+  constexpr int W = PK ? 4 : 8;                            // 32-bit words of 8 elements
+  const u32 wave_first =
+      (u32)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * 4u + (threadIdx.x >> 6)) * (16u * NB)));
+  if (wave_first >= total) return;                         // whole wavefronts only
+  const int lane = threadIdx.x & 63, quad = lane >> 2, ql = lane & 3;
+  const u32 row0 = wave_first / (u32)KB, kb0 = wave_first - row0 * (u32)KB;
+
+  bool live[NB];
+  long long row[NB];
+  int kb[NB];
+  u32 raw[NB][W];
+#pragma unroll
+  for (int s = 0; s < NB; ++s) {
+    const u32 off = (u32)quad + 16u * s;
+    live[s] = wave_first + off < total;
+    // a quad without a block works on the wavefront's first block and stores nothing
+    const u32 t = kb0 + (live[s] ? off : 0u);
+    u32 wrap;
+    if (KB >= 16 * NB) wrap = t >= (u32)KB ? 1u : 0u;      // t < KB + 16 NB <= 2 KB
+    else wrap = t / (u32)KB;
+    row[s] = (long long)(row0 + wrap);
+    kb[s] = (int)(t - wrap * (u32)KB);
+    const int c0 = kb[s] * kBlk + ql * 8;                  // first channel of this lane
+    const T* xp = X + row[s] * ld + c0;
+    if (vec_ok && c0 + 8 <= C) {
+      const uint4 q0 = *reinterpret_cast<const uint4*>(xp);
+      raw[s][0] = q0.x; raw[s][1] = q0.y; raw[s][2] = q0.z; raw[s][3] = q0.w;
+      if constexpr (!PK) {
+        const uint4 q1 = *reinterpret_cast<const uint4*>(xp + 4);
+        raw[s][4] = q1.x; raw[s][5] = q1.y; raw[s][6] = q1.z; raw[s][7] = q1.w;
+      }
+    } else {
+      // row tail or unaligned rows; channels at and beyond C are the zero padding
+#pragma unroll
+      for (int w = 0; w < W; ++w) raw[s][w] = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (c0 + i < C) {
+          if constexpr (PK) raw[s][i >> 1] |= (u32)xp[i] << (16 * (i & 1));
+          else raw[s][i] = __float_as_uint(xp[i]);
+        }
+      }
+    }
+  }
+
+  u32 word[NB];
+  float cs[NB], ds[NB];
+  block_core<T>(raw, ql, kq, kp, sc, word, cs, ds);
+#pragma unroll
+  for (int s = 0; s < NB; ++s)
+    if (live[s])
+      block_store(word[s], cs[s], ds[s], ql == s, row[s], kb[s], ql, C, q_vec_ok, Q, ld_q, bscale,
+                  bclip, ld_s);
 }
 
 template <typename T>
@@ -370,6 +401,119 @@ hipError_t launch_quantize_blocks(const void* X, tdq_dtype dt, long long M, int 
                                   bclip, ld_s, st);
   return quantize_blocks_t<float>(static_cast<const float*>(X), M, C, ld, kq, kp, sc, Q, ld_q,
                                   bscale, bclip, ld_s, st);
+}
+
+// ---------------------------------------------------------------------------
+// The same sweep over a convolutional feature map X[B, C, T] (T = H W tokens, contiguous;
+// Supp. "Implementation details", the 4-D branch): a group is the block of 32 channels
+// of one pixel.  A workgroup owns TT consecutive tokens of one image and walks the
+// channel axis in tiles of TC channels: 16-byte loads along the token axis into LDS,
+// then every quad gathers its block(s) of one token from the tile (2- or 4-byte LDS
+// reads; rows 8 bytes longer than the data keep them to two-way bank conflicts) and
+// runs block_core.  Codes and steps are token-major, as from the token-major sweep.
+// ---------------------------------------------------------------------------
+template <typename T, int TC>
+__global__ __launch_bounds__(256) void k_quantize_blocks_chw(
+    const T* __restrict__ X, long long ld_c, long long ld_b, int C, int T_, int vin_ok, int q_vec_ok,
+    int kq, int kp, Scalars sc, uint8_t* __restrict__ Q, long long ld_q, float* __restrict__ bscale,
+    float* __restrict__ bclip, long long ld_s) {
+  constexpr bool PK = sizeof(T) == 2;
+  constexpr int NB = PK ? 2 : 1;
+  constexpr int W = PK ? 4 : 8;
+  constexpr int E = 16 / (int)sizeof(T);                   // elements per 16 bytes
+  constexpr int TT = 16 * E;                               // tokens per tile
+  constexpr int PITCH = TT + 8 / (int)sizeof(T);
+  constexpr int QPT = TC / (kBlk * NB);                    // quads per token and tile
+  __shared__ __attribute__((aligned(16))) T tile[TC][PITCH];
+
+  const int t0 = blockIdx.x * TT, b = blockIdx.y;
+  const int tid = threadIdx.x, ql = tid & 3;
+  const T* xb = X + (long long)b * ld_b;
+  const int KB = (C + kBlk - 1) / kBlk;
+
+  for (int c0 = 0; c0 < C; c0 += TC) {
+    {
+      const int p = tid & 15;
+      const int tok = t0 + p * E;
+#pragma unroll
+      for (int i = 0; i < TC / 16; ++i) {
+        const int ch = (tid >> 4) + 16 * i;
+        const int c = c0 + ch;
+        __attribute__((aligned(16))) T v[E];
+        if (c < C && vin_ok && tok + E <= T_) {
+          *reinterpret_cast<uint4*>(v) = *reinterpret_cast<const uint4*>(xb + (long long)c * ld_c + tok);
+        } else {
+          // channels at and beyond C are the zero padding of the last block
+#pragma unroll
+          for (int k = 0; k < E; ++k)
+            v[k] = (c < C && tok + k < T_) ? xb[(long long)c * ld_c + tok + k] : (T)0;
+        }
+        uint2* d = reinterpret_cast<uint2*>(&tile[ch][p * E]);
+        const uint2* sp = reinterpret_cast<const uint2*>(v);
+        d[0] = sp[0];
+        d[1] = sp[1];
+      }
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int pass = 0; pass < TT * QPT / 64; ++pass) {
+      const int qd = (tid >> 2) + 64 * pass;
+      const int tl = qd / QPT, sub = qd % QPT;
+      u32 raw[NB][W];
+#pragma unroll
+      for (int s = 0; s < NB; ++s) {
+        const int chb = (sub * NB + s) * kBlk + ql * 8;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+          if constexpr (PK) {
+            const u32 lo = tile[chb + 2 * w][tl], hi = tile[chb + 2 * w + 1][tl];
+            raw[s][w] = lo | (hi << 16);
+          } else {
+            raw[s][w] = __float_as_uint(tile[chb + w][tl]);
+          }
+        }
+      }
+      u32 word[NB];
+      float cs[NB], ds[NB];
+      block_core<T>(raw, ql, kq, kp, sc, word, cs, ds);
+      const bool tok_ok = t0 + tl < T_;
+      const long long row = (long long)b * T_ + t0 + tl;
+#pragma unroll
+      for (int s = 0; s < NB; ++s) {
+        const int kb = c0 / kBlk + sub * NB + s;
+        if (tok_ok && kb < KB)
+          block_store(word[s], cs[s], ds[s], ql == s, row, kb, ql, C, q_vec_ok, Q, ld_q, bscale, bclip,
+                      ld_s);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T>
+static hipError_t quantize_blocks_chw_t(const T* X, int B, int C, int T_, long long ld_c,
+                                        long long ld_b, int kq, int kp, const Scalars& sc,
+                                        uint8_t* Q, long long ld_q, float* bscale, float* bclip,
+                                        long long ld_s, hipStream_t st) {
+  constexpr int E = 16 / (int)sizeof(T);
+  const int vin_ok =
+      ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld_c % E == 0 && ld_b % E == 0) ? 1 : 0;
+  const int q_vec_ok = ((reinterpret_cast<uintptr_t>(Q) & 3) == 0 && ld_q % 4 == 0) ? 1 : 0;
+  const dim3 grid((unsigned)((T_ + 16 * E - 1) / (16 * E)), (unsigned)B);
+  hipLaunchKernelGGL((k_quantize_blocks_chw<T, 128>), grid, dim3(256), 0, st, X, ld_c, ld_b, C, T_,
+                     vin_ok, q_vec_ok, kq, kp, sc, Q, ld_q, bscale, bclip, ld_s);
+  return hipGetLastError();
+}
+
+hipError_t launch_quantize_blocks_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
+                                      long long ld_b, int kq, int kp, const Scalars& sc, uint8_t* Q,
+                                      long long ld_q, float* bscale, float* bclip, long long ld_s,
+                                      hipStream_t st) {
+  if (dt == TDQ_F16)
+    return quantize_blocks_chw_t<u16>(static_cast<const u16*>(X), B, C, T, ld_c, ld_b, kq, kp, sc, Q,
+                                      ld_q, bscale, bclip, ld_s, st);
+  return quantize_blocks_chw_t<float>(static_cast<const float*>(X), B, C, T, ld_c, ld_b, kq, kp, sc, Q,
+                                      ld_q, bscale, bclip, ld_s, st);
 }
 
 }  // namespace tdq

@@ -86,6 +86,9 @@ def lib() -> C.CDLL:
                                          C.c_int, i64, vp]
     L.tdq_tokenize_chw.restype = C.c_int
     L.tdq_tokenize_chw.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64, vp, i64, vp]
+    L.tdq_quantize_act_blocks_chw.restype = C.c_int
+    L.tdq_quantize_act_blocks_chw.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64,
+                                              C.POINTER(Params), vp, i64, vp, vp, i64, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -212,6 +215,41 @@ def tdq_quantize_act(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor],
                                 _stream())
     _check(rc, "tdq_quantize_act")
     return out
+
+
+def _bct(X: torch.Tensor) -> Tuple[int, int, int, int, int]:
+    """(B, C, T, ld_c, ld_b) of a feature map [B, C, H, W] or [B, C, T] with contiguous
+    spatial axes."""
+    if X.dim() == 4:
+        if X.stride(3) != 1 or X.stride(2) != X.shape[3]:
+            raise ValueError("the spatial axes of X must be contiguous")
+        B, Cc, T = X.shape[0], X.shape[1], X.shape[2] * X.shape[3]
+    elif X.dim() == 3 and X.stride(2) == 1:
+        B, Cc, T = X.shape
+    else:
+        raise ValueError("X must be [B, C, H, W] or [B, C, T] with contiguous tokens")
+    ld_c = X.stride(1) if Cc > 1 else T
+    ld_b = X.stride(0) if B > 1 else max((Cc - 1) * ld_c + T, 1)
+    return B, Cc, T, ld_c, ld_b
+
+
+def tdq_quantize_act_blocks_chw(X: torch.Tensor, p: Params, want_clip: bool = False,
+                                out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+    """tdq_quantize_act_blocks on a feature map X[B, C, H, W] read in place:
+    -> (Qx[B*H*W, ld_q], block_scale[B*H*W, KB], block_clip or None)."""
+    B, Cc, T, ld_c, ld_b = _bct(X)
+    KB = (Cc + 31) // 32
+    if out is None:
+        Qx = torch.zeros((B * T, packed_row_bytes(Cc)), dtype=torch.uint8, device=X.device)
+        bs = torch.empty((B * T, KB), dtype=torch.float32, device=X.device)
+    else:
+        Qx, bs = out
+    bc = torch.empty((B * T, KB), dtype=torch.float32, device=X.device) if want_clip else None
+    rc = lib().tdq_quantize_act_blocks_chw(X.data_ptr(), _dt(X), B, Cc, T, ld_c, ld_b, C.byref(p),
+                                           Qx.data_ptr(), Qx.stride(0), bs.data_ptr(), _ptr(bc),
+                                           bs.stride(0), _stream())
+    _check(rc, "tdq_quantize_act_blocks_chw")
+    return Qx, bs, bc
 
 
 def tdq_tokenize_chw(X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -24,7 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
-            "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw",
+            "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -193,6 +193,26 @@ def test_tokenize_rejects_bad_arguments():
     assert call(ld_b=95) == tdq.ERR_SHAPE          # (C-1)*ld_c + T = 96
     assert call(ld_xt=7) == tdq.ERR_SHAPE
     assert call(X=FAKE + 1) == tdq.ERR_ALIGN
+
+
+def test_conv_layout_block_quantizer_rejects_bad_arguments():
+    f = tdq.lib().tdq_quantize_act_blocks_chw
+    p = tdq.block_params()
+
+    def call(q=None, X=FAKE, dt=0, B=2, Cc=40, T=12, ld_c=12, ld_b=480, Q=FAKE, ld_q=20, bs=FAKE,
+             bc=None, ld_s=2):
+        return f(X, dt, B, Cc, T, ld_c, ld_b, C.byref(q or p), Q, ld_q, bs, bc, ld_s, None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(bs=None) == tdq.ERR_NULL
+    assert call(dt=4) == tdq.ERR_DTYPE
+    assert call(T=0) == tdq.ERR_SHAPE
+    assert call(ld_c=11) == tdq.ERR_SHAPE
+    assert call(ld_b=479) == tdq.ERR_SHAPE         # (C-1)*ld_c + T = 480
+    assert call(ld_q=19) == tdq.ERR_SHAPE
+    assert call(ld_s=1) == tdq.ERR_SHAPE
+    assert call(X=FAKE + 1) == tdq.ERR_ALIGN
+    assert call(q=tdq.default_params()) == tdq.ERR_UNSUPPORTED
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -86,3 +86,61 @@ def test_conv_layout_through_both_token_paths():
                                            O.Params(n_groups=1, flags=2))
     assert np.array_equal(bc.cpu().numpy(), cb) and np.array_equal(bs.cpu().numpy(), sb)
     assert np.array_equal(U.unpack_device_codes(Qb, C), qb_ref)
+
+
+def _blocks_view(a, C):
+    M = a.shape[0]
+    KB = -(-C // 32)
+    out = np.zeros((M, KB * 32), dtype=a.dtype)
+    out[:, :C] = a
+    return out.reshape(M * KB, 32)
+
+
+@pytest.mark.parametrize("B,C,H,W,dtype,kw", [
+    (2, 128, 16, 8, np.float16, {}),                 # one channel tile, one token tile
+    (1, 320, 22, 22, np.float16, {}),                # ragged in both axes
+    (3, 100, 7, 9, np.float16, {}),                  # last block partly padding, unaligned rows
+    (1, 40, 5, 5, np.float16, dict(flags=2)),
+    (1, 7, 3, 3, np.float16, dict(flags=0)),
+    (2, 256, 16, 16, np.float16, dict(flags=2, zr=0.3)),        # bisection route (rank 10)
+    (1, 192, 12, 12, np.float16, dict(flags=3, base_pct=0.9)),
+    (2, 64, 8, 8, np.float32, {}),
+    (1, 130, 11, 13, np.float32, dict(flags=2)),
+    (1, 1024, 32, 32, np.float16, {}),               # eight channel tiles
+])
+def test_blocks_quantizer_reads_conv_layout_directly(B, C, H, W, dtype, kw):
+    """The fused 4-D branch: same bits as the token-major sweep on the tokenized map, and
+    the oracle's Algorithm 1 on the oracle's tokens."""
+    _say(f"[blocks-chw] B={B} C={C} H={H} W={W} dtype={dtype.__name__} {kw}")
+    X = _feature_map(B, C, H, W, dtype, 6)
+    p = tdq.block_params(**kw)
+    Xd = torch.from_numpy(X).to(U.dev())
+    Q, bs, bc = tdq.tdq_quantize_act_blocks_chw(Xd, p, want_clip=True)
+    Q2, bs2, bc2 = tdq.tdq_quantize_act_blocks(tdq.tdq_tokenize_chw(Xd), p, want_clip=True)
+    torch.cuda.synchronize()
+    assert torch.equal(Q, Q2) and torch.equal(bs, bs2) and torch.equal(bc, bc2)
+    Xt = O.tokenize_chw(X).reshape(B * H * W, C)
+    op = O.Params(n_groups=1, flags=p.flags & 3, tau=p.tau, zr=p.zr, base_pct=p.base_pct)
+    _, q_ref, clip, scale = O.dstg_dcrp_blocks(Xt, 32, op)
+    cg, sg = bc.cpu().numpy(), bs.cpu().numpy()
+    if not (p.flags & tdq.FLAG_C1):
+        assert np.array_equal(cg, clip) and np.array_equal(sg, scale)
+    assert np.allclose(cg, clip, rtol=U.SCALE_RTOL, atol=0)
+    assert np.allclose(sg, scale, rtol=U.SCALE_RTOL, atol=0)
+    exact = np.array_equal(cg, clip) and np.array_equal(sg, scale)
+    U.assert_codes_match(_blocks_view(U.unpack_device_codes(Q, C), C), _blocks_view(q_ref, C),
+                         _blocks_view(Xt.astype(np.float32), C), clip.reshape(-1),
+                         scale.reshape(-1), exact)
+
+
+def test_blocks_quantizer_conv_layout_strided_view():
+    B, C, H, W = 2, 72, 6, 12
+    X = _feature_map(B, C + 3, H + 1, W, np.float16, 7)
+    Xd = torch.from_numpy(X).to(U.dev())[:, 1:1 + C, :H, :]
+    p = tdq.block_params(flags=2)
+    Q, bs, bc = tdq.tdq_quantize_act_blocks_chw(Xd, p, want_clip=True)
+    torch.cuda.synchronize()
+    Xt = O.tokenize_chw(X[:, 1:1 + C, :H, :]).reshape(B * H * W, C)
+    _, q_ref, clip, scale = O.dstg_dcrp_blocks(Xt, 32, O.Params(n_groups=1, flags=2))
+    assert np.array_equal(bc.cpu().numpy(), clip) and np.array_equal(bs.cpu().numpy(), scale)
+    assert np.array_equal(U.unpack_device_codes(Q, C), q_ref)
