@@ -266,7 +266,28 @@ def blocks_leg(layers, torch, tdq, iters=10, warm=5):
                        "frac": round(lane_ops / (tl * 1e-3) / 1e12 / PEAK_VALU_TLOPS, 4),
                        "tops_int8": round(L.gemm_ops / (tl * 1e-3) / 1e12, 1)}})
         tot += tq + tl
-        del bs, Q
+        # the same buffer read as a feature map [B, C, 64, 64] (the 4-D branch): re-layout
+        # alone, and the per-block sweep reading the map in place
+        Xc = L.X.reshape(lc.B, lc.C, 64, lc.T // 64)
+        Xt = torch.empty_like(L.X)
+        tt = tc = 0.0
+        for it in range(warm + iters):
+            ev[0].record()
+            tdq.tdq_tokenize_chw(Xc, out=Xt)
+            ev[1].record()
+            tdq.tdq_quantize_act_blocks_chw(Xc, p, out=(Q, bs))
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it >= warm:
+                tt += ev[0].elapsed_time(ev[1])
+                tc += ev[1].elapsed_time(ev[2])
+        tt, tc = tt / iters, tc / iters
+        xb = e * (2 if lc.dtype == "f16" else 4)
+        res["layers"][-1]["conv_layout"] = {
+            "tokenize_ms": round(tt, 4), "tokenize_gbs": round(2 * xb / (tt * 1e-3) / 1e9, 1),
+            "quantize_blocks_chw_ms": round(tc, 4),
+            "quantize_blocks_chw_gbs": round(qbytes / (tc * 1e-3) / 1e9, 1)}
+        del bs, Q, Xt
     res["ms_per_pass"] = round(tot, 4)
     # the token-set path overwrote nothing it needs: L.Y is rewritten by the next step
     return res

@@ -60,6 +60,7 @@ typedef enum {
 #define TDQ_FLAG_EXACT_SELECT 256u
 
 #define TDQ_MAX_GROUPS 256
+#define TDQ_FUSED_MAX_GROUPS 64 /* most token sets per image of tdq_calibrate_quantize_fused */
 #define TDQ_BLOCK 32 /* channel block g of the per-(token, block) entry points (Sec. 5 setup) */
 
 /* Hyper-parameters (Supp. "Default Hyperparameters": tau = 1.0, zr = 0.2). */
@@ -193,6 +194,23 @@ int tdq_quantize_act_blocks_chw(const void* X, tdq_dtype dt, int32_t B, int32_t 
                                 int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx,
                                 int64_t ld_q, float* block_scale, float* block_clip, int64_t ld_s,
                                 void* stream);
+
+/*
+ * tdq_calibrate_groups followed by tdq_quantize_act in ONE launch, for shapes where launch
+ * latency rather than bandwidth sets the time (up to a few hundred kilobytes per image;
+ * it is correct for any size, one workgroup per image).  Same definitions and outputs:
+ * group_id, clip, scale, stats (or NULL) as from tdq_calibrate_groups, Qx as from
+ * tdq_quantize_act with those radii.  The rank of every set is found by a radix select
+ * on LDS histograms (exact).  n_groups <= TDQ_FUSED_MAX_GROUPS, else
+ * TDQ_ERR_UNSUPPORTED.  image_flags [B] out or NULL: TDQ_DEV_NONFINITE for an image that
+ * holds an Inf or NaN (the workspace's status word is not written).  workspace as for
+ * tdq_calibrate_groups (tdq_workspace_bytes).
+ */
+int tdq_calibrate_quantize_fused(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                                 int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                                 float* scale, tdq_group_stats* stats, uint32_t* image_flags,
+                                 uint8_t* Qx, int64_t ld_q, void* workspace, size_t workspace_bytes,
+                                 void* stream);
 
 /*
  * Diagnostics of the paper's Sec. 3.2 per (image, token set), as exact element counts

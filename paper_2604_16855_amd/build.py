@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtdq.so")
-SOURCES = ["tdq_api.hip", "tdq_act.hip", "tdq_rank.hip", "tdq_blocks.hip", "tdq_layout.hip",
+SOURCES = ["tdq_api.hip", "tdq_act.hip", "tdq_rank.hip", "tdq_blocks.hip", "tdq_layout.hip", "tdq_fused.hip",
            "tdq_gemm.hip"]
 
 FLAGS = [

@@ -216,130 +216,28 @@ hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long lo
 // ---------------------------------------------------------------------------
 constexpr int kAssignThreads = 1024;
 
-__device__ __forceinline__ u32 wave_max_u32(u32 v) { return xor_reduce_max<64>(v); }
-__device__ __forceinline__ u32 wave_min_u32(u32 v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) {
-    u32 o = (u32)__shfl_xor((int)v, m, 64);
-    v = o < v ? o : v;
-  }
-  return v;
-}
-
 __global__ __launch_bounds__(kAssignThreads) void k_assign(
     const float* __restrict__ r, const double* __restrict__ s1, const double* __restrict__ s2,
     int T, int G, int* __restrict__ gid, SetAcc* __restrict__ part, u32* __restrict__ img_flag,
     u32* __restrict__ status) {
   extern __shared__ __attribute__((aligned(16))) unsigned char assign_lds[];
   __shared__ u32 s_min[kAssignThreads / 64], s_max[kAssignThreads / 64];
-  __shared__ u32 s_lo, s_hi;
+  __shared__ u32 s_lohi[2];
   SetAcc* wacc = reinterpret_cast<SetAcc*>(assign_lds);     // [NW][G]
   // S workgroups share an image: each finds the image's key range over all T tokens
   // (cheap) and then handles every S-th group of token batches
   const int b = blockIdx.y, sub = blockIdx.x, S = gridDim.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   const int NW = blockDim.x >> 6;
-  const float* rb = r + (long long)b * T;
-  const double* s1b = s1 + (long long)b * T;
-  const double* s2b = s2 + (long long)b * T;
-  int* gb = gid + (long long)b * T;
-
-  for (int i = tid; i < NW * G; i += blockDim.x) {
-    SetAcc z;
-    z.s1 = 0.0; z.s2 = 0.0; z.cnt = 0; z.kmax = 0;
-    wacc[i] = z;
-  }
-  u32 kmin = 0xFFFFFFFFu, kmax = 0;
-  for (int t = tid; t < T; t += blockDim.x) {
-    const u32 k = __float_as_uint(rb[t]);
-    kmin = k < kmin ? k : kmin;
-    kmax = k > kmax ? k : kmax;
-  }
-  kmin = wave_min_u32(kmin);
-  kmax = wave_max_u32(kmax);
-  if (lane == 0) { s_min[wave] = kmin; s_max[wave] = kmax; }
-  __syncthreads();
-  if (tid == 0) {
-    u32 lo = 0xFFFFFFFFu, hi = 0;
-    for (int w = 0; w < NW; ++w) {
-      lo = s_min[w] < lo ? s_min[w] : lo;
-      hi = s_max[w] > hi ? s_max[w] : hi;
-    }
-    const u32 span = (u32)kOctaveFloor << 23;
-    const u32 floor_key = hi > span ? hi - span : 0u;
-    s_lo = lo > floor_key ? lo : floor_key;
-    s_hi = hi;
-    if (sub == 0) {
-      img_flag[b] = hi >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
-      if (b == 0) {                       // counts of sets the single-sweep select misses
-        status[1] = 0u;
-        status[2] = 0u;
-      }
+  assign_tokens(r + (long long)b * T, s1 + (long long)b * T, s2 + (long long)b * T, T, G,
+                gid + (long long)b * T, wacc, s_min, s_max, s_lohi, sub, S);
+  if (tid == 0 && sub == 0) {
+    img_flag[b] = s_lohi[1] >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
+    if (b == 0) {                         // counts of sets the single-sweep select misses
+      status[1] = 0u;
+      status[2] = 0u;
     }
   }
-  __syncthreads();
-  const u32 lo = s_lo, hi = s_hi;
-  const unsigned long long width = (unsigned long long)(hi - lo) + 1ull;
-
-  // Wavefront w of workgroup `sub` owns the token batches sub NW + w, + S NW, ... (64
-  // tokens each).  Inside a
-  // batch the tokens of one set are summed with a fixed xor tree and added to the
-  // wavefront's accumulator of that set, sets in order of first appearance: every
-  // floating-point sum has a fixed order, so the result is bitwise repeatable.
-  SetAcc* mine = wacc + wave * G;
-  const int n_batches = (T + 63) / 64;
-  // the loads of the next batch are issued before the current one is reduced
-  u32 nk = 0;
-  double n1 = 0.0, n2 = 0.0;
-  const int bt0 = sub * NW + wave, bstep = S * NW;
-  if (bt0 < n_batches && bt0 * 64 + lane < T) {
-    const int t = bt0 * 64 + lane;
-    nk = __float_as_uint(rb[t]);
-    n1 = s1b[t];
-    n2 = s2b[t];
-  }
-  for (int bt = bt0; bt < n_batches; bt += bstep) {
-    const int t = bt * 64 + lane;
-    const bool live = t < T;
-    const u32 k = nk;
-    const double v1 = n1, v2 = n2;
-    {
-      const int tn = t + bstep * 64;
-      if (bt + bstep < n_batches && tn < T) {
-        nk = __float_as_uint(rb[tn]);
-        n1 = s1b[tn];
-        n2 = s2b[tn];
-      }
-    }
-    int g = -1;
-    if (live) {
-      g = 0;
-      if (G > 1 && hi != lo && k > lo)
-        g = (int)(((unsigned long long)(k - lo) * (unsigned long long)G) / width);
-      gb[t] = g;
-    }
-    unsigned long long todo = __ballot(live);
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int gg = __builtin_amdgcn_readlane(g, leader);
-      const bool sel = g == gg;
-      const unsigned long long m = __ballot(sel);
-      const double a1 = group_sum_f64<64>(sel ? v1 : 0.0);     // totals land in lane 63
-      const double a2 = group_sum_f64<64>(sel ? v2 : 0.0);
-      const u32 km = group_max_u32<64>(sel ? k : 0u);
-      if (lane == 63) {
-        SetAcc a = mine[gg];
-        a.s1 += a1;
-        a.s2 += a2;
-        a.cnt += (u32)__popcll(m);
-        a.kmax = km > a.kmax ? km : a.kmax;
-        mine[gg] = a;
-      }
-      todo &= ~m;
-    }
-  }
-  __syncthreads();
-
   for (int g = tid; g < G; g += blockDim.x) {      // merge the wavefronts in a fixed order
     SetAcc m;
     m.s1 = 0.0; m.s2 = 0.0; m.cnt = 0; m.kmax = 0;

@@ -247,6 +247,35 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
   return TDQ_OK;
 }
 
+int tdq_calibrate_quantize_fused(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                                 int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                                 float* scale, tdq_group_stats* stats, uint32_t* image_flags,
+                                 uint8_t* Qx, int64_t ld_q, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  if (!X || !p || !group_id || !clip || !scale || !Qx || !workspace) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  const int G = p->n_groups;
+  if (G > TDQ_FUSED_MAX_GROUPS) return TDQ_ERR_UNSUPPORTED;
+  if (ld_q < (C + 1) / 2) return TDQ_ERR_SHAPE;
+  const WorkspaceLayout wl = make_layout(B, T, G, make_level_plan(dt, G));
+  if (workspace_bytes < wl.total) return TDQ_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return TDQ_ERR_WORKSPACE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(image_flags) & 3) return TDQ_ERR_ALIGN;
+  char* ws = static_cast<char*>(workspace);
+  if (launch_fused_small(X, dt, B, T, C, ld_x, G, make_scalars(p),
+                         reinterpret_cast<float*>(ws + wl.r), reinterpret_cast<double*>(ws + wl.s1),
+                         reinterpret_cast<double*>(ws + wl.s2), group_id, clip, scale, stats,
+                         image_flags, Qx, ld_q, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
 int tdq_tokenize_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T, int64_t ld_c,
                      int64_t ld_b, void* Xt, int64_t ld_xt, void* stream) {
   if (!X || !Xt) return TDQ_ERR_NULL;

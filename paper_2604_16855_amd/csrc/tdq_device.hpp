@@ -168,6 +168,119 @@ __device__ inline GroupWork merge_partials(const SetAcc* __restrict__ part, int 
   return w;
 }
 
+// ---------------------------------------------------------------------------
+// Token -> token set, and the per-set sums of one image (or of every S-th group of its
+// token batches), by ALL threads of a workgroup of NW wavefronts:
+//   key_t = bits(r_t); hi = max key; lo = max(min key, hi - 24 octaves);
+//   gid_t = key_t <= lo ? 0 : (key_t - lo) * G / (hi - lo + 1)      (64-bit integers)
+// wacc [NW][G], s_min / s_max [NW] and s_lohi [2] are LDS; on return (after a barrier)
+// wacc holds every wavefront's per-set record and s_lohi = {lo, hi}.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ u32 wave_max_u32(u32 v) { return xor_reduce_max<64>(v); }
+__device__ __forceinline__ u32 wave_min_u32(u32 v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) {
+    u32 o = (u32)__shfl_xor((int)v, m, 64);
+    v = o < v ? o : v;
+  }
+  return v;
+}
+
+__device__ inline void assign_tokens(const float* __restrict__ rb, const double* __restrict__ s1b,
+                                     const double* __restrict__ s2b, int T, int G,
+                                     int* __restrict__ gb, SetAcc* wacc, u32* s_min, u32* s_max,
+                                     u32* s_lohi, int sub, int S) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NW = blockDim.x >> 6;
+  for (int i = tid; i < NW * G; i += blockDim.x) {
+    SetAcc z;
+    z.s1 = 0.0; z.s2 = 0.0; z.cnt = 0; z.kmax = 0;
+    wacc[i] = z;
+  }
+  u32 kmin = 0xFFFFFFFFu, kmax = 0;
+  for (int t = tid; t < T; t += blockDim.x) {
+    const u32 k = __float_as_uint(rb[t]);
+    kmin = k < kmin ? k : kmin;
+    kmax = k > kmax ? k : kmax;
+  }
+  kmin = wave_min_u32(kmin);
+  kmax = wave_max_u32(kmax);
+  if (lane == 0) { s_min[wave] = kmin; s_max[wave] = kmax; }
+  __syncthreads();
+  if (tid == 0) {
+    u32 lo = 0xFFFFFFFFu, hi = 0;
+    for (int w = 0; w < NW; ++w) {
+      lo = s_min[w] < lo ? s_min[w] : lo;
+      hi = s_max[w] > hi ? s_max[w] : hi;
+    }
+    const u32 span = (u32)kOctaveFloor << 23;
+    const u32 floor_key = hi > span ? hi - span : 0u;
+    s_lohi[0] = lo > floor_key ? lo : floor_key;
+    s_lohi[1] = hi;
+  }
+  __syncthreads();
+  const u32 lo = s_lohi[0], hi = s_lohi[1];
+  const unsigned long long width = (unsigned long long)(hi - lo) + 1ull;
+
+  // Wavefront w of workgroup `sub` owns the token batches sub NW + w, + S NW, ... (64
+  // tokens each).  Inside a batch the tokens of one set are summed with a fixed tree and
+  // added to the wavefront's accumulator of that set, sets in order of first appearance:
+  // every floating-point sum has a fixed order, so the result is bitwise repeatable.
+  SetAcc* mine = wacc + wave * G;
+  const int n_batches = (T + 63) / 64;
+  // the loads of the next batch are issued before the current one is reduced
+  u32 nk = 0;
+  double n1 = 0.0, n2 = 0.0;
+  const int bt0 = sub * NW + wave, bstep = S * NW;
+  if (bt0 < n_batches && bt0 * 64 + lane < T) {
+    const int t = bt0 * 64 + lane;
+    nk = __float_as_uint(rb[t]);
+    n1 = s1b[t];
+    n2 = s2b[t];
+  }
+  for (int bt = bt0; bt < n_batches; bt += bstep) {
+    const int t = bt * 64 + lane;
+    const bool live = t < T;
+    const u32 k = nk;
+    const double v1 = n1, v2 = n2;
+    {
+      const int tn = t + bstep * 64;
+      if (bt + bstep < n_batches && tn < T) {
+        nk = __float_as_uint(rb[tn]);
+        n1 = s1b[tn];
+        n2 = s2b[tn];
+      }
+    }
+    int g = -1;
+    if (live) {
+      g = 0;
+      if (G > 1 && hi != lo && k > lo)
+        g = (int)(((unsigned long long)(k - lo) * (unsigned long long)G) / width);
+      gb[t] = g;
+    }
+    unsigned long long todo = __ballot(live);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int gg = __builtin_amdgcn_readlane(g, leader);
+      const bool sel = g == gg;
+      const unsigned long long m = __ballot(sel);
+      const double a1 = group_sum_f64<64>(sel ? v1 : 0.0);     // totals land in lane 63
+      const double a2 = group_sum_f64<64>(sel ? v2 : 0.0);
+      const u32 km = group_max_u32<64>(sel ? k : 0u);
+      if (lane == 63) {
+        SetAcc a = mine[gg];
+        a.s1 += a1;
+        a.s2 += a2;
+        a.cnt += (u32)__popcll(m);
+        a.kmax = km > a.kmax ? km : a.kmax;
+        mine[gg] = a;
+      }
+      todo &= ~m;
+    }
+  }
+  __syncthreads();
+}
+
 // Clears the radix-level histograms of set idx (threads tid, tid + nthreads, ...).
 __device__ inline void clear_level_hists(u32* __restrict__ hist, const LevelPlan& lp,
                                          long long groups_total, long long idx, int tid,

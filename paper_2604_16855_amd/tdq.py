@@ -89,6 +89,9 @@ def lib() -> C.CDLL:
     L.tdq_quantize_act_blocks_chw.restype = C.c_int
     L.tdq_quantize_act_blocks_chw.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64,
                                               C.POINTER(Params), vp, i64, vp, vp, i64, vp]
+    L.tdq_calibrate_quantize_fused.restype = C.c_int
+    L.tdq_calibrate_quantize_fused.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params),
+                                               vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -176,6 +179,36 @@ def tdq_calibrate_groups(X: torch.Tensor, p: Params, workspace: Optional[torch.T
                                     workspace.data_ptr(), workspace.numel(), _stream())
     _check(rc, "tdq_calibrate_groups")
     return gid, clip, scale, stats, workspace
+
+
+def tdq_calibrate_quantize_fused(X: torch.Tensor, p: Params,
+                                 workspace: Optional[torch.Tensor] = None,
+                                 want_stats: bool = False, out=None):
+    """One launch for tdq_calibrate_groups + tdq_quantize_act (small shapes).
+    -> (group_id[B,T], clip[B,G], scale[B,G], stats or None, image_flags[B] int32, Qx,
+    workspace)."""
+    B, T, Cc, ld = _btc(X)
+    G = p.n_groups
+    dev = X.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, Cc, _dt(X), p, dev)
+    if out is None:
+        gid = torch.empty((B, T), dtype=torch.int32, device=dev)
+        clip = torch.empty((B, G), dtype=torch.float32, device=dev)
+        scale = torch.empty((B, G), dtype=torch.float32, device=dev)
+        flags = torch.empty((B,), dtype=torch.int32, device=dev)
+        Qx = torch.zeros((B * T, packed_row_bytes(Cc)), dtype=torch.uint8, device=dev)
+    else:
+        gid, clip, scale, flags, Qx = out
+    stats = (torch.empty((B * G, C.sizeof(GroupStats)), dtype=torch.uint8, device=dev)
+             if want_stats else None)
+    rc = lib().tdq_calibrate_quantize_fused(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p),
+                                            gid.data_ptr(), clip.data_ptr(), scale.data_ptr(),
+                                            _ptr(stats), flags.data_ptr(), Qx.data_ptr(),
+                                            Qx.stride(0), workspace.data_ptr(), workspace.numel(),
+                                            _stream())
+    _check(rc, "tdq_calibrate_quantize_fused")
+    return gid, clip, scale, stats, flags, Qx, workspace
 
 
 def device_status(workspace: torch.Tensor) -> int:

@@ -25,6 +25,7 @@ def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
             "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
+            "tdq_calibrate_quantize_fused",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -213,6 +214,28 @@ def test_conv_layout_block_quantizer_rejects_bad_arguments():
     assert call(ld_s=1) == tdq.ERR_SHAPE
     assert call(X=FAKE + 1) == tdq.ERR_ALIGN
     assert call(q=tdq.default_params()) == tdq.ERR_UNSUPPORTED
+
+
+def test_fused_entry_rejects_bad_arguments():
+    f = tdq.lib().tdq_calibrate_quantize_fused
+    p = tdq.default_params()
+
+    def call(q=None, X=FAKE, dt=0, B=1, T=8, Cc=8, ld=8, gid=FAKE, clip=FAKE, scale=FAKE, flags=None,
+             Q=FAKE, ld_q=4, ws=FAKE, wsb=1 << 30):
+        return f(X, dt, B, T, Cc, ld, C.byref(q or p), gid, clip, scale, None, flags, Q, ld_q, ws, wsb,
+                 None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(Q=None) == tdq.ERR_NULL
+    assert call(ws=None) == tdq.ERR_NULL
+    assert call(dt=5) == tdq.ERR_DTYPE
+    assert call(T=0) == tdq.ERR_SHAPE
+    assert call(ld_q=3) == tdq.ERR_SHAPE
+    assert call(wsb=16) == tdq.ERR_WORKSPACE
+    assert call(ws=FAKE + 8) == tdq.ERR_WORKSPACE
+    assert call(flags=FAKE + 2) == tdq.ERR_ALIGN
+    assert call(q=tdq.default_params(n_groups=65)) == tdq.ERR_UNSUPPORTED
+    assert call(q=tdq.block_params()) == tdq.ERR_UNSUPPORTED
 
 
 def test_bench_refuses_more_than_one_gpu():
