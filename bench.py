@@ -325,10 +325,11 @@ def quality(L, torch, tdq):
     out["tdq"]["bind_counts"] = {n: int((st["bind"] == i).sum()) for i, n in enumerate(names)}
     used = st["n"] > 0
     out["tdq"]["eta_max"] = round(float((st["scale"][used] / st["sigma"][used]).max()), 4)
-    # range disparity D(X) = max |x| / median over tokens of the per-token median |x|
-    ax = L.X.reshape(lc.M, lc.C).abs().float()
-    out["range_disparity"] = round(float(ax.max() / ax.median(dim=1).values.median()), 1)
-    del ax
+    # range disparity D(X) = max |x| / median_t median_c |x| (Eq. range_disparity) of every
+    # image, on the device; reported: the median and the largest over the batch
+    D, _, _ = tdq.tdq_range_disparity(L.X)
+    out["range_disparity"] = {"median_over_images": round(float(D.median()), 1),
+                              "max_over_images": round(float(D.max()), 1)}
     p1 = tdq.default_params(1, flags=0)
     gid1, clip1, scale1, _, _ = tdq.tdq_calibrate_groups(L.X, p1)
     Q1 = tdq.tdq_quantize_act(L.X, p1, gid1, clip1, scale1)

@@ -150,6 +150,19 @@ int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t 
                      const float* scale, uint8_t* Qx, int64_t ld_q, void* stream);
 
 /*
+ * Range disparity of Eq. (range_disparity), per image:
+ *   D[b] = max |x| / median_t median_c |x|,
+ * medians taken as the ceil(n/2)-th smallest value (the paper's rank rule k = ceil(p n) at
+ * p = 1/2; the paper does not say which median it means for an even count), found exactly.
+ * D is +Inf where the denominator is 0.  X [B*T, ld_x]; token_median, token_max [B*T] out
+ * (the per-token median and maximum of |x|, also scratch of the call); disparity,
+ * max_abs [B] out.
+ */
+int tdq_range_disparity(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                        float* token_median, float* token_max, float* disparity, float* max_abs,
+                        void* stream);
+
+/*
  * Convolutional feature maps as tokens (Supp. implementation details: the dynamic path
  * maps X[B, C, H, W] to X'[B, HW, C] and applies DSTG + DCRP along the channels).
  * Exact re-layout, element (b, c, t) of X -> row b*T + t, column c of Xt, T = H*W; every

@@ -379,6 +379,26 @@ def zero_bin_mass(x: np.ndarray, scale) -> float:
     return float(np.count_nonzero(np.abs(x) <= np.asarray(scale, np.float64) / 2) / x.size)
 
 
+def range_disparity(X: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Range disparity of Eq. (range_disparity), per image of X[B, T, C]:
+    D = max |x| / median_t median_c |x|.  The paper does not say which median it takes for
+    an even count; here it is the lower one, the ceil(n/2)-th smallest, i.e. the paper's
+    own rank rule k = ceil(p n) at p = 1/2 (and what `torch.median` returns).
+    Returns (D[B] f32 (inf where the denominator is 0), token_median[B, T] f32,
+    max_abs[B] f32)."""
+    A = np.abs(np.asarray(X, dtype=np.float32))
+    B, T, C = A.shape
+    tok = np.empty((B, T), dtype=np.float32)
+    for b in range(B):
+        for t in range(T):
+            tok[b, t] = kth_smallest(A[b, t], quantile_rank(0.5, C))
+    den = np.array([kth_smallest(tok[b], quantile_rank(0.5, T)) for b in range(B)], dtype=np.float32)
+    mx = A.reshape(B, -1).max(axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        D = np.where(den > 0, mx / den, np.float32(np.inf)).astype(np.float32)
+    return D, tok, mx
+
+
 def sqnr_db(x: np.ndarray, xhat: np.ndarray) -> float:
     x = np.asarray(x, dtype=np.float64)
     e = x - np.asarray(xhat, dtype=np.float64)

@@ -696,6 +696,150 @@ hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, l
 }
 
 // ---------------------------------------------------------------------------
+// Range disparity D(X) = max |x| / median_t median_c |x| (Eq. range_disparity), per
+// image.  Medians are lower medians, the ceil(n/2)-th smallest (the rank rule
+// k = ceil(p n) at p = 1/2), found exactly by a radix select on the magnitude bit
+// patterns: k_row_median, a wavefront per token over its C channels; k_image_disparity,
+// a workgroup per image over its T token medians.
+// ---------------------------------------------------------------------------
+// One step of a radix select by the lanes of ONE wavefront on a 256-bin LDS histogram
+// (already filled): finds the digit where the running count first reaches k_rem,
+// returns it in every lane and lowers k_rem by the count below it.
+__device__ __forceinline__ u32 wave_pick_digit(const u32* h, long long& k_rem) {
+  const int lane = threadIdx.x & 63;
+  const uint4 hb = *reinterpret_cast<const uint4*>(&h[4 * lane]);
+  const u32 c4[4] = {hb.x, hb.y, hb.z, hb.w};
+  const long long mine = (long long)c4[0] + c4[1] + c4[2] + c4[3];
+  long long incl = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const long long o = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += o;
+  }
+  const unsigned long long reached = __ballot(incl >= k_rem);
+  const int first = reached ? __ffsll((long long)reached) - 1 : 63;
+  long long below = incl - mine;
+  int j = 0;
+  for (; j < 3; ++j) {
+    if (below + (long long)c4[j] >= k_rem) break;
+    below += (long long)c4[j];
+  }
+  const u32 digit = (u32)__shfl((int)(4 * lane + j), first, 64);
+  below = __shfl(below, first, 64);
+  k_rem -= below;
+  return digit;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_row_median(const T* __restrict__ X, long long ld, int M, int C,
+                                                    float* __restrict__ med, float* __restrict__ rmax) {
+  constexpr bool F16 = sizeof(T) == 2;
+  constexpr int kLevels = F16 ? 2 : 4;
+  constexpr int kBits = F16 ? 15 : 31;
+  __shared__ __attribute__((aligned(16))) u32 hist[4][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long row_raw = (long long)blockIdx.x * 4 + wave;
+  const bool valid = row_raw < M;                  // a wavefront without a row works on the last one
+  const T* xp = X + (valid ? row_raw : (long long)(M - 1)) * ld;
+  u32* h = hist[wave];
+  long long k_rem = ((long long)C + 1) / 2;
+  u32 prefix = 0, kmax = 0;
+#pragma unroll 1
+  for (int lev = 0; lev < kLevels; ++lev) {
+    const int done = 8 * lev;
+    const int bits = (lev == kLevels - 1) ? 7 : 8;
+    const int shift = kBits - done - bits;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[lane + 64 * i] = 0;
+    __syncthreads();
+    for (int c = lane; c < C; c += 64) {
+      const u32 key = Elem<T>::key(xp[c]);
+      if (lev == 0) kmax = key > kmax ? key : kmax;
+      if (done == 0 || (key >> (kBits - done)) == prefix)
+        atomicAdd(&h[(key >> shift) & ((1u << bits) - 1u)], 1u);
+    }
+    __syncthreads();
+    const u32 digit = wave_pick_digit(h, k_rem);
+    prefix = (prefix << bits) | digit;
+    __syncthreads();
+  }
+  kmax = xor_reduce_max<64>(kmax);
+  if (lane == 0 && valid) {
+    med[row_raw] = Elem<T>::key_to_float(prefix);
+    rmax[row_raw] = Elem<T>::key_to_float(kmax);
+  }
+}
+
+// med, rmax [B*T] hold non-negative floats: their bit patterns order like the values.
+__global__ __launch_bounds__(256) void k_image_disparity(const float* __restrict__ med,
+                                                         const float* __restrict__ rmax, int T,
+                                                         float* __restrict__ disparity,
+                                                         float* __restrict__ max_abs) {
+  __shared__ __attribute__((aligned(16))) u32 hist[256];
+  __shared__ u32 s_max[4], s_digit;
+  __shared__ long long s_krem;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* mb = med + (long long)b * T;
+  const float* rb = rmax + (long long)b * T;
+  u32 kmax = 0;
+  for (int t = tid; t < T; t += 256) {
+    const u32 k = __float_as_uint(rb[t]);
+    kmax = k > kmax ? k : kmax;
+  }
+  kmax = xor_reduce_max<64>(kmax);
+  if (lane == 0) s_max[wave] = kmax;
+  if (tid == 0) s_krem = ((long long)T + 1) / 2;
+  u32 prefix = 0;
+#pragma unroll 1
+  for (int lev = 0; lev < 4; ++lev) {
+    const int done = 8 * lev;
+    const int bits = lev == 3 ? 7 : 8;
+    const int shift = 31 - done - bits;
+    hist[tid] = 0;
+    __syncthreads();
+    for (int t = tid; t < T; t += 256) {
+      const u32 key = __float_as_uint(mb[t]) & 0x7FFFFFFFu;
+      if (done == 0 || (key >> (31 - done)) == prefix)
+        atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1u);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      long long k_rem = s_krem;
+      const u32 digit = wave_pick_digit(hist, k_rem);
+      if (lane == 0) { s_digit = digit; s_krem = k_rem; }
+    }
+    __syncthreads();
+    prefix = (prefix << bits) | s_digit;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    u32 k = s_max[0];
+    for (int w = 1; w < 4; ++w) k = s_max[w] > k ? s_max[w] : k;
+    const float mx = __uint_as_float(k), den = __uint_as_float(prefix);
+    max_abs[b] = mx;
+    disparity[b] = den > 0.f ? mx / den : __uint_as_float(0x7F800000u);
+  }
+}
+
+hipError_t launch_range_disparity(const void* X, tdq_dtype dt, int B, int T, int C, long long ld,
+                                  float* token_median, float* token_max, float* disparity,
+                                  float* max_abs, hipStream_t st) {
+  const long long M = (long long)B * T;
+  const unsigned grid = (unsigned)((M + 3) / 4);
+  if (dt == TDQ_F16)
+    hipLaunchKernelGGL((k_row_median<u16>), dim3(grid), dim3(256), 0, st, static_cast<const u16*>(X),
+                       ld, (int)M, C, token_median, token_max);
+  else
+    hipLaunchKernelGGL((k_row_median<float>), dim3(grid), dim3(256), 0, st,
+                       static_cast<const float*>(X), ld, (int)M, C, token_median, token_max);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_image_disparity, dim3(B), dim3(256), 0, st, token_median, token_max, T,
+                     disparity, max_abs);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Offline weight quantizer (Eq. weight_quant): one wavefront per output channel.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_quantize_weight(const float* __restrict__ W, int K,

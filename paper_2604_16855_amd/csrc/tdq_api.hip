@@ -276,6 +276,24 @@ int tdq_calibrate_quantize_fused(const void* X, tdq_dtype dt, int32_t B, int32_t
   return TDQ_OK;
 }
 
+int tdq_range_disparity(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                        float* token_median, float* token_max, float* disparity, float* max_abs,
+                        void* stream) {
+  if (!X || !token_median || !token_max || !disparity || !max_abs) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  const int rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(token_median) | reinterpret_cast<uintptr_t>(token_max) |
+       reinterpret_cast<uintptr_t>(disparity) | reinterpret_cast<uintptr_t>(max_abs)) & 3)
+    return TDQ_ERR_ALIGN;
+  if (launch_range_disparity(X, dt, B, T, C, ld_x, token_median, token_max, disparity, max_abs,
+                             static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
 int tdq_tokenize_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T, int64_t ld_c,
                      int64_t ld_b, void* Xt, int64_t ld_xt, void* stream) {
   if (!X || !Xt) return TDQ_ERR_NULL;

@@ -92,6 +92,8 @@ def lib() -> C.CDLL:
     L.tdq_calibrate_quantize_fused.restype = C.c_int
     L.tdq_calibrate_quantize_fused.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params),
                                                vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    L.tdq_range_disparity.restype = C.c_int
+    L.tdq_range_disparity.argtypes = [vp, C.c_int, i32, i32, i32, i64, vp, vp, vp, vp, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -364,6 +366,20 @@ def tdq_group_diagnostics(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor
                                      clipped.data_ptr(), _stream())
     _check(rc, "tdq_group_diagnostics")
     return zero, clipped
+
+
+def tdq_range_disparity(X: torch.Tensor):
+    """-> (D[B], token_median[B, T], max_abs[B]) f32: range disparity per image."""
+    B, T, Cc, ld = _btc(X)
+    dev = X.device
+    med = torch.empty((B, T), dtype=torch.float32, device=dev)
+    tmax = torch.empty((B, T), dtype=torch.float32, device=dev)
+    D = torch.empty((B,), dtype=torch.float32, device=dev)
+    mx = torch.empty((B,), dtype=torch.float32, device=dev)
+    rc = lib().tdq_range_disparity(X.data_ptr(), _dt(X), B, T, Cc, ld, med.data_ptr(),
+                                   tmax.data_ptr(), D.data_ptr(), mx.data_ptr(), _stream())
+    _check(rc, "tdq_range_disparity")
+    return D, med, mx
 
 
 def tdq_quantize_weight(W: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:

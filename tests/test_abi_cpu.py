@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
             "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
-            "tdq_calibrate_quantize_fused",
+            "tdq_calibrate_quantize_fused", "tdq_range_disparity",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -236,6 +236,21 @@ def test_fused_entry_rejects_bad_arguments():
     assert call(flags=FAKE + 2) == tdq.ERR_ALIGN
     assert call(q=tdq.default_params(n_groups=65)) == tdq.ERR_UNSUPPORTED
     assert call(q=tdq.block_params()) == tdq.ERR_UNSUPPORTED
+
+
+def test_range_disparity_rejects_bad_arguments():
+    f = tdq.lib().tdq_range_disparity
+
+    def call(X=FAKE, dt=0, B=1, T=8, Cc=8, ld=8, med=FAKE, tmax=FAKE, D=FAKE, mx=FAKE):
+        return f(X, dt, B, T, Cc, ld, med, tmax, D, mx, None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(D=None) == tdq.ERR_NULL
+    assert call(dt=2) == tdq.ERR_DTYPE
+    assert call(Cc=0) == tdq.ERR_SHAPE
+    assert call(ld=7) == tdq.ERR_SHAPE
+    assert call(X=FAKE + 1) == tdq.ERR_ALIGN
+    assert call(med=FAKE + 2) == tdq.ERR_ALIGN
 
 
 def test_bench_refuses_more_than_one_gpu():

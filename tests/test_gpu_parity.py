@@ -493,3 +493,34 @@ def test_group_diagnostics(case, ld_pad):
         assert np.array_equal(clipped.cpu().numpy(), cr)
         if shrink == 0.5:
             assert cr.sum() > 0
+
+
+@pytest.mark.parametrize("case,over,ld_pad", [("cfg0", {}, 0), ("cfg1", {}, 0), ("cfg2_qkv", dict(B=3), 4),
+                                              ("cfg2_fc2", dict(B=2), 0), ("cfg4_fc1_h10", dict(B=1), 0)])
+def test_range_disparity(case, over, ld_pad):
+    """D(X) of Eq. (range_disparity) on the device: per-token lower medians, their
+    median and the maximum are elements of the data, hence bit-exact; D is one binary32
+    division."""
+    lc = I.case(case, **over)
+    X, _ = I.make_activations(lc)
+    if case.startswith("cfg4"):
+        X = X[:, :300]
+    _say(f"[disparity] {case} {X.shape} {X.dtype}")
+    D, med, mx = tdq.tdq_range_disparity(U.to_device(X, ld_pad))
+    torch.cuda.synchronize()
+    Dr, medr, mxr = O.range_disparity(X)
+    assert np.array_equal(med.cpu().numpy(), medr)
+    assert np.array_equal(mx.cpu().numpy(), mxr)
+    assert np.array_equal(D.cpu().numpy(), Dr)
+
+
+def test_range_disparity_degenerate():
+    X = np.zeros((3, 5, 9), dtype=np.float16)
+    X[1] = -2.0
+    X[2, :, :4] = 1.0          # 4 of 9 channels non-zero: every token's median is 0
+    X[2, 0, 8] = 7.0
+    D, med, mx = tdq.tdq_range_disparity(U.to_device(X))
+    torch.cuda.synchronize()
+    Dr, medr, mxr = O.range_disparity(X)
+    assert np.array_equal(D.cpu().numpy(), Dr) and np.isinf(Dr[0]) and Dr[1] == 1.0 and np.isinf(Dr[2])
+    assert np.array_equal(med.cpu().numpy(), medr) and np.array_equal(mx.cpu().numpy(), mxr)

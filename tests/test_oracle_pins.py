@@ -501,3 +501,31 @@ def test_tokenize_chw_by_explicit_index_loops():
     _, _, clip, _ = O.dstg_dcrp_blocks(Xt, 32, O.Params(flags=0))
     assert clip[1, 7, 0] == np.abs(X[1, :32, 1, 2]).max()
     assert clip[1, 7, 1] == np.abs(X[1, 32:, 1, 2]).max()
+
+
+def test_range_disparity_hand_cases_and_invariances():
+    """Eq. (range_disparity) on cases worked by hand, scale invariance, and the lower
+    median against sorting."""
+    # two tokens of three channels: medians 2 and 20 -> lower median of {2, 20} is 2
+    X = np.array([[[1.0, -2.0, 3.0], [10.0, 20.0, -400.0]]], dtype=np.float32)
+    D, tok, mx = O.range_disparity(X)
+    assert tok.tolist() == [[2.0, 20.0]] and mx.tolist() == [400.0] and D.tolist() == [200.0]
+    # even counts take the lower middle value
+    X = np.array([[[4.0, 1.0, 3.0, 2.0]]], dtype=np.float32)
+    assert O.range_disparity(X)[1].tolist() == [[2.0]]
+    # a constant tensor has D = 1, an all-zero one D = inf
+    assert O.range_disparity(np.full((1, 5, 7), -3.0, np.float32))[0].tolist() == [1.0]
+    assert np.isinf(O.range_disparity(np.zeros((1, 4, 4), np.float32))[0][0])
+    rng = np.random.Generator(np.random.PCG64(81))
+    X = rng.standard_normal((3, 9, 14)).astype(np.float32)
+    D, tok, mx = O.range_disparity(X)
+    for b in range(3):
+        med = [np.sort(np.abs(X[b, t]))[(14 + 1) // 2 - 1] for t in range(9)]
+        assert tok[b].tolist() == med
+        assert D[b] == np.float32(np.abs(X[b]).max() / np.sort(med)[(9 + 1) // 2 - 1])
+    # power-of-two rescaling leaves D unchanged bit for bit; one spike raises it in proportion
+    assert np.array_equal(O.range_disparity(X * np.float32(8))[0], D)
+    Y = X.copy()
+    Y[0, 0, 0] = 1024.0
+    den0 = np.sort(O.range_disparity(Y)[1][0])[(9 + 1) // 2 - 1]
+    assert O.range_disparity(Y)[0][0] == np.float32(np.float32(1024.0) / den0)
