@@ -309,3 +309,45 @@ def test_blocks_linear_full_size_sampled():
     tol = _blocks_linear_bound(codes[rows], bscale[rows], qw, w_scale, None, K // G_BLK)
     tol = tol + 2.0 ** -11 * np.abs(Yref) + 2.0 ** -25
     assert (np.abs(Ys - Yref) <= tol).all()
+
+
+@pytest.mark.timeout(600)
+def test_blocks_path_full_size_sampled():
+    """The fc2 input of the largest configuration (32 x 4096 tokens x 4096 channels) through
+    the per-block quantizer and the block-scaled linear in the launches the measurement
+    times; sampled rows against the oracle (every block is local to its row), and sums
+    that hold at any size."""
+    lc = I.case("cfg4_fc2_h10")
+    _say("[blocks full size] generating inputs")
+    X, _ = I.make_activations(lc, workers=16)
+    W = I.make_weight(lc)
+    p = tdq.block_params()
+    B, T, C, N = lc.B, lc.T, lc.C, lc.N
+    KB = C // G_BLK
+    Xd = torch.from_numpy(X).to(U.dev())
+    Q, bs, bc = tdq.tdq_quantize_act_blocks(Xd, p, want_clip=True)
+    Qw_d, ws_d = tdq.tdq_quantize_weight(torch.from_numpy(W).to(U.dev()))
+    Y = tdq.tdq_w4a4_linear_blocks(Q, bs, C, Qw_d, ws_d)
+    torch.cuda.synchronize()
+    # any size: radius = 7 steps (or the eps floor), no radius above the block maximum
+    assert bool(((bc <= bs * 7 * (1 + 1e-6)) & (bs > 0)).all())
+    xmax = Xd.reshape(B * T, KB, G_BLK).abs().amax(dim=2).float()
+    assert bool((bc <= torch.clamp(xmax, min=1e-8)).all())
+    del xmax
+    rows = np.concatenate([np.arange(40), np.arange(B * T - 40, B * T),
+                           np.random.Generator(np.random.PCG64(8)).integers(0, B * T, 120)])
+    rd = torch.from_numpy(rows).to(U.dev())
+    Xs = X.reshape(B * T, C)[rows]
+    _say("[blocks full size] oracle on sampled rows")
+    _, q_ref, clip, scale = O.dstg_dcrp_blocks(Xs, G_BLK, _oracle_params(p))
+    cg, sg = bc[rd].cpu().numpy(), bs[rd].cpu().numpy()
+    assert np.allclose(cg, clip, rtol=U.SCALE_RTOL, atol=0) and np.allclose(sg, scale, rtol=U.SCALE_RTOL, atol=0)
+    q_gpu = O.unpack_nibbles(Q[rd].cpu().numpy()[:, :C // 2], C)
+    exact = np.array_equal(cg, clip) and np.array_equal(sg, scale)
+    U.assert_codes_match(_blocks_view(q_gpu, C), _blocks_view(q_ref, C),
+                         _blocks_view(Xs.astype(np.float32), C), clip.reshape(-1),
+                         scale.reshape(-1), exact)
+    qw, sw = O.quantize_weight(W)
+    Yref = O.blocks_linear(q_gpu, sg, G_BLK, qw, sw, None)
+    tol = _blocks_linear_bound(q_gpu, sg, qw, sw, None, KB)
+    assert (np.abs(Y[rd].cpu().numpy().astype(np.float64) - Yref) <= tol).all()
