@@ -177,6 +177,18 @@ int tdq_tokenize_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t 
                      int64_t ld_b, void* Xt, int64_t ld_xt, void* stream);
 
 /*
+ * tdq_calibrate_groups for a convolutional feature map (layout of tdq_tokenize_chw): the
+ * statistics sweep reads the map in place and writes the token-major copy Xt [B*T, ld_xt]
+ * as it goes; the rank select then runs on Xt, and so does tdq_quantize_act afterwards
+ * (pass it Xt).  Outputs as tdq_calibrate_groups on the tokenized map.  B <= 65535.
+ */
+int tdq_calibrate_groups_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
+                             int64_t ld_c, int64_t ld_b, const tdq_params* p, void* Xt,
+                             int64_t ld_xt, int32_t* group_id, float* clip, float* scale,
+                             tdq_group_stats* stats, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * The paper's own granularity (Sec. 4.2, Eq. direct_sum; Supp. Algorithm 1, steps 1-9) in
  * one sweep of X: the channel axis of every token is zero-padded to KB = ceil(C / 32)
  * blocks of g = TDQ_BLOCK channels and every (token, block) is a group of its own:

@@ -103,6 +103,72 @@ static Scalars make_scalars(const tdq_params* p) {
   return s;
 }
 
+// Everything of tdq_calibrate_groups after the per-token statistics (which are in the
+// workspace): assignment, rank select(s), projection.  X is token-major.
+static int calibrate_after_stats(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                                 int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                                 float* scale, tdq_group_stats* stats, void* workspace,
+                                 const LevelPlan& lp, const WorkspaceLayout& wl, hipStream_t st) {
+  const int G = p->n_groups;
+  char* ws = static_cast<char*>(workspace);
+  unsigned* status = reinterpret_cast<unsigned*>(ws + wl.status);
+  unsigned* img_flag = reinterpret_cast<unsigned*>(ws + wl.img_flag);
+  float* r = reinterpret_cast<float*>(ws + wl.r);
+  double* s1 = reinterpret_cast<double*>(ws + wl.s1);
+  double* s2 = reinterpret_cast<double*>(ws + wl.s2);
+  GroupWork* grp = reinterpret_cast<GroupWork*>(ws + wl.grp);
+  unsigned* hist = reinterpret_cast<unsigned*>(ws + wl.hist);
+  const Scalars sc = make_scalars(p);
+
+  void* part = ws + wl.part;
+  if (launch_assign(r, s1, s2, B, T, G, group_id, part, img_flag, status, st) != hipSuccess)
+    return TDQ_ERR_HIP;
+
+  // One rank select per rank wanted of every set: first the base radius Q_p(|x|) when a
+  // percentile is asked for (Eq. DSTG_clip), then Q_zr(|x|) with the projection.
+  // binary16 input: one sweep resolves the rank of (nearly) every set exactly, and the
+  // kernel that verifies it resolves the others.  binary32 input, or too many sets for
+  // the interval histogram: radix levels.
+  const int W = bracket_bins(G);
+  const bool single_sweep = dt == TDQ_F16 && W > 0 && (long long)T * C < (1ll << 32);
+  const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
+  Bracket* br = reinterpret_cast<Bracket*>(ws + wl.br);
+  unsigned* bhist = reinterpret_cast<unsigned*>(ws + wl.bhist);
+  const bool two_passes = sc.base_pct > 0.0;
+  for (int pass = two_passes ? kPassBase : kPassZr; pass >= kPassZr; --pass) {
+    const bool keep_base = two_passes && pass == kPassZr;
+    if (single_sweep) {
+      if (!exact_only) {
+        if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, part, sc, pass, keep_base, grp, br,
+                           bhist, st) != hipSuccess)
+          return TDQ_ERR_HIP;
+        if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
+          return TDQ_ERR_HIP;
+      } else if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
+                 hipSuccess) {
+        return TDQ_ERR_HIP;
+      }
+      if (launch_bracket_finish(X, B, T, C, ld_x, G, W, group_id, bhist, exact_only, sc, pass, grp,
+                                br, clip, scale, stats, img_flag, status, st) != hipSuccess)
+        return TDQ_ERR_HIP;
+      continue;
+    }
+    if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
+        hipSuccess)
+      return TDQ_ERR_HIP;
+    for (int l = 0; l < lp.n_levels; ++l) {
+      unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
+      if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], st) !=
+          hipSuccess)
+        return TDQ_ERR_HIP;
+      if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
+                        scale, stats, img_flag, status, pass, st) != hipSuccess)
+        return TDQ_ERR_HIP;
+    }
+  }
+  return TDQ_OK;
+}
+
 }  // namespace tdq
 
 using namespace tdq;
@@ -167,65 +233,44 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  unsigned* status = reinterpret_cast<unsigned*>(ws + wl.status);
-  unsigned* img_flag = reinterpret_cast<unsigned*>(ws + wl.img_flag);
-  float* r = reinterpret_cast<float*>(ws + wl.r);
-  double* s1 = reinterpret_cast<double*>(ws + wl.s1);
-  double* s2 = reinterpret_cast<double*>(ws + wl.s2);
-  GroupWork* grp = reinterpret_cast<GroupWork*>(ws + wl.grp);
-  unsigned* hist = reinterpret_cast<unsigned*>(ws + wl.hist);
-  const Scalars sc = make_scalars(p);
-  const int M = B * T;
-
-  if (launch_token_stats(X, dt, M, C, ld_x, r, s1, s2, st) != hipSuccess) return TDQ_ERR_HIP;
-
-  void* part = ws + wl.part;
-  if (launch_assign(r, s1, s2, B, T, G, group_id, part, img_flag, status, st) != hipSuccess)
+  if (launch_token_stats(X, dt, B * T, C, ld_x, reinterpret_cast<float*>(ws + wl.r),
+                         reinterpret_cast<double*>(ws + wl.s1),
+                         reinterpret_cast<double*>(ws + wl.s2), st) != hipSuccess)
     return TDQ_ERR_HIP;
+  return calibrate_after_stats(X, dt, B, T, C, ld_x, p, group_id, clip, scale, stats, workspace, lp,
+                               wl, st);
+}
 
-  // One rank select per rank wanted of every set: first the base radius Q_p(|x|) when a
-  // percentile is asked for (Eq. DSTG_clip), then Q_zr(|x|) with the projection.
-  // binary16 input: one sweep resolves the rank of (nearly) every set exactly, and the
-  // kernel that verifies it resolves the others.  binary32 input, or too many sets for
-  // the interval histogram: radix levels.
-  const int W = bracket_bins(G);
-  const bool single_sweep = dt == TDQ_F16 && W > 0 && (long long)T * C < (1ll << 32);
-  const bool exact_only = (p->flags & TDQ_FLAG_EXACT_SELECT) != 0;
-  Bracket* br = reinterpret_cast<Bracket*>(ws + wl.br);
-  unsigned* bhist = reinterpret_cast<unsigned*>(ws + wl.bhist);
-  const bool two_passes = sc.base_pct > 0.0;
-  for (int pass = two_passes ? kPassBase : kPassZr; pass >= kPassZr; --pass) {
-    const bool keep_base = two_passes && pass == kPassZr;
-    if (single_sweep) {
-      if (!exact_only) {
-        if (launch_bracket(X, B, T, C, ld_x, G, W, group_id, part, sc, pass, keep_base, grp, br,
-                           bhist, st) != hipSuccess)
-          return TDQ_ERR_HIP;
-        if (launch_bracket_hist(X, B, T, C, ld_x, G, W, group_id, br, bhist, st) != hipSuccess)
-          return TDQ_ERR_HIP;
-      } else if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
-                 hipSuccess) {
-        return TDQ_ERR_HIP;
-      }
-      if (launch_bracket_finish(X, B, T, C, ld_x, G, W, group_id, bhist, exact_only, sc, pass, grp,
-                                br, clip, scale, stats, img_flag, status, st) != hipSuccess)
-        return TDQ_ERR_HIP;
-      continue;
-    }
-    if (launch_finalize_groups(part, B, T, C, G, sc, pass, keep_base, grp, hist, lp, st) !=
-        hipSuccess)
-      return TDQ_ERR_HIP;
-    for (int l = 0; l < lp.n_levels; ++l) {
-      unsigned* hl = reinterpret_cast<unsigned*>(ws + wl.hist_level[l]);
-      if (launch_hist(X, dt, B, T, C, ld_x, G, group_id, grp, hl, lp.shift[l], lp.bits[l], st) !=
-          hipSuccess)
-        return TDQ_ERR_HIP;
-      if (launch_select(hl, B, G, lp.shift[l], lp.bits[l], l == lp.n_levels - 1, dt, sc, grp, clip,
-                        scale, stats, img_flag, status, pass, st) != hipSuccess)
-        return TDQ_ERR_HIP;
-    }
-  }
-  return TDQ_OK;
+int tdq_calibrate_groups_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
+                             int64_t ld_c, int64_t ld_b, const tdq_params* p, void* Xt,
+                             int64_t ld_xt, int32_t* group_id, float* clip, float* scale,
+                             tdq_group_stats* stats, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  if (!X || !Xt || !p || !group_id || !clip || !scale || !workspace) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_xt);
+  if (rc != TDQ_OK) return rc;
+  if (B > 65535) return TDQ_ERR_SHAPE;
+  if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T) return TDQ_ERR_SHAPE;
+  const int G = p->n_groups;
+  const LevelPlan lp = make_level_plan(dt, G);
+  const WorkspaceLayout wl = make_layout(B, T, G, lp);
+  if (workspace_bytes < wl.total) return TDQ_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return TDQ_ERR_WORKSPACE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz || reinterpret_cast<uintptr_t>(Xt) % esz)
+    return TDQ_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  if (launch_tokenize_stats_chw(X, dt, B, C, T, ld_c, ld_b, Xt, ld_xt,
+                                reinterpret_cast<float*>(ws + wl.r),
+                                reinterpret_cast<double*>(ws + wl.s1),
+                                reinterpret_cast<double*>(ws + wl.s2), st) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return calibrate_after_stats(Xt, dt, B, T, C, ld_xt, p, group_id, clip, scale, stats, workspace,
+                               lp, wl, st);
 }
 
 int tdq_quantize_act(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,

@@ -153,6 +153,9 @@ hipError_t launch_fused_small(const void* X, tdq_dtype dt, int B, int T, int C, 
 hipError_t launch_range_disparity(const void* X, tdq_dtype dt, int B, int T, int C, long long ld,
                                   float* token_median, float* token_max, float* disparity,
                                   float* max_abs, hipStream_t st);
+hipError_t launch_tokenize_stats_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
+                                     long long ld_b, void* Xt, long long ld_xt, float* r, double* s1,
+                                     double* s2, hipStream_t st);
 hipError_t launch_tokenize_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                long long ld_b, void* Xt, long long ld_xt, hipStream_t st);
 hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,

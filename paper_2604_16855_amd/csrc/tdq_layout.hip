@@ -102,4 +102,149 @@ hipError_t launch_tokenize_chw(const void* X, tdq_dtype dt, int B, int C, int T,
                            static_cast<float*>(Xt), ld_xt, st);
 }
 
+// ---------------------------------------------------------------------------
+// The re-layout fused with the statistics sweep of the token-set path: one read of the
+// feature map yields the token-major copy Xt AND every token's range and moments
+// (r_t = max_c |x|, sum x, sum x^2 in binary64; Sec. 4.2), so a convolutional input costs
+// the token-set path one extra write of X, not an extra read and write.  A workgroup
+// owns TT consecutive tokens of one image and walks the channel axis in tiles of 64:
+// every thread keeps the partial statistics of its 4 tokens across the tiles; at the end
+// the lanes that share a token (adjacent ones) are reduced with DPP.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_tokenize_stats_chw(
+    const T* __restrict__ X, long long ld_c, long long ld_b, int C, int T_, T* __restrict__ Xt,
+    long long ld_xt, int vin_ok, int vout_ok, float* __restrict__ r, double* __restrict__ s1,
+    double* __restrict__ s2) {
+  constexpr int E = 16 / (int)sizeof(T);
+  constexpr int TC = 64;
+  constexpr int TT = 16 * E;
+  constexpr int PITCH = TT + 8 / (int)sizeof(T);
+  constexpr int PQ = TC / E;                 // lanes per token
+  constexpr int TPP = 256 / PQ;              // tokens per pass
+  constexpr int NP = TT / TPP;               // passes = tokens per thread (4)
+  __shared__ __attribute__((aligned(16))) T tile[TC][PITCH];
+
+  const int t0 = blockIdx.x * TT, b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const T* xb = X + (long long)b * ld_b;
+  const int q = tid % PQ;
+  u32 kmax[NP];
+  double a1[NP], a2[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) { kmax[i] = 0; a1[i] = 0.0; a2[i] = 0.0; }
+
+  // the next tile's global loads are in flight while the current one is processed
+  const int lp = tid & 15, ltok = t0 + (tid & 15) * E;
+  uint4 stage[4];
+  auto load_tile = [&](int c0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = c0 + (tid >> 4) + 16 * i;
+      if (c < C && vin_ok && ltok + E <= T_) {
+        stage[i] = *reinterpret_cast<const uint4*>(xb + (long long)c * ld_c + ltok);
+      } else {
+        __attribute__((aligned(16))) T v[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+          v[k] = (c < C && ltok + k < T_) ? xb[(long long)c * ld_c + ltok + k] : (T)0;
+        stage[i] = *reinterpret_cast<const uint4*>(v);
+      }
+    }
+  };
+  load_tile(0);
+  for (int c0 = 0; c0 < C; c0 += TC) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint2* d = reinterpret_cast<uint2*>(&tile[(tid >> 4) + 16 * i][lp * E]);
+      d[0] = make_uint2(stage[i].x, stage[i].y);
+      d[1] = make_uint2(stage[i].z, stage[i].w);
+    }
+    __syncthreads();
+    if (c0 + TC < C) load_tile(c0 + TC);
+    const int c = c0 + q * E;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int tl = tid / PQ + TPP * i;
+      const int tok = t0 + tl;
+      __attribute__((aligned(16))) T v[E];
+#pragma unroll
+      for (int k = 0; k < E; ++k) v[k] = tile[q * E + k][tl];
+      // channels beyond C are zeros in the tile: they change neither maximum nor sums
+      if constexpr (sizeof(T) == 2) {
+        // as in the token-major statistics sweep: the 8 values and their squares (exact
+        // in binary32) are first summed in binary32, then accumulated in binary64
+        float p1 = 0.f, p2 = 0.f;
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+          const float f = Elem<T>::val(v[k]);
+          const u32 key = Elem<T>::key(v[k]);
+          kmax[i] = key > kmax[i] ? key : kmax[i];
+          p1 += f;
+          p2 = __builtin_fmaf(f, f, p2);
+        }
+        a1[i] += (double)p1;
+        a2[i] += (double)p2;
+      } else {
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+          const double f = (double)Elem<T>::val(v[k]);
+          const u32 key = Elem<T>::key(v[k]);
+          kmax[i] = key > kmax[i] ? key : kmax[i];
+          a1[i] += f;
+          a2[i] = fma(f, f, a2[i]);
+        }
+      }
+      if (tok < T_) {
+        T* dst = Xt + ((long long)b * T_ + tok) * ld_xt + c;
+        if (vout_ok && c + E <= C) {
+          *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(v);
+        } else {
+#pragma unroll
+          for (int k = 0; k < E; ++k)
+            if (c + k < C) dst[k] = v[k];
+        }
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const u32 km = group_max_u32<PQ>(kmax[i]);
+    const double t1 = group_sum_f64<PQ>(a1[i]);
+    const double t2 = group_sum_f64<PQ>(a2[i]);
+    const int tok = t0 + tid / PQ + TPP * i;
+    if (q == PQ - 1 && tok < T_) {               // the group's last lane holds the totals
+      const long long row = (long long)b * T_ + tok;
+      r[row] = Elem<T>::key_to_float(km);
+      s1[row] = t1;
+      s2[row] = t2;
+    }
+  }
+}
+
+template <typename T>
+static hipError_t tokenize_stats_t(const T* X, int B, int C, int T_, long long ld_c, long long ld_b,
+                                   T* Xt, long long ld_xt, float* r, double* s1, double* s2,
+                                   hipStream_t st) {
+  constexpr int E = 16 / (int)sizeof(T);
+  const int vin_ok =
+      ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld_c % E == 0 && ld_b % E == 0) ? 1 : 0;
+  const int vout_ok = ((reinterpret_cast<uintptr_t>(Xt) & 15) == 0 && ld_xt % E == 0) ? 1 : 0;
+  const dim3 grid((unsigned)((T_ + 16 * E - 1) / (16 * E)), (unsigned)B);
+  hipLaunchKernelGGL((k_tokenize_stats_chw<T>), grid, dim3(256), 0, st, X, ld_c, ld_b, C, T_, Xt,
+                     ld_xt, vin_ok, vout_ok, r, s1, s2);
+  return hipGetLastError();
+}
+
+hipError_t launch_tokenize_stats_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
+                                     long long ld_b, void* Xt, long long ld_xt, float* r, double* s1,
+                                     double* s2, hipStream_t st) {
+  if (dt == TDQ_F16)
+    return tokenize_stats_t<u16>(static_cast<const u16*>(X), B, C, T, ld_c, ld_b,
+                                 static_cast<u16*>(Xt), ld_xt, r, s1, s2, st);
+  return tokenize_stats_t<float>(static_cast<const float*>(X), B, C, T, ld_c, ld_b,
+                                 static_cast<float*>(Xt), ld_xt, r, s1, s2, st);
+}
+
 }  // namespace tdq

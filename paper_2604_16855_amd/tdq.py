@@ -94,6 +94,9 @@ def lib() -> C.CDLL:
                                                vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.tdq_range_disparity.restype = C.c_int
     L.tdq_range_disparity.argtypes = [vp, C.c_int, i32, i32, i32, i64, vp, vp, vp, vp, vp]
+    L.tdq_calibrate_groups_chw.restype = C.c_int
+    L.tdq_calibrate_groups_chw.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64, C.POINTER(Params),
+                                           vp, i64, vp, vp, vp, vp, vp, sz, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -266,6 +269,33 @@ def _bct(X: torch.Tensor) -> Tuple[int, int, int, int, int]:
     ld_c = X.stride(1) if Cc > 1 else T
     ld_b = X.stride(0) if B > 1 else max((Cc - 1) * ld_c + T, 1)
     return B, Cc, T, ld_c, ld_b
+
+
+def tdq_calibrate_groups_chw(X: torch.Tensor, p: Params, workspace: Optional[torch.Tensor] = None,
+                             want_stats: bool = False, out=None):
+    """tdq_calibrate_groups on a feature map X[B, C, H, W] read in place.
+    -> (Xt[B, H*W, C] token-major copy, group_id[B,T], clip[B,G], scale[B,G], stats or None,
+    workspace); quantize with tdq_quantize_act(Xt, ...)."""
+    B, Cc, T, ld_c, ld_b = _bct(X)
+    G = p.n_groups
+    dev = X.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, Cc, _dt(X), p, dev)
+    if out is None:
+        Xt = torch.empty((B, T, Cc), dtype=X.dtype, device=dev)
+        gid = torch.empty((B, T), dtype=torch.int32, device=dev)
+        clip = torch.empty((B, G), dtype=torch.float32, device=dev)
+        scale = torch.empty((B, G), dtype=torch.float32, device=dev)
+    else:
+        Xt, gid, clip, scale = out
+    stats = (torch.empty((B * G, C.sizeof(GroupStats)), dtype=torch.uint8, device=dev)
+             if want_stats else None)
+    rc = lib().tdq_calibrate_groups_chw(X.data_ptr(), _dt(X), B, Cc, T, ld_c, ld_b, C.byref(p),
+                                        Xt.data_ptr(), Xt.stride(1), gid.data_ptr(), clip.data_ptr(),
+                                        scale.data_ptr(), _ptr(stats), workspace.data_ptr(),
+                                        workspace.numel(), _stream())
+    _check(rc, "tdq_calibrate_groups_chw")
+    return Xt, gid, clip, scale, stats, workspace
 
 
 def tdq_quantize_act_blocks_chw(X: torch.Tensor, p: Params, want_clip: bool = False,

@@ -26,6 +26,7 @@ def test_every_declared_symbol_is_exported():
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
             "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
             "tdq_calibrate_quantize_fused", "tdq_range_disparity",
+            "tdq_calibrate_groups_chw",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -251,6 +252,27 @@ def test_range_disparity_rejects_bad_arguments():
     assert call(ld=7) == tdq.ERR_SHAPE
     assert call(X=FAKE + 1) == tdq.ERR_ALIGN
     assert call(med=FAKE + 2) == tdq.ERR_ALIGN
+
+
+def test_conv_layout_calibration_rejects_bad_arguments():
+    f = tdq.lib().tdq_calibrate_groups_chw
+    p = tdq.default_params()
+
+    def call(q=None, X=FAKE, dt=0, B=2, Cc=8, T=12, ld_c=12, ld_b=96, Xt=FAKE, ld_xt=8, gid=FAKE,
+             ws=FAKE, wsb=1 << 30):
+        return f(X, dt, B, Cc, T, ld_c, ld_b, C.byref(q or p), Xt, ld_xt, gid, FAKE, FAKE, None, ws,
+                 wsb, None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(Xt=None) == tdq.ERR_NULL
+    assert call(gid=None) == tdq.ERR_NULL
+    assert call(dt=3) == tdq.ERR_DTYPE
+    assert call(ld_c=11) == tdq.ERR_SHAPE
+    assert call(ld_b=95) == tdq.ERR_SHAPE
+    assert call(ld_xt=7) == tdq.ERR_SHAPE
+    assert call(wsb=8) == tdq.ERR_WORKSPACE
+    assert call(X=FAKE + 1) == tdq.ERR_ALIGN
+    assert call(q=tdq.block_params()) == tdq.ERR_UNSUPPORTED
 
 
 def test_bench_refuses_more_than_one_gpu():

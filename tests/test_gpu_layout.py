@@ -144,3 +144,30 @@ def test_blocks_quantizer_conv_layout_strided_view():
     _, q_ref, clip, scale = O.dstg_dcrp_blocks(Xt, 32, O.Params(n_groups=1, flags=2))
     assert np.array_equal(bc.cpu().numpy(), clip) and np.array_equal(bs.cpu().numpy(), scale)
     assert np.array_equal(U.unpack_device_codes(Q, C), q_ref)
+
+
+@pytest.mark.parametrize("B,C,H,W,dtype,G", [
+    (2, 64, 16, 8, np.float16, 4), (1, 320, 22, 22, np.float16, 16), (3, 100, 7, 9, np.float16, 5),
+    (2, 72, 12, 16, np.float16, 8), (2, 64, 8, 8, np.float32, 4), (1, 130, 11, 13, np.float32, 3),
+    (1, 1024, 32, 32, np.float16, 32), (1, 1, 1, 1, np.float16, 2)])
+def test_token_set_calibration_reads_conv_layout(B, C, H, W, dtype, G):
+    """tdq_calibrate_groups_chw: the token-major copy is exact, and ids, thresholds and
+    steps are the oracle's on the oracle's tokens."""
+    _say(f"[calibrate-chw] B={B} C={C} H={H} W={W} dtype={dtype.__name__} G={G}")
+    X = _feature_map(B, C, H, W, dtype, 8)
+    p = tdq.default_params(G)
+    Xt, gid, clip, scale, stats, ws = tdq.tdq_calibrate_groups_chw(torch.from_numpy(X).to(U.dev()), p,
+                                                                  want_stats=True)
+    Q = tdq.tdq_quantize_act(Xt, p, gid, clip, scale)
+    torch.cuda.synchronize()
+    Xt_ref = O.tokenize_chw(X)
+    assert np.array_equal(Xt.cpu().numpy().view(np.uint8), Xt_ref.view(np.uint8))
+    assert tdq.device_status(ws) == 0
+    g = dict(gid=gid.cpu().numpy(), clip=clip.cpu().numpy(), scale=scale.cpu().numpy(),
+             stats=tdq.stats_to_numpy(stats))
+    og, oc, osc, _ = U.assert_calibration_matches(g, Xt_ref, p)
+    q_ref = O.quantize_act(Xt_ref, og, oc, osc, U.oracle_params(p)).reshape(B * H * W, C)
+    rows = np.arange(B)[:, None]
+    exact = np.array_equal(g["scale"], osc) and np.array_equal(g["clip"], oc)
+    U.assert_codes_match(U.unpack_device_codes(Q, C), q_ref, Xt_ref, oc[rows, og].reshape(-1),
+                         osc[rows, og].reshape(-1), exact)
