@@ -218,6 +218,7 @@ def main():
     out["rank_select_missed_sets"] = [tdq.exact_select_sets(L.ws) for L in layers]
     if not args.no_blocks:
         out["paper_literal_blocks"] = blocks_leg(layers, torch, tdq)
+        out["f6_contraction"] = f6_leg(layers, torch, tdq)
     if not args.no_quality:
         out["quality"] = quality(fc1, torch, tdq)
     if not args.no_cpu_baseline:
@@ -290,6 +291,37 @@ def blocks_leg(layers, torch, tdq, iters=10, warm=5):
         del bs, Q, Xt
     res["ms_per_pass"] = round(tot, 4)
     # the token-set path overwrote nothing it needs: L.Y is rewritten by the next step
+    return res
+
+
+def f6_leg(layers, torch, tdq, iters=10, warm=5):
+    """The same token-set path with the codes carried as bf6 operands of the 6-bit matrix
+    instruction (tdq_quantize_act_f6 -> tdq_w4a4_linear_f6, bit-identical Y), outside the
+    timed steps: the instruction runs at twice the int8 rate and needs no nibble expansion,
+    but the operands are 0.75 instead of 0.5 bytes per code."""
+    res = []
+    for L in layers:
+        lc = L.lc
+        F = torch.empty((tdq.f6_bytes(lc.M, lc.C),), dtype=torch.uint8, device=L.X.device)
+        W6 = tdq.tdq_pack_codes_f6(L.Qw, lc.C)                       # offline
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tq = tl = 0.0
+        for it in range(warm + iters):
+            ev[0].record()
+            tdq.tdq_quantize_act_f6(L.X, L.p, L.gid, L.clip, L.scale, out=F)
+            ev[1].record()
+            tdq.tdq_w4a4_linear_f6(F, L.gid, L.scale, lc.B, lc.T, lc.C, W6, lc.N, L.w_scale, None,
+                                   out=L.Y)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it >= warm:
+                tq += ev[0].elapsed_time(ev[1])
+                tl += ev[1].elapsed_time(ev[2])
+        tq, tl = tq / iters, tl / iters
+        res.append({"layer": lc.name, "quantize_f6_ms": round(tq, 4), "linear_f6_ms": round(tl, 4),
+                    "linear_f6_tops": round(L.gemm_ops / (tl * 1e-3) / 1e12, 1),
+                    "frac_of_fp6_peak": round(L.gemm_ops / (tl * 1e-3) / 1e12 / 10100.0, 4)})
+        del F, W6
     return res
 
 

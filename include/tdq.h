@@ -288,6 +288,30 @@ int tdq_w4a4_linear_blocks(const uint8_t* Qx, int64_t ld_q, const float* block_s
                            int64_t ld_y, void* stream);
 
 /*
+ * The same contraction on gfx950's 6-bit matrix format.  All sixteen int4 codes are exact
+ * in bf6 (e3m2), integer sums below 2^24 are exact in the binary32 accumulator, and the
+ * 6-bit matrix instruction runs at twice the int8 instruction's rate with no nibble
+ * expansion: same acc, same Y, bit for bit, as tdq_w4a4_linear.
+ *
+ * Operands are "f6 fragments" (tdq_f6_bytes bytes, 16-byte aligned): rows in blocks of 32,
+ * K zero-padded to KB = 2 ceil(K/128) blocks of 64; block (rb, kb) is the 1536 bytes at
+ * (rb KB + kb) 1536 and holds, for lane l = row % 32 + 32 ((k % 64) / 32), 24 bytes with
+ * code k % 32 as a bf6 pattern in bits [6 (k % 32), +6).  tdq_pack_codes_f6 converts packed
+ * nibbles [rows, ld] (bytes) to fragments; tdq_quantize_act_f6 writes them directly.
+ */
+size_t tdq_f6_bytes(int64_t rows, int32_t K);
+/* tdq_quantize_act writing f6 fragments: Qx6 holds tdq_f6_bytes(B*T, C) bytes, all written
+ * (rows and codes of the padding are zero). */
+int tdq_quantize_act_f6(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                        const tdq_params* p, const int32_t* group_id, const float* clip,
+                        const float* scale, uint8_t* Qx6, void* stream);
+int tdq_pack_codes_f6(const uint8_t* Q, int64_t ld, int64_t rows, int32_t K, uint8_t* F, void* stream);
+int tdq_w4a4_linear_f6(const uint8_t* Qx6, const int32_t* group_id, const float* scale, int32_t B,
+                       int32_t T, int32_t K, int32_t N, int32_t G, const uint8_t* Qw6,
+                       const float* w_scale, const float* bias, void* Y, tdq_dtype y_dt, int64_t ld_y,
+                       int32_t* acc_dump, void* stream);
+
+/*
  * Static symmetric per-output-channel weight quantization (Eq. weight_quant),
  * done once offline:  s_o = max(max_i |W_oi|, 1e-8) / 7,
  * Qw = clamp(rint(W / s_o), -8, 7) packed.  W [N, K] fp32 (device),

@@ -612,6 +612,117 @@ hipError_t launch_quantize(const void* X, tdq_dtype dt, int B, int T, int C, lon
 }
 
 // ---------------------------------------------------------------------------
+// K_c writing the operand format of the 6-bit contraction (tdq_w4a4_linear_f6): the same
+// codes, each as the bf6 (e3m2) pattern of its integer value, in fragments of 32 rows x
+// 64 codes laid out in the lane order of the matrix instruction.  One wavefront per
+// fragment; lane l = row % 32 + 32 * ((k % 64) / 32) quantizes 32 consecutive elements of
+// its row, rounds the quotients to integers (the same arithmetic as k_quantize) and
+// packs them with one conversion instruction, which takes the even elements in its first
+// and the odd ones in its second operand; a wavefront stores 1536 contiguous bytes.
+// ---------------------------------------------------------------------------
+typedef float v16f_t __attribute__((ext_vector_type(16)));
+typedef int v6i_t __attribute__((ext_vector_type(6)));
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_quantize_f6(const T* __restrict__ X, long long ld, int M, int C,
+                                                     int T_, int G, int KB, int vec_ok,
+                                                     const int* __restrict__ gid,
+                                                     const float* __restrict__ clip,
+                                                     const float* __restrict__ scale,
+                                                     uint8_t* __restrict__ F, long long n_blocks) {
+  constexpr int V = Elem<T>::V;
+  constexpr int ROWB = 64 * (int)sizeof(T);                  // bytes of a fragment's row of X
+  constexpr int PITCH = ROWB + 16;                           // LDS row pitch: 16-byte reads stay aligned
+  constexpr int PPR = ROWB / 16;                             // 16-byte pieces per row: 8 or 16
+  __shared__ __attribute__((aligned(16))) uint8_t stage[4][32 * PITCH];
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const long long blk_raw = (long long)blockIdx.x * 4 + wave;
+  const bool live = blk_raw < n_blocks;                      // a wavefront without a fragment idles along
+  const long long blk = live ? blk_raw : n_blocks - 1;
+  const int kb = (int)(blk % KB);
+  const long long row0 = (blk / KB) * 32;
+  const long long row = row0 + (l & 31);
+  const int k0 = kb * 64 + 32 * (l >> 5);
+  // whole fragments of aligned rows go through LDS: the global loads then read every
+  // 128-byte line exactly once, 8 (16) lanes to a row, and the lane that owns (row, half)
+  // in the matrix instruction's order picks its 32 elements up from there
+  const bool tile_ok = vec_ok && kb * 64 + 64 <= C && row0 + 32 <= M;      // uniform per wavefront
+  if (tile_ok) {
+#pragma unroll
+    for (int j = 0; j < 32 * PPR / 64; ++j) {
+      const int r = j * (64 / PPR) + l / PPR, pc = l % PPR;
+      const uint4 w = load_last_use(reinterpret_cast<const T*>(
+          reinterpret_cast<const uint8_t*>(X + (row0 + r) * ld + kb * 64) + pc * 16));
+      *reinterpret_cast<uint4*>(&stage[wave][r * PITCH + pc * 16]) = w;
+    }
+  }
+  __syncthreads();
+  v16f_t ev, od;                                             // even / odd elements, as rounded quotients
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { ev[i] = 0.f; od[i] = 0.f; }
+  if (row < M && k0 < C) {
+    const int b = (int)(row / T_);
+    const int g = gid ? gid[row] : 0;
+    const float c = clip[(long long)b * G + g], d = scale[(long long)b * G + g];
+    const float rcp = 1.0f / d;
+    const T* xp = X + row * ld + k0;
+    auto q = [&](float x) {                                  // integer-valued float in [-8, 7]
+      return __uint_as_float(quant_bits<true>(x, c, d, rcp)) - 12582912.0f;
+    };
+    if (tile_ok || (vec_ok && k0 + 32 <= C)) {
+#pragma unroll
+      for (int j = 0; j < 32 / V; ++j) {
+        uint4 w;
+        if (tile_ok)
+          w = *reinterpret_cast<const uint4*>(&stage[wave][(l & 31) * PITCH + (l >> 5) * (ROWB / 2) + j * 16]);
+        else
+          w = *reinterpret_cast<const uint4*>(xp + j * V);   // plain: the line is shared with lane l ^ 32
+        T e[V];
+        Elem<T>::unpack(w, e);
+#pragma unroll
+        for (int i = 0; i < V; i += 2) {
+          ev[(j * V + i) >> 1] = q(Elem<T>::val(e[i]));
+          od[(j * V + i) >> 1] = q(Elem<T>::val(e[i + 1]));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (k0 + 2 * i < C) ev[i] = q(Elem<T>::val(xp[2 * i]));
+        if (k0 + 2 * i + 1 < C) od[i] = q(Elem<T>::val(xp[2 * i + 1]));
+      }
+    }
+  }
+  const v6i_t r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(ev, od, 1.0f);
+  if (live) {
+    uint2* dst = reinterpret_cast<uint2*>(F + (blk * 64 + l) * 24);
+    dst[0] = make_uint2((u32)r[0], (u32)r[1]);
+    dst[1] = make_uint2((u32)r[2], (u32)r[3]);
+    dst[2] = make_uint2((u32)r[4], (u32)r[5]);
+  }
+}
+
+hipError_t launch_quantize_f6(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
+                              const int* gid, const float* clip, const float* scale, uint8_t* F,
+                              hipStream_t st) {
+  const long long M = (long long)B * T;
+  const int KB = 2 * ((C + 127) / 128);
+  const long long n_blocks = ((M + 31) / 32) * KB;
+  const unsigned grid = (unsigned)((n_blocks + 3) / 4);
+  if (dt == TDQ_F16) {
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0) ? 1 : 0;
+    hipLaunchKernelGGL((k_quantize_f6<u16>), dim3(grid), dim3(256), 0, st, static_cast<const u16*>(X),
+                       ld, (int)M, C, T, G, KB, vec_ok, gid, clip, scale, F, n_blocks);
+  } else {
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 4 == 0) ? 1 : 0;
+    hipLaunchKernelGGL((k_quantize_f6<float>), dim3(grid), dim3(256), 0, st,
+                       static_cast<const float*>(X), ld, (int)M, C, T, G, KB, vec_ok, gid, clip, scale,
+                       F, n_blocks);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Diagnostics of Sec. 3.2 per (image, token set), as exact counts: elements whose code
 // is 0 (zero-bin mass rho_0 = count / n, Eq. rho0_def) and elements clipped by the
 // radius (|x| > c).  The code is computed exactly as K_c computes it.  One sweep of X.

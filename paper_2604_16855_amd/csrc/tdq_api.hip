@@ -474,6 +474,60 @@ int tdq_w4a4_linear_blocks(const uint8_t* Qx, int64_t ld_q, const float* block_s
   return TDQ_OK;
 }
 
+int tdq_quantize_act_f6(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C, int64_t ld_x,
+                        const tdq_params* p, const int32_t* group_id, const float* clip,
+                        const float* scale, uint8_t* Qx6, void* stream) {
+  if (!X || !p || !clip || !scale || !Qx6) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  if (C > 131072) return TDQ_ERR_SHAPE;
+  if (!group_id && p->n_groups != 1) return TDQ_ERR_NULL;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(Qx6) & 15) return TDQ_ERR_ALIGN;
+  if (launch_quantize_f6(X, dt, B, T, C, ld_x, p->n_groups, group_id, clip, scale, Qx6,
+                         static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+size_t tdq_f6_bytes(int64_t rows, int32_t K) {
+  if (rows < 1 || K < 1) return 0;
+  const int64_t KB = 2 * (((int64_t)K + 127) / 128);
+  return (size_t)(((rows + 31) / 32) * KB * 1536);
+}
+
+int tdq_pack_codes_f6(const uint8_t* Q, int64_t ld, int64_t rows, int32_t K, uint8_t* F, void* stream) {
+  if (!Q || !F) return TDQ_ERR_NULL;
+  if (rows < 1 || rows > (int64_t)1 << 30 || K < 1 || K > 131072 || ld < (K + 1) / 2) return TDQ_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(F) & 15) return TDQ_ERR_ALIGN;
+  if (launch_pack_f6(Q, ld, (int)rows, K, F, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+int tdq_w4a4_linear_f6(const uint8_t* Qx6, const int32_t* group_id, const float* scale, int32_t B,
+                       int32_t T, int32_t K, int32_t N, int32_t G, const uint8_t* Qw6,
+                       const float* w_scale, const float* bias, void* Y, tdq_dtype y_dt, int64_t ld_y,
+                       int32_t* acc_dump, void* stream) {
+  if (!Qx6 || !scale || !Qw6 || !w_scale || !Y) return TDQ_ERR_NULL;
+  if (y_dt != TDQ_F16 && y_dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  if (B < 1 || T < 1 || K < 1 || N < 1) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T > (int64_t)1 << 30 || K > 131072 || ld_y < N) return TDQ_ERR_SHAPE;
+  if (G < 1 || G > TDQ_MAX_GROUPS) return TDQ_ERR_PARAM;
+  if (!group_id && G != 1) return TDQ_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(Qx6) & 15) || (reinterpret_cast<uintptr_t>(Qw6) & 15))
+    return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(Y) % (y_dt == TDQ_F16 ? 2 : 4)) return TDQ_ERR_ALIGN;
+  if (launch_w4a4_gemm_f6(Qx6, Qw6, K, group_id, scale, B * T, T, N, G, w_scale, bias, Y, y_dt, ld_y,
+                          acc_dump, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
 int tdq_quantize_weight(const float* W, int32_t N, int32_t K, int64_t ld_w_in, uint8_t* Qw,
                         int64_t ld_w, float* w_scale, void* stream) {
   if (!W || !Qw || !w_scale) return TDQ_ERR_NULL;

@@ -156,6 +156,14 @@ hipError_t launch_range_disparity(const void* X, tdq_dtype dt, int B, int T, int
 hipError_t launch_tokenize_stats_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                      long long ld_b, void* Xt, long long ld_xt, float* r, double* s1,
                                      double* s2, hipStream_t st);
+hipError_t launch_quantize_f6(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
+                              const int* gid, const float* clip, const float* scale, uint8_t* F,
+                              hipStream_t st);
+hipError_t launch_pack_f6(const uint8_t* Q, long long ld, int R, int K, uint8_t* F, hipStream_t st);
+hipError_t launch_w4a4_gemm_f6(const uint8_t* A6, const uint8_t* B6, int K, const int* gid,
+                               const float* scale, int M, int T, int N, int G, const float* w_scale,
+                               const float* bias, void* Y, tdq_dtype y_dt, long long ld_y,
+                               int* acc_dump, hipStream_t st);
 hipError_t launch_tokenize_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                long long ld_b, void* Xt, long long ld_xt, hipStream_t st);
 hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,

@@ -97,6 +97,16 @@ def lib() -> C.CDLL:
     L.tdq_calibrate_groups_chw.restype = C.c_int
     L.tdq_calibrate_groups_chw.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64, C.POINTER(Params),
                                            vp, i64, vp, vp, vp, vp, vp, sz, vp]
+    L.tdq_f6_bytes.restype = sz
+    L.tdq_f6_bytes.argtypes = [i64, i32]
+    L.tdq_quantize_act_f6.restype = C.c_int
+    L.tdq_quantize_act_f6.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp, vp,
+                                      vp, vp]
+    L.tdq_pack_codes_f6.restype = C.c_int
+    L.tdq_pack_codes_f6.argtypes = [vp, i64, i64, i32, vp, vp]
+    L.tdq_w4a4_linear_f6.restype = C.c_int
+    L.tdq_w4a4_linear_f6.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, C.c_int,
+                                     i64, vp, vp]
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
@@ -410,6 +420,48 @@ def tdq_range_disparity(X: torch.Tensor):
                                    tmax.data_ptr(), D.data_ptr(), mx.data_ptr(), _stream())
     _check(rc, "tdq_range_disparity")
     return D, med, mx
+
+
+def f6_bytes(rows: int, K: int) -> int:
+    return int(lib().tdq_f6_bytes(rows, K))
+
+
+def tdq_quantize_act_f6(X: torch.Tensor, p: Params, gid: Optional[torch.Tensor], clip: torch.Tensor,
+                        scale: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """tdq_quantize_act writing f6 fragments (uint8 [tdq_f6_bytes(B*T, C)])."""
+    B, T, Cc, ld = _btc(X)
+    if out is None:
+        out = torch.empty((f6_bytes(B * T, Cc),), dtype=torch.uint8, device=X.device)
+    rc = lib().tdq_quantize_act_f6(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p), _ptr(gid),
+                                   clip.data_ptr(), scale.data_ptr(), out.data_ptr(), _stream())
+    _check(rc, "tdq_quantize_act_f6")
+    return out
+
+
+def tdq_pack_codes_f6(Q: torch.Tensor, K: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Packed nibbles Q[rows, ld] -> f6 fragments (uint8 [tdq_f6_bytes(rows, K)])."""
+    rows = Q.shape[0]
+    if out is None:
+        out = torch.empty((f6_bytes(rows, K),), dtype=torch.uint8, device=Q.device)
+    rc = lib().tdq_pack_codes_f6(Q.data_ptr(), Q.stride(0), rows, K, out.data_ptr(), _stream())
+    _check(rc, "tdq_pack_codes_f6")
+    return out
+
+
+def tdq_w4a4_linear_f6(Qx6: torch.Tensor, gid: Optional[torch.Tensor], scale: torch.Tensor, B: int,
+                       T: int, K: int, Qw6: torch.Tensor, N: int, w_scale: torch.Tensor,
+                       bias: Optional[torch.Tensor] = None, out_dtype=torch.float32,
+                       out: Optional[torch.Tensor] = None, acc_dump: Optional[torch.Tensor] = None
+                       ) -> torch.Tensor:
+    """tdq_w4a4_linear on f6-fragment operands -> Y[B*T, N]."""
+    G = scale.shape[1] if scale.dim() == 2 else scale.numel() // B
+    if out is None:
+        out = torch.empty((B * T, N), dtype=out_dtype, device=Qx6.device)
+    rc = lib().tdq_w4a4_linear_f6(Qx6.data_ptr(), _ptr(gid), scale.data_ptr(), B, T, K, N, G,
+                                  Qw6.data_ptr(), w_scale.data_ptr(), _ptr(bias), out.data_ptr(),
+                                  _dt(out), out.stride(0), _ptr(acc_dump), _stream())
+    _check(rc, "tdq_w4a4_linear_f6")
+    return out
 
 
 def tdq_quantize_weight(W: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported():
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
             "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
             "tdq_calibrate_quantize_fused", "tdq_range_disparity",
-            "tdq_calibrate_groups_chw",
+            "tdq_calibrate_groups_chw", "tdq_w4a4_linear_f6", "tdq_quantize_act_f6",
+            "tdq_pack_codes_f6", "tdq_f6_bytes",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -273,6 +274,38 @@ def test_conv_layout_calibration_rejects_bad_arguments():
     assert call(wsb=8) == tdq.ERR_WORKSPACE
     assert call(X=FAKE + 1) == tdq.ERR_ALIGN
     assert call(q=tdq.block_params()) == tdq.ERR_UNSUPPORTED
+
+
+def test_f6_entries_reject_bad_arguments():
+    L = tdq.lib()
+    assert tdq.f6_bytes(1, 1) == 2 * 1536 and tdq.f6_bytes(33, 129) == 2 * 4 * 1536
+    assert tdq.f6_bytes(0, 8) == 0
+    pk = L.tdq_pack_codes_f6
+    assert pk(None, 4, 8, 8, FAKE, None) == tdq.ERR_NULL
+    assert pk(FAKE, 3, 8, 8, FAKE, None) == tdq.ERR_SHAPE
+    assert pk(FAKE, 4, 8, 8, FAKE + 8, None) == tdq.ERR_ALIGN
+    p = tdq.default_params()
+    q = L.tdq_quantize_act_f6
+    assert q(FAKE, 0, 1, 8, 8, 8, C.byref(p), None, FAKE, FAKE, FAKE, None) == tdq.ERR_NULL   # G > 1 needs ids
+    assert q(FAKE, 0, 1, 8, 8, 8, C.byref(p), FAKE, FAKE, FAKE, None, None) == tdq.ERR_NULL
+    assert q(FAKE, 0, 1, 8, 8, 8, C.byref(p), FAKE, FAKE, FAKE, FAKE + 4, None) == tdq.ERR_ALIGN
+    assert q(FAKE, 0, 1, 8, 8, 7, C.byref(p), FAKE, FAKE, FAKE, FAKE, None) == tdq.ERR_SHAPE
+    g = L.tdq_w4a4_linear_f6
+    ok = dict(Qx=FAKE, gid=FAKE, scale=FAKE, B=1, T=8, K=64, N=8, G=4, Qw=FAKE, ws=FAKE, bias=None,
+              Y=FAKE, ydt=1, ld_y=8, dump=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return g(a["Qx"], a["gid"], a["scale"], a["B"], a["T"], a["K"], a["N"], a["G"], a["Qw"],
+                 a["ws"], a["bias"], a["Y"], a["ydt"], a["ld_y"], a["dump"], None)
+
+    assert call(Qx=None) == tdq.ERR_NULL
+    assert call(gid=None) == tdq.ERR_NULL
+    assert call(K=0) == tdq.ERR_SHAPE
+    assert call(ld_y=7) == tdq.ERR_SHAPE
+    assert call(G=300) == tdq.ERR_PARAM
+    assert call(Qw=FAKE + 8) == tdq.ERR_ALIGN
+    assert call(ydt=2) == tdq.ERR_DTYPE
 
 
 def test_bench_refuses_more_than_one_gpu():
