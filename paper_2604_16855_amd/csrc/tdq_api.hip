@@ -528,6 +528,24 @@ int tdq_w4a4_linear_f6(const uint8_t* Qx6, const int32_t* group_id, const float*
   return TDQ_OK;
 }
 
+int tdq_w4a4_linear_blocks_f6(const uint8_t* Qx6, const float* block_scale, int64_t ld_s, int64_t M,
+                              int32_t K, int32_t N, const uint8_t* Qw6, const float* w_scale,
+                              const float* bias, void* Y, tdq_dtype y_dt, int64_t ld_y, void* stream) {
+  if (!Qx6 || !block_scale || !Qw6 || !w_scale || !Y) return TDQ_ERR_NULL;
+  if (y_dt != TDQ_F16 && y_dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  if (M < 1 || K < 1 || N < 1 || M > (int64_t)1 << 30 || K > 131072) return TDQ_ERR_SHAPE;
+  const int64_t KB = ((int64_t)K + TDQ_BLOCK - 1) / TDQ_BLOCK;
+  if (ld_y < N || ld_s < KB) return TDQ_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(Qx6) & 15) || (reinterpret_cast<uintptr_t>(Qw6) & 15))
+    return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(block_scale) & 3) return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(Y) % (y_dt == TDQ_F16 ? 2 : 4)) return TDQ_ERR_ALIGN;
+  if (launch_w4a4_gemm_blocks_f6(Qx6, Qw6, block_scale, ld_s, (int)M, K, N, w_scale, bias, Y, y_dt,
+                                 ld_y, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
 int tdq_quantize_weight(const float* W, int32_t N, int32_t K, int64_t ld_w_in, uint8_t* Qw,
                         int64_t ld_w, float* w_scale, void* stream) {
   if (!W || !Qw || !w_scale) return TDQ_ERR_NULL;

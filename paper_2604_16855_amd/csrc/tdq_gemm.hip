@@ -1362,4 +1362,225 @@ hipError_t launch_w4a4_gemm_f6(const uint8_t* A6, const uint8_t* B6, int K, cons
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// The block-scaled contraction (one step per row and 32-code block) on f6 fragments.
+// The 6-bit instruction covers 64 codes = two blocks, lanes 0-31 supplying the even
+// block and lanes 32-63 the odd one of the row operand; zeroing the other half of that
+// operand makes it deliver one block's sum, already as a float, so the rescale is one
+// fused multiply-add per element and block (16 per matrix instruction) instead of a
+// conversion and a multiply-add on top of the nibble expansion (38): the kernel stays
+// bound by the vector unit, at 2.4 times fewer vector instructions.  Same arithmetic as
+// k_w4a4_gemm_blocks (f <- fma(acc_kb, Delta[m, kb], f), kb ascending): same bits.
+//
+// 128 x 128 tile, 2 x 2 wavefronts of 64 x 64; a stage is 128 codes of K (two K blocks of
+// 64 = four scale blocks): 8 chunks of 3 KiB of fragments, register-staged into LDS as
+// they are (a lane's 24-byte operand is read as three 8-byte pieces, conflict-free), and
+// the steps block-major as in k_w4a4_gemm_blocks.
+// ---------------------------------------------------------------------------
+template <typename OUT>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks_f6(
+    const uint8_t* __restrict__ A6, const uint8_t* __restrict__ B6, int KB64,
+    const float* __restrict__ bscale, long long ld_s, int M, int K, int N,
+    const float* __restrict__ w_scale, const float* __restrict__ bias, OUT* __restrict__ Y,
+    long long ld_y, int m_tiles, int n_tiles) {
+  constexpr int MT = 2, NT = 2, BM = 128, BN = 128;
+  constexpr int KS = 2;                          // 64-blocks of K per stage
+  constexpr int SBK = 2 * KS;                    // scale blocks per stage
+  constexpr int CH = KS * F6_FRAG;               // 3072 bytes per row block and stage
+  constexpr int SLOT = 8 * CH;                   // 4 row blocks of A, 4 of B
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[2][SLOT];
+  __shared__ __attribute__((aligned(16))) float sD[2][SBK][BM];
+  __shared__ float sCol[BN], sBias[BN];
+
+  const int bid = blockIdx.x;
+  const int xcd = bid % XCDS, idx = bid / XCDS;
+  const int m_tile = (idx / n_tiles) * XCDS + xcd;
+  const int n_tile = idx % n_tiles;
+  if (m_tile >= m_tiles) return;
+  const int m0 = m_tile * BM, n0 = n_tile * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int stages = KB64 / KS;
+  const int KB = (K + 31) / 32;                  // scale blocks that exist
+  const int MBk = (M + 31) / 32, NBk = (N + 31) / 32;
+
+  for (int j = tid; j < BN; j += GEMM_THREADS) {
+    const int n = n0 + j;
+    sCol[j] = n < N ? w_scale[n] : 0.f;
+    sBias[j] = (bias && n < N) ? bias[n] : 0.f;
+  }
+
+  // The fragments of a stage are 24 KiB of contiguous 3 KiB chunks: direct-to-LDS loads
+  // of 1 KiB, 6 per wavefront, no staging registers (with register staging the compiler
+  // put the loaded data into the registers of the matrix results and had to wait for
+  // every stage's loads before computing).  Piece wave + 4 e: chunk (row block) piece / 3,
+  // part piece % 3.
+  constexpr int NDMA = SLOT / 1024 / 4;
+  const uint8_t* src[NDMA];
+#pragma unroll
+  for (int e = 0; e < NDMA; ++e) {
+    const int pi = wave + 4 * e;
+    const int c = pi / 3, part = pi % 3;
+    long long rb;
+    const uint8_t* base;
+    if (c < 4) {
+      rb = (long long)m_tile * 4 + c;
+      rb = rb < MBk ? rb : MBk - 1;              // past the end: a harmless re-read
+      base = A6;
+    } else {
+      rb = (long long)n_tile * 4 + (c - 4);
+      rb = rb < NBk ? rb : NBk - 1;
+      base = B6;
+    }
+    src[e] = base + rb * KB64 * F6_FRAG + part * 1024 + lane * 16;
+  }
+  const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)&ring[0][0];
+  const int drow = tid >> 1, dcol = (tid & 1) * (SBK / 2);
+  const bool d_row_ok = m0 + drow < M;
+  const float* pd = bscale + (long long)(m0 + (d_row_ok ? drow : 0)) * ld_s + dcol;
+
+  float gd[SBK / 2];
+  auto load_stage = [&](int st, int buf) {
+#pragma unroll
+    for (int e = 0; e < NDMA; ++e)
+      dma16(src[e] + (long long)st * CH,
+            __builtin_amdgcn_readfirstlane(ring_base + buf * SLOT + (__builtin_amdgcn_readfirstlane(wave) + 4 * e) * 1024));
+    // 4-byte loads, as in k_w4a4_gemm_blocks
+    const int b0 = st * SBK + dcol;
+#pragma unroll
+    for (int j = 0; j < SBK / 2; ++j) gd[j] = (d_row_ok && b0 + j < KB) ? pd[st * SBK + j] : 0.f;
+  };
+  auto store_stage = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < SBK / 2; ++j) sD[buf][dcol + j][drow] = gd[j];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the direct loads have landed
+  };
+
+  float accf[MT][NT][16];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) accf[i][j][r] = 0.f;
+
+  load_stage(0, 0);
+  store_stage(0);
+  __syncthreads();
+
+  const int a_off = wm * 2 * CH + lane * 24, b_off = (4 + wn * 2) * CH + lane * 24;
+  const int d_off = wm * 32 * MT + (lane >> 5) * 4;
+  const bool lower = lane < 32;
+  const v16f zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto read_frag = [&](int buf, int off) {
+    const uint2* p = reinterpret_cast<const uint2*>(&ring[buf][off]);
+    const uint2 q0 = p[0], q1 = p[1], q2 = p[2];
+    const v8i v = {(int)q0.x, (int)q0.y, (int)q1.x, (int)q1.y, (int)q2.x, (int)q2.y, 0, 0};
+    return v;
+  };
+  for (int st = 0; st < stages; ++st) {
+    const int cur = st & 1;
+    if (st + 1 < stages) load_stage(st + 1, cur ^ 1);
+#pragma unroll 1
+    for (int kk = 0; kk < KS; ++kk) {
+      v8i alo[MT], ahi[MT], b[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const v8i a = read_frag(cur, a_off + i * CH + kk * F6_FRAG);
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {            // the operand restricted to one scale block
+          alo[i][w] = lower ? a[w] : 0;
+          ahi[i][w] = lower ? 0 : a[w];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) b[j] = read_frag(cur, b_off + j * CH + kk * F6_FRAG);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        float dl[MT][16];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float4 d4 =
+                *reinterpret_cast<const float4*>(&sD[cur][2 * kk + h][d_off + i * 32 + q * 8]);
+            dl[i][4 * q] = d4.x; dl[i][4 * q + 1] = d4.y; dl[i][4 * q + 2] = d4.z; dl[i][4 * q + 3] = d4.w;
+          }
+        // all four matrix instructions first, into four sets of result registers: the
+        // multiply-adds on the first result then run while the others are still in the
+        // matrix pipe (left to itself the compiler re-used one set and serialised them)
+        v16f t[MT][NT];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            t[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(h ? ahi[i] : alo[i], b[j], zero, 3, 3,
+                                                                      0, 127, 0, 127);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              accf[i][j][r] = __builtin_fmaf(t[i][j][r], dl[i][r], accf[i][j][r]);
+      }
+    }
+    if (st + 1 < stages) store_stage(cur ^ 1);
+    __syncthreads();
+  }
+
+  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      const int rl = wm * 32 * MT + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
+      const int m = m0 + rl;
+      float y0[NT], y1[NT];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int cl = wn * 32 * NT + j * 32 + ccol;
+        y0[j] = accf[i][j][r] * sCol[cl];
+        y1[j] = accf[i][j][r + 1] * sCol[cl];
+        if (bias) {
+          y0[j] = y0[j] + sBias[cl];
+          y1[j] = y1[j] + sBias[cl];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int n = n0 + wn * 32 * NT + j * 32 + ccol;
+        if (m < M && n < N) store_out<OUT>(Y + (long long)m * ld_y + n, y0[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int n = n0 + wn * 32 * NT + j * 32 + ccol;
+        if (m + 1 < M && n < N) store_out<OUT>(Y + (long long)(m + 1) * ld_y + n, y1[j]);
+      }
+    }
+}
+
+hipError_t launch_w4a4_gemm_blocks_f6(const uint8_t* A6, const uint8_t* B6, const float* bscale,
+                                      long long ld_s, int M, int K, int N, const float* w_scale,
+                                      const float* bias, void* Y, tdq_dtype y_dt, long long ld_y,
+                                      hipStream_t st) {
+  const int KB64 = 2 * ((K + 127) / 128);
+  const int m_tiles = (M + 127) / 128, n_tiles = (N + 127) / 128;
+  const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
+  const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
+  if (y_dt == TDQ_F32)
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks_f6<float>), dim3(grid), dim3(GEMM_THREADS), 0, st, A6, B6,
+                       KB64, bscale, ld_s, M, K, N, w_scale, bias, static_cast<float*>(Y), ld_y, m_tiles,
+                       n_tiles);
+  else
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks_f6<_Float16>), dim3(grid), dim3(GEMM_THREADS), 0, st, A6, B6,
+                       KB64, bscale, ld_s, M, K, N, w_scale, bias, static_cast<_Float16*>(Y), ld_y,
+                       m_tiles, n_tiles);
+  return hipGetLastError();
+}
+
 }  // namespace tdq

@@ -164,6 +164,10 @@ hipError_t launch_w4a4_gemm_f6(const uint8_t* A6, const uint8_t* B6, int K, cons
                                const float* scale, int M, int T, int N, int G, const float* w_scale,
                                const float* bias, void* Y, tdq_dtype y_dt, long long ld_y,
                                int* acc_dump, hipStream_t st);
+hipError_t launch_w4a4_gemm_blocks_f6(const uint8_t* A6, const uint8_t* B6, const float* bscale,
+                                      long long ld_s, int M, int K, int N, const float* w_scale,
+                                      const float* bias, void* Y, tdq_dtype y_dt, long long ld_y,
+                                      hipStream_t st);
 hipError_t launch_tokenize_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                long long ld_b, void* Xt, long long ld_xt, hipStream_t st);
 hipError_t launch_group_diag(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,

@@ -102,6 +102,9 @@ def lib() -> C.CDLL:
     L.tdq_quantize_act_f6.restype = C.c_int
     L.tdq_quantize_act_f6.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp, vp,
                                       vp, vp]
+    L.tdq_w4a4_linear_blocks_f6.restype = C.c_int
+    L.tdq_w4a4_linear_blocks_f6.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, C.c_int, i64,
+                                            vp]
     L.tdq_pack_codes_f6.restype = C.c_int
     L.tdq_pack_codes_f6.argtypes = [vp, i64, i64, i32, vp, vp]
     L.tdq_w4a4_linear_f6.restype = C.c_int
@@ -461,6 +464,21 @@ def tdq_w4a4_linear_f6(Qx6: torch.Tensor, gid: Optional[torch.Tensor], scale: to
                                   Qw6.data_ptr(), w_scale.data_ptr(), _ptr(bias), out.data_ptr(),
                                   _dt(out), out.stride(0), _ptr(acc_dump), _stream())
     _check(rc, "tdq_w4a4_linear_f6")
+    return out
+
+
+def tdq_w4a4_linear_blocks_f6(Qx6: torch.Tensor, block_scale: torch.Tensor, K: int,
+                              Qw6: torch.Tensor, N: int, w_scale: torch.Tensor,
+                              bias: Optional[torch.Tensor] = None, out_dtype=torch.float32,
+                              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """tdq_w4a4_linear_blocks on f6-fragment operands -> Y[M, N], M = block_scale.shape[0]."""
+    M = block_scale.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=Qx6.device)
+    rc = lib().tdq_w4a4_linear_blocks_f6(Qx6.data_ptr(), block_scale.data_ptr(), block_scale.stride(0),
+                                         M, K, N, Qw6.data_ptr(), w_scale.data_ptr(), _ptr(bias),
+                                         out.data_ptr(), _dt(out), out.stride(0), _stream())
+    _check(rc, "tdq_w4a4_linear_blocks_f6")
     return out
 
 

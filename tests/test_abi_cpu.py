@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
             "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
             "tdq_calibrate_quantize_fused", "tdq_range_disparity",
             "tdq_calibrate_groups_chw", "tdq_w4a4_linear_f6", "tdq_quantize_act_f6",
-            "tdq_pack_codes_f6", "tdq_f6_bytes",
+            "tdq_pack_codes_f6", "tdq_f6_bytes", "tdq_w4a4_linear_blocks_f6",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -306,6 +306,20 @@ def test_f6_entries_reject_bad_arguments():
     assert call(G=300) == tdq.ERR_PARAM
     assert call(Qw=FAKE + 8) == tdq.ERR_ALIGN
     assert call(ydt=2) == tdq.ERR_DTYPE
+    gb = L.tdq_w4a4_linear_blocks_f6
+    okb = dict(Qx=FAKE, ds=FAKE, ld_s=2, M=8, K=64, N=8, Qw=FAKE, ws=FAKE, bias=None, Y=FAKE, ydt=1, ld_y=8)
+
+    def callb(**kw):
+        a = dict(okb, **kw)
+        return gb(a["Qx"], a["ds"], a["ld_s"], a["M"], a["K"], a["N"], a["Qw"], a["ws"], a["bias"],
+                  a["Y"], a["ydt"], a["ld_y"], None)
+
+    assert callb(ds=None) == tdq.ERR_NULL
+    assert callb(ld_s=1) == tdq.ERR_SHAPE          # K = 64 has two blocks of 32
+    assert callb(M=0) == tdq.ERR_SHAPE
+    assert callb(Qx=FAKE + 8) == tdq.ERR_ALIGN
+    assert callb(ds=FAKE + 2) == tdq.ERR_ALIGN
+    assert callb(ydt=3) == tdq.ERR_DTYPE
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -9,6 +9,7 @@ from paper_2604_16855_amd import inputs as I
 from paper_2604_16855_amd import tdq
 
 import parity_util as U
+from test_gpu_blocks import _blocks_linear_bound
 
 pytestmark = pytest.mark.gpu
 
@@ -198,3 +199,36 @@ def test_f6_path_end_to_end():
     ref = O.tdq_linear_forward(X, W, O.Params(n_groups=lc.G))
     if np.array_equal(scale.cpu().numpy(), ref["scale"]):
         assert np.array_equal(Y2.cpu().numpy(), ref["Y"])
+
+
+@pytest.mark.parametrize("M,K,N,with_bias,out_dtype", [
+    (1, 1, 1, False, torch.float32), (5, 31, 3, True, torch.float32), (64, 33, 64, False, torch.float32),
+    (129, 64, 130, True, torch.float32), (300, 320, 200, False, torch.float16),
+    (256, 1280, 320, True, torch.float32), (130, 4100, 140, False, torch.float32),
+    (200, 128, 129, True, torch.float16)])
+def test_f6_block_scaled_linear_equals_the_int8_one(M, K, N, with_bias, out_dtype):
+    """tdq_w4a4_linear_blocks_f6: the same bits as tdq_w4a4_linear_blocks, and within the
+    bound of the binary32 evaluation of the oracle's Algorithm 1 linear."""
+    _say(f"[f6-blocks] M={M} K={K} N={N} bias={with_bias} out={out_dtype}")
+    rng = np.random.Generator(np.random.PCG64([M, K, N, 3]))
+    KB = -(-K // 32)
+    codes = I.random_codes((M, K), 70)
+    qw = I.random_codes((N, K), 71)
+    spread = 1.0 if out_dtype == torch.float16 else 4.0        # keep binary16 outputs finite
+    bscale = np.exp(rng.normal(-3.0, spread, (M, KB))).astype(np.float32)
+    bias = rng.normal(0, 0.02, N).astype(np.float32) if with_bias else None
+    bs_d = torch.from_numpy(bscale).to(U.dev())
+    ws_d = torch.from_numpy(WS[:N]).to(U.dev())
+    bias_d = None if bias is None else torch.from_numpy(bias).to(U.dev())
+    A6 = torch.from_numpy(f6_fragments(codes)).to(U.dev())
+    B6 = torch.from_numpy(f6_fragments(qw)).to(U.dev())
+    Y6 = tdq.tdq_w4a4_linear_blocks_f6(A6, bs_d, K, B6, N, ws_d, bias_d, out_dtype)
+    Y8 = tdq.tdq_w4a4_linear_blocks(U.pack_to_device(codes), bs_d, K, U.pack_to_device(qw), ws_d, bias_d,
+                                    out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(Y6, Y8)
+    Yref = O.blocks_linear(codes, bscale, 32, qw, WS[:N], bias)
+    tol = _blocks_linear_bound(codes, bscale, qw, WS[:N], bias, KB)
+    if out_dtype == torch.float16:
+        tol = tol * 1.001 + 2.0 ** -11 * 1.001 * np.abs(Yref) + 2.0 ** -24   # + half an ulp of binary16
+    assert (np.abs(Y6.cpu().numpy().astype(np.float64) - Yref) <= tol).all()
