@@ -314,7 +314,11 @@ int tdq_w4a4_linear_f6(const uint8_t* Qx6, const int32_t* group_id, const float*
 /*
  * tdq_w4a4_linear_blocks on f6-fragment operands: same definition, same bits of Y.  The
  * 6-bit instruction delivers each block's sum as a float, so the per-block rescale costs
- * 16 instead of 38 vector instructions per matrix instruction.
+ * 16 instead of 38 vector instructions per matrix instruction.  Qx6 / Qw6: f6 fragments
+ * of the [M, K] / [N, K] codes (device, 16-byte aligned); block_scale [M, ld_s] floats
+ * (device), ld_s >= ceil(K / 32) and <= 2^22; w_scale [N], bias [N] or NULL; Y [M, ld_y]
+ * binary32 or binary16.  Nothing is allocated; asynchronous on `stream`.
+ * Errors: TDQ_ERR_NULL / _DTYPE / _SHAPE / _ALIGN / _HIP.
  */
 int tdq_w4a4_linear_blocks_f6(const uint8_t* Qx6, const float* block_scale, int64_t ld_s, int64_t M,
                               int32_t K, int32_t N, const uint8_t* Qw6, const float* w_scale,

@@ -536,6 +536,7 @@ int tdq_w4a4_linear_blocks_f6(const uint8_t* Qx6, const float* block_scale, int6
   if (M < 1 || K < 1 || N < 1 || M > (int64_t)1 << 30 || K > 131072) return TDQ_ERR_SHAPE;
   const int64_t KB = ((int64_t)K + TDQ_BLOCK - 1) / TDQ_BLOCK;
   if (ld_y < N || ld_s < KB) return TDQ_ERR_SHAPE;
+  if (ld_s > ((int64_t)1 << 22)) return TDQ_ERR_SHAPE;     // 128 rows of scales within 32-bit offsets
   if ((reinterpret_cast<uintptr_t>(Qx6) & 15) || (reinterpret_cast<uintptr_t>(Qw6) & 15))
     return TDQ_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(block_scale) & 3) return TDQ_ERR_ALIGN;

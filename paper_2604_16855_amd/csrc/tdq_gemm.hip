@@ -85,6 +85,30 @@ __device__ __forceinline__ h2v round_pair_to_half(float a, float b) {
   return __builtin_convertvector(v, h2v);
 }
 
+// 16 bytes of consecutive outputs with one store (p aligned to 16 bytes).
+template <typename OUT>
+struct OutVec;
+template <>
+struct OutVec<float> { static constexpr int W = 4; };
+template <>
+struct OutVec<_Float16> { static constexpr int W = 8; };
+template <typename OUT>
+__device__ __forceinline__ void store_out_vec(OUT* p, const float (&y)[OutVec<OUT>::W]);
+template <>
+__device__ __forceinline__ void store_out_vec<float>(float* p, const float (&y)[4]) {
+  typedef float f4v __attribute__((ext_vector_type(4)));
+  const f4v v = {y[0], y[1], y[2], y[3]};
+  __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(p));
+}
+template <>
+__device__ __forceinline__ void store_out_vec<_Float16>(_Float16* p, const float (&y)[8]) {
+  typedef _Float16 h8v __attribute__((ext_vector_type(8)));
+  const h2v a = round_pair_to_half(y[0], y[1]), b = round_pair_to_half(y[2], y[3]);
+  const h2v c = round_pair_to_half(y[4], y[5]), d = round_pair_to_half(y[6], y[7]);
+  const h8v v = {a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+  __builtin_nontemporal_store(v, reinterpret_cast<h8v*>(p));
+}
+
 // Wavefront tile = (32 MT) x (32 NT) of Y, workgroup = 2 x 2 wavefronts.
 //   MT = NT = 4: 256 x 256 per workgroup, 256 accumulator registers per lane, one
 //                wavefront per SIMD; 3 expand operations per matrix instruction.
@@ -1365,32 +1389,72 @@ hipError_t launch_w4a4_gemm_f6(const uint8_t* A6, const uint8_t* B6, int K, cons
 // ---------------------------------------------------------------------------
 // The block-scaled contraction (one step per row and 32-code block) on f6 fragments.
 // The 6-bit instruction covers 64 codes = two blocks, lanes 0-31 supplying the even
-// block and lanes 32-63 the odd one of the row operand; zeroing the other half of that
-// operand makes it deliver one block's sum, already as a float, so the rescale is one
-// fused multiply-add per element and block (16 per matrix instruction) instead of a
-// conversion and a multiply-add on top of the nibble expansion (38): the kernel stays
-// bound by the vector unit, at 2.4 times fewer vector instructions.  Same arithmetic as
+// block and lanes 32-63 the odd one of an operand; zeroing the other half of one operand
+// makes it deliver one block's sum, already as a float, so the rescale is one fused
+// multiply-add per element and block (16 per matrix instruction) instead of a conversion
+// and a multiply-add on top of the nibble expansion (38).  Same arithmetic as
 // k_w4a4_gemm_blocks (f <- fma(acc_kb, Delta[m, kb], f), kb ascending): same bits.
 //
-// 128 x 128 tile, 2 x 2 wavefronts of 64 x 64; a stage is 128 codes of K (two K blocks of
-// 64 = four scale blocks): 8 chunks of 3 KiB of fragments, register-staged into LDS as
-// they are (a lane's 24-byte operand is read as three 8-byte pieces, conflict-free), and
-// the steps block-major as in k_w4a4_gemm_blocks.
+// The weights are the instruction's row operand and the activations its column operand,
+// so a lane holds ONE activation row m (= lane % 32) and 16 output channels: Delta[m, kb]
+// is one register per lane instead of sixteen.
+//
+// 128 x 128 tile, 2 x 2 wavefronts of 64 x 64; a stage is 128 codes of K = four scale
+// blocks = four "rounds" of 4 matrix instructions + 64 multiply-adds per wavefront.  The
+// kernel is bound by the vector unit, so the two must overlap inside a wavefront: a round
+// consumes the four results of the round before, one at a time, and re-issues the matrix
+// instruction into the result registers just freed, so every result has three quarters
+// of a round (about 200 cycles) to arrive and the vector unit never waits for the matrix
+// pipe.  Operands of a round are read from LDS during the round before.
+//   Ring of three slots of 24 KiB + the stage's scales [4][128], all by direct-to-LDS
+//   loads (8 per wavefront and stage, no staging registers).  Everything read from the
+//   slot of stage s is read by round 2 of stage s; the barrier in that round publishes
+//   stage s + 1, and right behind it the loads of stage s + 3 go into the slot of stage
+//   s: two full stages of flight.  A half-zero operand is read as such: the lanes of the
+//   unwanted half read 24 zero bytes (one multiply-add on the address, no selects on the
+//   data).  No branch inside the stage: a branch would end the basic block and the
+//   compiler would regroup the instructions.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void dma16s(const uint8_t* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_base)
+               : "memory");
+}
+// 64 floats from 64 addresses -> 64 consecutive floats of LDS
+__device__ __forceinline__ void dma4s(const float* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_base)
+               : "memory");
+}
+
 template <typename OUT>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks_f6(
     const uint8_t* __restrict__ A6, const uint8_t* __restrict__ B6, int KB64,
     const float* __restrict__ bscale, long long ld_s, int M, int K, int N,
     const float* __restrict__ w_scale, const float* __restrict__ bias, OUT* __restrict__ Y,
-    long long ld_y, int m_tiles, int n_tiles) {
-  constexpr int MT = 2, NT = 2, BM = 128, BN = 128;
+    long long ld_y, int m_tiles, int n_tiles, int y_vec_ok) {
+  // WM x 2 wavefronts of 64 x 64.  (WM = 4, one workgroup of 256 x 128 per CU, brings a
+  // quarter less into the CU per stage, but was 3 % slower on both large shapes: with one
+  // workgroup per CU nothing overlaps a tile's first loads and its output phase.)
+  constexpr int WM = 2;
+  constexpr int MT = 2, NT = 2, BM = WM * 64, BN = 128;
+  constexpr int NW = 2 * WM, THREADS = NW * 64;
   constexpr int KS = 2;                          // 64-blocks of K per stage
   constexpr int SBK = 2 * KS;                    // scale blocks per stage
   constexpr int CH = KS * F6_FRAG;               // 3072 bytes per row block and stage
-  constexpr int SLOT = 8 * CH;                   // 4 row blocks of A, 4 of B
-  __shared__ __attribute__((aligned(1024))) uint8_t ring[2][SLOT];
-  __shared__ __attribute__((aligned(16))) float sD[2][SBK][BM];
-  __shared__ float sCol[BN], sBias[BN];
+  constexpr int ACH = 2 * WM;                    // row blocks of A; then 4 of B
+  constexpr int SLOT = (ACH + 4) * CH;
+  constexpr int PIECES = SLOT / 1024;            // 1 KiB direct loads per stage: 24 or 36
+  constexpr int NDMA = (PIECES + NW - 1) / NW;   // per wavefront: 6 or 5 (4 of the 40 twice)
+  constexpr int NVM = NDMA + 2;                  // + 2 scale loads
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[3 * SLOT];
+  __shared__ __attribute__((aligned(256))) float sD[3][BM][SBK];
+  __shared__ __attribute__((aligned(16))) float sCol[BN], sBias[BN];
+  __shared__ __attribute__((aligned(32))) unsigned sZero[8];
+  typedef unsigned u2v __attribute__((ext_vector_type(2)));
+  typedef const __attribute__((address_space(3))) u2v* lds_u2;
 
   const int bid = blockIdx.x;
   const int xcd = bid % XCDS, idx = bid / XCDS;
@@ -1400,168 +1464,261 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks_f6(
   const int m0 = m_tile * BM, n0 = n_tile * BN;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;        // wm < WM
   const int stages = KB64 / KS;
   const int KB = (K + 31) / 32;                  // scale blocks that exist
   const int MBk = (M + 31) / 32, NBk = (N + 31) / 32;
 
-  for (int j = tid; j < BN; j += GEMM_THREADS) {
+  for (int j = tid; j < BN; j += THREADS) {
     const int n = n0 + j;
     sCol[j] = n < N ? w_scale[n] : 0.f;
     sBias[j] = (bias && n < N) ? bias[n] : 0.f;
   }
+  if (tid < 8) sZero[tid] = 0u;
 
-  // The fragments of a stage are 24 KiB of contiguous 3 KiB chunks: direct-to-LDS loads
-  // of 1 KiB, 6 per wavefront, no staging registers (with register staging the compiler
-  // put the loaded data into the registers of the matrix results and had to wait for
-  // every stage's loads before computing).  Piece wave + 4 e: chunk (row block) piece / 3,
-  // part piece % 3.
-  constexpr int NDMA = SLOT / 1024 / 4;
-  const uint8_t* src[NDMA];
+  // piece wave + NW e of a stage (past the last: one of the first again, the same bytes
+  // to the same place): chunk (row block) piece / 3, 1 KiB part piece % 3
+  const uint8_t* sbase[NDMA];
+  int piece[NDMA];
 #pragma unroll
   for (int e = 0; e < NDMA; ++e) {
-    const int pi = wave + 4 * e;
+    int pi = wave + NW * e;
+    pi = pi < PIECES ? pi : pi - PIECES;
+    piece[e] = pi;
     const int c = pi / 3, part = pi % 3;
     long long rb;
     const uint8_t* base;
-    if (c < 4) {
-      rb = (long long)m_tile * 4 + c;
+    if (c < ACH) {
+      rb = (long long)m_tile * ACH + c;
       rb = rb < MBk ? rb : MBk - 1;              // past the end: a harmless re-read
       base = A6;
     } else {
-      rb = (long long)n_tile * 4 + (c - 4);
+      rb = (long long)n_tile * 4 + (c - ACH);
       rb = rb < NBk ? rb : NBk - 1;
       base = B6;
     }
-    src[e] = base + rb * KB64 * F6_FRAG + part * 1024 + lane * 16;
+    sbase[e] = base + rb * KB64 * F6_FRAG + part * 1024;
   }
-  const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)&ring[0][0];
-  const int drow = tid >> 1, dcol = (tid & 1) * (SBK / 2);
-  const bool d_row_ok = m0 + drow < M;
-  const float* pd = bscale + (long long)(m0 + (d_row_ok ? drow : 0)) * ld_s + dcol;
-
-  float gd[SBK / 2];
-  auto load_stage = [&](int st, int buf) {
+  const unsigned lane16 = lane * 16;
+  const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)ring;
+  const unsigned sd_base = (unsigned)(size_t)(__attribute__((address_space(3))) float*)&sD[0][0][0];
+  const unsigned zero_addr = (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)sZero;
+  // scales of a stage, [BM][4] in LDS: one load brings 16 rows x 4 blocks, four lanes per
+  // row, so it touches 16 lines (a lane per row would touch 64 for the same 256 bytes,
+  // and the L2 request rate is what this kernel runs against); BM / 16 = 2 NW loads,
+  // wavefront w brings row groups w and w + NW.  Rows and blocks past the end are
+  // clamped to real ones (their products are zero or unused); only the last stage can
+  // have fewer than four blocks.
+  const float* d_row0 = bscale + (long long)m0 * ld_s;
+  const int last_real = KB - 1 - (stages - 1) * SBK;       // 0..3 (or more: no clamp)
+  unsigned d_voff[2], d_voff_last[2];
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    int row = (wave + hf * NW) * 16 + (lane >> 2);
+    row = m0 + row < M ? row : M - 1 - m0;
+    const int b = lane & 3;
+    d_voff[hf] = ((unsigned)row * (unsigned)ld_s + (unsigned)b) * 4u;
+    d_voff_last[hf] = ((unsigned)row * (unsigned)ld_s + (unsigned)(b < last_real ? b : last_real)) * 4u;
+  }
+  // stage st (clamped to the last: past the end a harmless re-load) -> slot (run-time
+  // 0, 1, 2 in turn: with compile-time slots the compiler hoists every LDS address out
+  // of the loop and spills them)
+  auto dma_stage = [&](int slot, int st) {
+    const int sc = st < stages ? st : stages - 1;
 #pragma unroll
     for (int e = 0; e < NDMA; ++e)
-      dma16(src[e] + (long long)st * CH,
-            __builtin_amdgcn_readfirstlane(ring_base + buf * SLOT + (__builtin_amdgcn_readfirstlane(wave) + 4 * e) * 1024));
-    // 4-byte loads, as in k_w4a4_gemm_blocks
-    const int b0 = st * SBK + dcol;
+      dma16s(sbase[e] + (long long)sc * CH, lane16,
+             __builtin_amdgcn_readfirstlane(ring_base + slot * SLOT + piece[e] * 1024));
+    const bool last = sc == stages - 1;
 #pragma unroll
-    for (int j = 0; j < SBK / 2; ++j) gd[j] = (d_row_ok && b0 + j < KB) ? pd[st * SBK + j] : 0.f;
-  };
-  auto store_stage = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < SBK / 2; ++j) sD[buf][dcol + j][drow] = gd[j];
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the direct loads have landed
+    for (int hf = 0; hf < 2; ++hf)
+      dma4s(d_row0 + sc * SBK, last ? d_voff_last[hf] : d_voff[hf],
+            __builtin_amdgcn_readfirstlane(sd_base + (slot * BM + (wave + hf * NW) * 16) * SBK * 4));
   };
 
-  float accf[MT][NT][16];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) accf[i][j][r] = 0.f;
-
-  load_stage(0, 0);
-  store_stage(0);
-  __syncthreads();
-
-  const int a_off = wm * 2 * CH + lane * 24, b_off = (4 + wn * 2) * CH + lane * 24;
-  const int d_off = wm * 32 * MT + (lane >> 5) * 4;
+  // operand reads.  x (activations): lanes of half h read their 24 bytes, the others the
+  // zeros: address = base + flag * offset, one instruction, kept where it is written.
   const bool lower = lane < 32;
-  const v16f zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  auto read_frag = [&](int buf, int off) {
-    const uint2* p = reinterpret_cast<const uint2*>(&ring[buf][off]);
-    const uint2 q0 = p[0], q1 = p[1], q2 = p[2];
+  const unsigned x_lane = ring_base + (wm * 2 * CH + lane * 24);
+  const unsigned w_lane = ring_base + ((ACH + wn * 2) * CH + lane * 24);
+  const unsigned x_base[2] = {lower ? x_lane : zero_addr, lower ? zero_addr : x_lane};
+  const unsigned x_flag[2] = {lower ? 1u : 0u, lower ? 0u : 1u};
+  const unsigned d_lane = sd_base + (wm * 64 + (lane & 31)) * SBK * 4;
+  auto read24 = [&](unsigned addr) {
+    const lds_u2 p = (lds_u2)(size_t)addr;
+    const u2v q0 = p[0], q1 = p[1], q2 = p[2];
     const v8i v = {(int)q0.x, (int)q0.y, (int)q1.x, (int)q1.y, (int)q2.x, (int)q2.y, 0, 0};
     return v;
   };
-  for (int st = 0; st < stages; ++st) {
-    const int cur = st & 1;
-    if (st + 1 < stages) load_stage(st + 1, cur ^ 1);
-#pragma unroll 1
-    for (int kk = 0; kk < KS; ++kk) {
-      v8i alo[MT], ahi[MT], b[NT];
+  auto read_x = [&](v8i (&dst)[MT], int slot, int kk, int h) {          // kk, h compile-time
 #pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        const v8i a = read_frag(cur, a_off + i * CH + kk * F6_FRAG);
-#pragma unroll
-        for (int w = 0; w < 8; ++w) {            // the operand restricted to one scale block
-          alo[i][w] = lower ? a[w] : 0;
-          ahi[i][w] = lower ? 0 : a[w];
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j) b[j] = read_frag(cur, b_off + j * CH + kk * F6_FRAG);
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        float dl[MT][16];
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float4 d4 =
-                *reinterpret_cast<const float4*>(&sD[cur][2 * kk + h][d_off + i * 32 + q * 8]);
-            dl[i][4 * q] = d4.x; dl[i][4 * q + 1] = d4.y; dl[i][4 * q + 2] = d4.z; dl[i][4 * q + 3] = d4.w;
-          }
-        // all four matrix instructions first, into four sets of result registers: the
-        // multiply-adds on the first result then run while the others are still in the
-        // matrix pipe (left to itself the compiler re-used one set and serialised them)
-        v16f t[MT][NT];
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-          for (int j = 0; j < NT; ++j)
-            t[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(h ? ahi[i] : alo[i], b[j], zero, 3, 3,
-                                                                      0, 127, 0, 127);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-          for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              accf[i][j][r] = __builtin_fmaf(t[i][j][r], dl[i][r], accf[i][j][r]);
-      }
+    for (int i = 0; i < MT; ++i) {
+      const unsigned off = (unsigned)(slot * SLOT + i * CH + kk * F6_FRAG);   // scalar
+      unsigned addr;
+      asm volatile("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(addr) : "v"(x_flag[h]), "s"(off), "v"(x_base[h]));
+      dst[i] = read24(addr);
     }
-    if (st + 1 < stages) store_stage(cur ^ 1);
-    __syncthreads();
-  }
+  };
+  auto read_w = [&](v8i (&dst)[NT], int slot, int kk) {
+    const unsigned w_slot = w_lane + (unsigned)(slot * SLOT);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) dst[j] = read24(w_slot + (unsigned)(j * CH + kk * F6_FRAG));
+  };
+  typedef float f4v __attribute__((ext_vector_type(4)));
+  typedef const __attribute__((address_space(3))) f4v* lds_f4;
+  auto read_dl = [&](f4v (&dst)[MT], int slot) {           // the lane's rows, the stage's 4 blocks
+    const lds_f4 p = (lds_f4)(size_t)(d_lane + (unsigned)(slot * SBK * BM * 4));
+#pragma unroll
+    for (int i = 0; i < MT; ++i) dst[i] = p[i * 32];
+  };
 
-  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+  float accf[MT][NT][16];
+  v16f t[MT][NT];
+  f4v dcur[MT];                                  // the stage's scales of the lane's rows
+  float dlast[MT];                               // those of the previous stage's last block
 #pragma unroll
-  for (int i = 0; i < MT; ++i)
+  for (int i = 0; i < MT; ++i) {
+    dlast[i] = 0.f;
+    dcur[i] = f4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      const int rl = wm * 32 * MT + i * 32 + (r >> 2) * 8 + rquad + (r & 3);
-      const int m = m0 + rl;
-      float y0[NT], y1[NT];
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int cl = wn * 32 * NT + j * 32 + ccol;
-        y0[j] = accf[i][j][r] * sCol[cl];
-        y1[j] = accf[i][j][r + 1] * sCol[cl];
+      for (int r = 0; r < 16; ++r) {
+        accf[i][j][r] = 0.f;
+        t[i][j][r] = 0.f;
+      }
+  }
+  const v16f zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto consume = [&](int i, int j, float d) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accf[i][j][r] = __builtin_fmaf(t[i][j][r], d, accf[i][j][r]);
+  };
+
+  v8i xbuf[2][MT], wbuf[2][NT];                  // activations by half h, weights by kk
+  dma_stage(0, 0);
+  dma_stage(1, 1);
+  dma_stage(2, 2);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NVM) : "memory");   // stage 0 has landed
+  __syncthreads();
+  read_x(xbuf[0], 0, 0, 0);
+  read_w(wbuf[0], 0, 0);
+
+  // Round R of the stage in slot CUR (NXT: the next stage's).  R and the register
+  // indices are compile-time constants.  Round 0 consumes the last group of the stage
+  // before (scale kept in dlast) and reads this stage's scales; round R > 0 consumes
+  // group R - 1.
+#define TDQ_BF6_SLOT(R, I, J)                                                                     \
+  do {                                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    consume(I, J, (R) == 0 ? dlast[I] : dcur[I][((R) + 3) & 3]);                                  \
+    t[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wbuf[(R) >> 1][J], xbuf[(R) & 1][I], \
+                                                              zero, 3, 3, 0, 127, 0, 127);        \
+  } while (0)
+#define TDQ_BF6_ROUND(s, CUR, NXT, R)                                                             \
+  do {                                                                                            \
+    /* the next round's activations first: four slots until they are used */                     \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    if ((R) < 3) read_x(xbuf[((R) + 1) & 1], CUR, ((R) + 1) >> 1, ((R) + 1) & 1);                 \
+    else read_x(xbuf[0], NXT, 0, 0);                                                              \
+    TDQ_BF6_SLOT(R, 0, 0);                                                                        \
+    if ((R) == 0) {                                                                               \
+      read_dl(dcur, CUR);                         /* the old ones were spent in round 3 */        \
+      read_w(wbuf[1], CUR, 1);                    /* for rounds 2 and 3 */                        \
+    }                                                                                             \
+    TDQ_BF6_SLOT(R, 0, 1);                                                                        \
+    TDQ_BF6_SLOT(R, 1, 0);                                                                        \
+    if ((R) == 2) {                                                                               \
+      __builtin_amdgcn_sched_barrier(0);                                                          \
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NVM) : "memory");                       \
+      __builtin_amdgcn_s_barrier();                                                               \
+      dma_stage(CUR, (s) + 3);                                                                    \
+      read_w(wbuf[0], NXT, 0);                    /* for rounds 0 and 1 of the next stage */      \
+    }                                                                                             \
+    TDQ_BF6_SLOT(R, 1, 1);                                                                        \
+    if ((R) == 3) {                                                                               \
+      dlast[0] = dcur[0][3];                                                                      \
+      dlast[1] = dcur[1][3];                                                                      \
+    }                                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  } while (0)
+
+  int cur = 0, nxt = 1, nn = 2;
+#pragma unroll 1
+  for (int s = 0; s < stages; ++s) {
+    TDQ_BF6_ROUND(s, cur, nxt, 0);
+    TDQ_BF6_ROUND(s, cur, nxt, 1);
+    TDQ_BF6_ROUND(s, cur, nxt, 2);
+    TDQ_BF6_ROUND(s, cur, nxt, 3);
+    const int o = cur;
+    cur = nxt;
+    nxt = nn;
+    nn = o;
+  }
+#undef TDQ_BF6_ROUND
+#undef TDQ_BF6_SLOT
+  consume(0, 0, dlast[0]);                       // the last round's results
+  consume(0, 1, dlast[0]);
+  consume(1, 0, dlast[1]);
+  consume(1, 1, dlast[1]);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // nothing of ours may still be landing
+
+  // Register r of result (i, j) is row m = 32 i + lane % 32 of the wavefront's 64 and
+  // channel 32 j + 8 (r / 4) + 4 (lane / 32) + r % 4: a lane holds short runs of 32 rows,
+  // which as stores would touch 32 lines with 8 or 16 bytes each.  So the wavefront's
+  // 64 x 64 results (already scaled) go, 32 rows at a time, through its own 8.5 KiB of the
+  // ring, now free, and leave row-major: every store instruction writes whole 128-byte lines.
+  __syncthreads();                               // every wavefront's loads have landed
+  constexpr int TP = 68;                         // pitch in floats: 16-byte aligned rows, staggered banks
+  float* T = reinterpret_cast<float*>(ring) + wave * (32 * TP);
+  const int ml = lane & 31, nq = (lane >> 5) * 4;
+  constexpr int W = 16 / (int)sizeof(OUT);       // outputs per 16-byte store: 4 or 8
+  constexpr int LPR = 64 / W;                    // lanes per row of 64
+  constexpr int RPI = 64 / LPR;                  // rows per store instruction
+  const int rsub = lane / LPR, col = (lane % LPR) * W;
+  const int nbase = n0 + wn * 64 + col;
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {                 // 32 rows at a time
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int cw = j * 32 + rq * 8 + nq;     // channel within the wavefront's 64
+        const float4 sc4 = *reinterpret_cast<const float4*>(&sCol[wn * 64 + cw]);
+        const float4 bi4 = *reinterpret_cast<const float4*>(&sBias[wn * 64 + cw]);
+        float4 y = make_float4(accf[i][j][4 * rq] * sc4.x, accf[i][j][4 * rq + 1] * sc4.y,
+                               accf[i][j][4 * rq + 2] * sc4.z, accf[i][j][4 * rq + 3] * sc4.w);
         if (bias) {
-          y0[j] = y0[j] + sBias[cl];
-          y1[j] = y1[j] + sBias[cl];
+          y.x = y.x + bi4.x;
+          y.y = y.y + bi4.y;
+          y.z = y.z + bi4.z;
+          y.w = y.w + bi4.w;
+        }
+        *reinterpret_cast<float4*>(&T[ml * TP + cw]) = y;
+      }
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; ++it) {
+      const int row = it * RPI + rsub;
+      const int m = m0 + wm * 64 + i * 32 + row;
+      float y[W];
+#pragma unroll
+      for (int q = 0; q < W / 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4*>(&T[row * TP + col + 4 * q]);
+        y[4 * q] = v.x; y[4 * q + 1] = v.y; y[4 * q + 2] = v.z; y[4 * q + 3] = v.w;
+      }
+      if (m < M) {
+        OUT* yp = Y + (long long)m * ld_y + nbase;
+        if (y_vec_ok && nbase + W - 1 < N) {
+          store_out_vec<OUT>(yp, y);
+        } else {
+#pragma unroll
+          for (int e = 0; e < W; ++e)
+            if (nbase + e < N) store_out<OUT>(yp + e, y[e]);
         }
       }
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn * 32 * NT + j * 32 + ccol;
-        if (m < M && n < N) store_out<OUT>(Y + (long long)m * ld_y + n, y0[j]);
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn * 32 * NT + j * 32 + ccol;
-        if (m + 1 < M && n < N) store_out<OUT>(Y + (long long)(m + 1) * ld_y + n, y1[j]);
-      }
     }
+  }
 }
 
 hipError_t launch_w4a4_gemm_blocks_f6(const uint8_t* A6, const uint8_t* B6, const float* bscale,
@@ -1572,14 +1729,17 @@ hipError_t launch_w4a4_gemm_blocks_f6(const uint8_t* A6, const uint8_t* B6, cons
   const int m_tiles = (M + 127) / 128, n_tiles = (N + 127) / 128;
   const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
   const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
+  // 16-byte stores where every row of Y starts on a 16-byte boundary
+  const int per16 = y_dt == TDQ_F32 ? 4 : 8;
+  const int y_vec_ok = (reinterpret_cast<uintptr_t>(Y) % 16 == 0 && ld_y % per16 == 0) ? 1 : 0;
   if (y_dt == TDQ_F32)
     hipLaunchKernelGGL((k_w4a4_gemm_blocks_f6<float>), dim3(grid), dim3(GEMM_THREADS), 0, st, A6, B6,
                        KB64, bscale, ld_s, M, K, N, w_scale, bias, static_cast<float*>(Y), ld_y, m_tiles,
-                       n_tiles);
+                       n_tiles, y_vec_ok);
   else
     hipLaunchKernelGGL((k_w4a4_gemm_blocks_f6<_Float16>), dim3(grid), dim3(GEMM_THREADS), 0, st, A6, B6,
                        KB64, bscale, ld_s, M, K, N, w_scale, bias, static_cast<_Float16*>(Y), ld_y,
-                       m_tiles, n_tiles);
+                       m_tiles, n_tiles, y_vec_ok);
   return hipGetLastError();
 }
 

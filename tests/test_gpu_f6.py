@@ -232,3 +232,37 @@ def test_f6_block_scaled_linear_equals_the_int8_one(M, K, N, with_bias, out_dtyp
     if out_dtype == torch.float16:
         tol = tol * 1.001 + 2.0 ** -11 * 1.001 * np.abs(Yref) + 2.0 ** -24   # + half an ulp of binary16
     assert (np.abs(Y6.cpu().numpy().astype(np.float64) - Yref) <= tol).all()
+
+
+@pytest.mark.parametrize("M,K,N,with_bias,out_dtype", [
+    (16500, 200, 1030, True, torch.float32), (33000, 96, 520, False, torch.float16)])
+def test_f6_block_scaled_linear_many_tiles(M, K, N, with_bias, out_dtype):
+    """Several workgroups per CU, ragged in M, K and N: the same bits as
+    tdq_w4a4_linear_blocks everywhere, and sampled rows within the bound of the oracle's
+    Algorithm 1 linear."""
+    _say(f"[f6-blocks-many] M={M} K={K} N={N} bias={with_bias} out={out_dtype}")
+    rng = np.random.Generator(np.random.PCG64([M, K, N, 5]))
+    KB = -(-K // 32)
+    codes = I.random_codes((M, K), 72)
+    qw = I.random_codes((N, K), 73)
+    bscale = np.exp(rng.normal(-3.0, 1.0, (M, KB))).astype(np.float32)
+    wsc = np.exp(rng.normal(-4.0, 0.5, N)).astype(np.float32)
+    bias = rng.normal(0, 0.02, N).astype(np.float32) if with_bias else None
+    bs_d = torch.from_numpy(bscale).to(U.dev())
+    ws_d = torch.from_numpy(wsc).to(U.dev())
+    bias_d = None if bias is None else torch.from_numpy(bias).to(U.dev())
+    A6 = tdq.tdq_pack_codes_f6(U.pack_to_device(codes), K)
+    B6 = tdq.tdq_pack_codes_f6(U.pack_to_device(qw), K)
+    Y6 = tdq.tdq_w4a4_linear_blocks_f6(A6, bs_d, K, B6, N, ws_d, bias_d, out_dtype)
+    Y8 = tdq.tdq_w4a4_linear_blocks(U.pack_to_device(codes), bs_d, K, U.pack_to_device(qw), ws_d, bias_d,
+                                    out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(Y6, Y8)
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(M - 300, M),
+                                     rng.integers(0, M, 200)]))
+    Yref = O.blocks_linear(codes[rows], bscale[rows], 32, qw, wsc, bias)
+    tol = _blocks_linear_bound(codes[rows], bscale[rows], qw, wsc, bias, KB)
+    if out_dtype == torch.float16:
+        tol = tol * 1.001 + 2.0 ** -11 * 1.001 * np.abs(Yref) + 2.0 ** -24
+    got = Y6[torch.from_numpy(rows).to(U.dev())].cpu().numpy().astype(np.float64)
+    assert (np.abs(got - Yref) <= tol).all()
