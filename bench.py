@@ -234,7 +234,7 @@ def blocks_leg(layers, torch, tdq, iters=10, warm=5):
     binary32, 2 vector operations (convert, fused multiply-add) per output element and
     block, which bounds it by the vector unit rather than by the matrix cores."""
     res = {"layers": []}
-    tot = 0.0
+    tot = tot6 = 0.0
     for L in layers:
         lc = L.lc
         p = tdq.block_params()
@@ -267,6 +267,31 @@ def blocks_leg(layers, torch, tdq, iters=10, warm=5):
                        "frac": round(lane_ops / (tl * 1e-3) / 1e12 / PEAK_VALU_TLOPS, 4),
                        "tops_int8": round(L.gemm_ops / (tl * 1e-3) / 1e12, 1)}})
         tot += tq + tl
+        # the same granularity with the codes as bf6 operands of the 6-bit matrix instruction
+        # (tdq_quantize_act_blocks_f6 -> tdq_w4a4_linear_blocks_f6): the same bits of Y,
+        # 16 instead of 38 vector instructions per matrix instruction
+        F = torch.empty((tdq.f6_bytes(lc.M, lc.C),), dtype=torch.uint8, device=L.X.device)
+        W6 = tdq.tdq_pack_codes_f6(L.Qw, lc.C)                       # offline
+        tq6 = tl6 = 0.0
+        for it in range(warm + iters):
+            ev[0].record()
+            tdq.tdq_quantize_act_blocks_f6(L.X, p, out=(F, bs))
+            ev[1].record()
+            tdq.tdq_w4a4_linear_blocks_f6(F, bs, lc.C, W6, lc.N, L.w_scale, None, out=L.Y)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it >= warm:
+                tq6 += ev[0].elapsed_time(ev[1])
+                tl6 += ev[1].elapsed_time(ev[2])
+        tq6, tl6 = tq6 / iters, tl6 / iters
+        q6bytes = e * (2 if lc.dtype == "f16" else 4) + tdq.f6_bytes(lc.M, lc.C) + lc.M * KB * 4
+        res["layers"][-1]["f6_route"] = {
+            "quantize_ms": round(tq6, 4), "linear_ms": round(tl6, 4),
+            "quantize_gbs": round(q6bytes / (tq6 * 1e-3) / 1e9, 1),
+            "linear_lane_tops": round(lane_ops / 2.0 / (tl6 * 1e-3) / 1e12, 2),
+            "tops_int8": round(L.gemm_ops / (tl6 * 1e-3) / 1e12, 1)}
+        tot6 += tq6 + tl6
+        del F, W6
         # the same buffer read as a feature map [B, C, 64, 64] (the 4-D branch): re-layout
         # alone, and the per-block sweep reading the map in place
         Xc = L.X.reshape(lc.B, lc.C, 64, lc.T // 64)
@@ -290,6 +315,7 @@ def blocks_leg(layers, torch, tdq, iters=10, warm=5):
             "quantize_blocks_chw_gbs": round(qbytes / (tc * 1e-3) / 1e9, 1)}
         del bs, Q, Xt
     res["ms_per_pass"] = round(tot, 4)
+    res["ms_per_pass_f6_route"] = round(tot6, 4)
     # the token-set path overwrote nothing it needs: L.Y is rewritten by the next step
     return res
 

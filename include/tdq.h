@@ -312,6 +312,16 @@ int tdq_w4a4_linear_f6(const uint8_t* Qx6, const int32_t* group_id, const float*
                        int32_t* acc_dump, void* stream);
 
 /*
+ * tdq_quantize_act_blocks writing f6 fragments (the operand of tdq_w4a4_linear_blocks_f6)
+ * instead of packed nibbles: the same codes, steps and radii.  Qx6 holds
+ * tdq_f6_bytes(B*T, C) bytes (device, 16-byte aligned), all written (rows and codes of
+ * the padding are zero); the other arguments as in tdq_quantize_act_blocks.
+ */
+int tdq_quantize_act_blocks_f6(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                               int64_t ld_x, const tdq_params* p, uint8_t* Qx6, float* block_scale,
+                               float* block_clip, int64_t ld_s, void* stream);
+
+/*
  * tdq_w4a4_linear_blocks on f6-fragment operands: same definition, same bits of Y.  The
  * 6-bit instruction delivers each block's sum as a float, so the per-block rescale costs
  * 16 instead of 38 vector instructions per matrix instruction.  Qx6 / Qw6: f6 fragments

@@ -404,6 +404,135 @@ hipError_t launch_quantize_blocks(const void* X, tdq_dtype dt, long long M, int 
 }
 
 // ---------------------------------------------------------------------------
+// The sweep writing the operand format of the 6-bit contraction (f6 fragments of 32 rows
+// x 64 codes, see k_quantize_f6) instead of packed nibbles; steps and radii as before.
+// A workgroup owns 32 rows x 16 blocks (8 fragments): every wavefront pass runs
+// block_core on NB rows x 16 blocks (reads of 1 KiB per row), the nibble words go to LDS,
+// and after a barrier every thread turns two (row, block) entries -- 32 codes, 16 bytes
+// of nibbles -- into 24 bytes of bf6 patterns: sign-extending extract, integer -> float,
+// one conversion instruction for the 32 (even codes in its first operand, odd ones in its
+// second).  A fragment leaves as 1536 contiguous bytes.  Rows past M and blocks past
+// ceil(C / 32) are zero codes.
+// ---------------------------------------------------------------------------
+typedef float blk_v16f __attribute__((ext_vector_type(16)));
+typedef int blk_v6i __attribute__((ext_vector_type(6)));
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_quantize_blocks_f6(
+    const T* __restrict__ X, long long ld, long long M, int C, int KB, int KB64, int k_tiles,
+    int vec_ok, int kq, int kp, Scalars sc, uint8_t* __restrict__ F, float* __restrict__ bscale,
+    float* __restrict__ bclip, long long ld_s) {
+  constexpr bool PK = sizeof(T) == 2;
+  constexpr int NB = PK ? 2 : 1;                           // blocks per lane = rows per pass
+  constexpr int W = PK ? 4 : 8;
+  constexpr int TBK = 16;                                  // blocks per tile
+  constexpr int PITCH = TBK * 4 + 4;                       // words per tile row: 16-byte reads on disjoint banks
+  constexpr int PASSES = 32 / NB / 4;                      // per wavefront
+  __shared__ __attribute__((aligned(16))) u32 sN[32 * PITCH];
+
+  const long long rb = blockIdx.x / k_tiles;
+  const int kt = blockIdx.x % k_tiles;
+  const long long row0 = rb * 32;
+  const int kbt0 = kt * TBK;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, quad = lane >> 2, ql = lane & 3;
+  const int kb = kbt0 + quad;
+  const int c0 = kb * kBlk + ql * 8;                       // first channel of this lane
+
+#pragma unroll 1
+  for (int p = 0; p < PASSES; ++p) {
+    bool live[NB];
+    long long row[NB];
+    int r_in[NB];
+    u32 raw[NB][W];
+#pragma unroll
+    for (int s = 0; s < NB; ++s) {
+      r_in[s] = (wave * PASSES + p) * NB + s;
+      row[s] = row0 + r_in[s];
+      live[s] = row[s] < M && kb < KB;
+#pragma unroll
+      for (int w = 0; w < W; ++w) raw[s][w] = 0;
+      if (live[s]) {
+        const T* xp = X + row[s] * ld + c0;
+        if (vec_ok && c0 + 8 <= C) {
+          const uint4 q0 = *reinterpret_cast<const uint4*>(xp);
+          raw[s][0] = q0.x; raw[s][1] = q0.y; raw[s][2] = q0.z; raw[s][3] = q0.w;
+          if constexpr (!PK) {
+            const uint4 q1 = *reinterpret_cast<const uint4*>(xp + 4);
+            raw[s][4] = q1.x; raw[s][5] = q1.y; raw[s][6] = q1.z; raw[s][7] = q1.w;
+          }
+        } else {
+          // row tail or unaligned rows; channels at and beyond C are the zero padding
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            if (c0 + i < C) {
+              if constexpr (PK) raw[s][i >> 1] |= (u32)xp[i] << (16 * (i & 1));
+              else raw[s][i] = __float_as_uint(xp[i]);
+            }
+          }
+        }
+      }
+    }
+    u32 word[NB];
+    float cs[NB], ds[NB];
+    block_core<T>(raw, ql, kq, kp, sc, word, cs, ds);      // (a quad without a block works on zeros)
+#pragma unroll
+    for (int s = 0; s < NB; ++s) {
+      if (live[s] && ql == s) {
+        bscale[row[s] * ld_s + kb] = ds[s];
+        if (bclip) bclip[row[s] * ld_s + kb] = cs[s];
+      }
+      sN[r_in[s] * PITCH + quad * 4 + ql] = live[s] ? word[s] : 0u;
+    }
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int e = threadIdx.x + 256 * k;
+    const int f = e >> 6, l = e & 63;                      // fragment of the tile, lane of the fragment
+    const int kb64 = kbt0 / 2 + f;
+    if (kb64 >= KB64) continue;
+    const uint4 w4 = *reinterpret_cast<const uint4*>(&sN[(l & 31) * PITCH + (2 * f + (l >> 5)) * 4]);
+    const u32 w[4] = {w4.x, w4.y, w4.z, w4.w};
+    blk_v16f ev, od;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const u32 wd = w[i >> 2];
+      const int sh = 8 * (i & 3);                          // codes 2 i and 2 i + 1: bits sh, sh + 4
+      ev[i] = (float)((int)(wd << (28 - sh)) >> 28);
+      od[i] = (float)((int)(wd << (24 - sh)) >> 28);
+    }
+    const blk_v6i r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(ev, od, 1.0f);
+    uint2* dst = reinterpret_cast<uint2*>(F + ((rb * KB64 + kb64) * 64 + l) * 24);
+    dst[0] = make_uint2((u32)r[0], (u32)r[1]);
+    dst[1] = make_uint2((u32)r[2], (u32)r[3]);
+    dst[2] = make_uint2((u32)r[4], (u32)r[5]);
+  }
+}
+
+hipError_t launch_quantize_blocks_f6(const void* X, tdq_dtype dt, long long M, int C, long long ld,
+                                     int kq, int kp, const Scalars& sc, uint8_t* F, float* bscale,
+                                     float* bclip, long long ld_s, hipStream_t st) {
+  const int KB = (C + kBlk - 1) / kBlk;
+  const int KB64 = 2 * ((C + 127) / 128);
+  const int k_tiles = (KB64 + 7) / 8;
+  const long long n_rb = (M + 31) / 32;
+  const unsigned grid = (unsigned)(n_rb * k_tiles);        // checked by the caller: < 2^31
+  if (dt == TDQ_F16) {
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0) ? 1 : 0;
+    hipLaunchKernelGGL((k_quantize_blocks_f6<u16>), dim3(grid), dim3(256), 0, st,
+                       static_cast<const u16*>(X), ld, M, C, KB, KB64, k_tiles, vec_ok, kq, kp, sc, F,
+                       bscale, bclip, ld_s);
+  } else {
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 4 == 0) ? 1 : 0;
+    hipLaunchKernelGGL((k_quantize_blocks_f6<float>), dim3(grid), dim3(256), 0, st,
+                       static_cast<const float*>(X), ld, M, C, KB, KB64, k_tiles, vec_ok, kq, kp, sc, F,
+                       bscale, bclip, ld_s);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // The same sweep over a convolutional feature map X[B, C, T] (T = H W tokens, contiguous;
 // Supp. "Implementation details", the 4-D branch): a group is the block of 32 channels
 // of one pixel.  A workgroup owns TT consecutive tokens of one image and walks the

@@ -142,6 +142,9 @@ hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const floa
                                    long long ld_s, int M, int K, int N, const uint8_t* Qw,
                                    long long ld_w, const float* w_scale, const float* bias, void* Y,
                                    tdq_dtype y_dt, long long ld_y, hipStream_t st);
+hipError_t launch_quantize_blocks_f6(const void* X, tdq_dtype dt, long long M, int C, long long ld,
+                                     int kq, int kp, const Scalars& sc, uint8_t* F, float* bscale,
+                                     float* bclip, long long ld_s, hipStream_t st);
 hipError_t launch_quantize_blocks_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                       long long ld_b, int kq, int kp, const Scalars& sc, uint8_t* Q,
                                       long long ld_q, float* bscale, float* bclip, long long ld_s,

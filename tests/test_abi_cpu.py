@@ -28,6 +28,7 @@ def test_every_declared_symbol_is_exported():
             "tdq_calibrate_quantize_fused", "tdq_range_disparity",
             "tdq_calibrate_groups_chw", "tdq_w4a4_linear_f6", "tdq_quantize_act_f6",
             "tdq_pack_codes_f6", "tdq_f6_bytes", "tdq_w4a4_linear_blocks_f6",
+            "tdq_quantize_act_blocks_f6",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -306,6 +307,14 @@ def test_f6_entries_reject_bad_arguments():
     assert call(G=300) == tdq.ERR_PARAM
     assert call(Qw=FAKE + 8) == tdq.ERR_ALIGN
     assert call(ydt=2) == tdq.ERR_DTYPE
+    qb = L.tdq_quantize_act_blocks_f6
+    pb = tdq.block_params()
+    assert qb(None, 0, 1, 8, 64, 64, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_NULL
+    assert qb(FAKE, 0, 1, 8, 64, 64, C.byref(pb), FAKE, None, None, 2, None) == tdq.ERR_NULL
+    assert qb(FAKE, 0, 1, 8, 64, 64, C.byref(pb), FAKE, FAKE, None, 1, None) == tdq.ERR_SHAPE   # two blocks
+    assert qb(FAKE, 0, 1, 8, 64, 64, C.byref(pb), FAKE + 8, FAKE, None, 2, None) == tdq.ERR_ALIGN
+    assert qb(FAKE, 5, 1, 8, 64, 64, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_DTYPE
+    assert qb(FAKE, 0, 1, 8, 64, 64, C.byref(p), FAKE, FAKE, None, 2, None) == tdq.ERR_UNSUPPORTED   # chan_group 0: the token-set path
     gb = L.tdq_w4a4_linear_blocks_f6
     okb = dict(Qx=FAKE, ds=FAKE, ld_s=2, M=8, K=64, N=8, Qw=FAKE, ws=FAKE, bias=None, Y=FAKE, ydt=1, ld_y=8)
 

@@ -266,3 +266,57 @@ def test_f6_block_scaled_linear_many_tiles(M, K, N, with_bias, out_dtype):
         tol = tol * 1.001 + 2.0 ** -11 * 1.001 * np.abs(Yref) + 2.0 ** -24
     got = Y6[torch.from_numpy(rows).to(U.dev())].cpu().numpy().astype(np.float64)
     assert (np.abs(got - Yref) <= tol).all()
+
+
+@pytest.mark.parametrize("B,T,C,dtype,ld_pad,variant", [
+    (1, 77, 80, np.float16, 0, (3, 1.0, 0.2, 0.0)),      # last block half padding, one K tile
+    (1, 1000, 33, np.float16, 0, (3, 1.0, 0.2, 0.0)),    # odd C
+    (1, 5, 7, np.float16, 0, (3, 1.0, 0.2, 0.0)),
+    (3, 50, 4100, np.float16, 0, (3, 1.0, 0.2, 0.0)),    # scalar loads, many K tiles, ragged last
+    (2, 64, 1024, np.float16, 8, (3, 1.0, 0.2, 0.0)),    # whole tiles
+    (2, 33, 96, np.float16, 3, (2, 1.0, 0.6, 0.0)),      # unaligned rows, bisection rank
+    (1, 200, 96, np.float32, 0, (3, 2.0, 0.1, 0.0)),
+    (2, 64, 1000, np.float32, 0, (0, 1.0, 0.2, 0.9)),    # percentile base radius
+    (1, 31, 45, np.float32, 5, (1, 0.3, 0.2, 0.0)),
+    (1, 300, 544, np.float16, 0, (3, 1.0, 0.2, 0.5)),    # 17 blocks: second K tile holds one
+])
+def test_block_quantizer_f6_equals_the_nibble_one(B, T, C, dtype, ld_pad, variant):
+    """tdq_quantize_act_blocks_f6: steps and radii bit for bit those of
+    tdq_quantize_act_blocks (checked against the oracle in test_gpu_blocks.py), and the
+    fragments are its codes in the storage format written out above, padding zero."""
+    flags, tau, zr, base_pct = variant
+    _say(f"[f6-blockquant] B={B} T={T} C={C} dtype={dtype.__name__} ld_pad={ld_pad} variant={variant}")
+    rng = np.random.Generator(np.random.PCG64([B, T, C, 9]))
+    X = rng.standard_normal((B, T, C)) * np.exp(rng.normal(0, 1.5, (B, T, 1)))
+    X[rng.random((B, T, C)) < 0.02] *= 30.0
+    X = X.astype(dtype)
+    p = tdq.block_params(tau, zr, flags, base_pct)
+    Xd = U.to_device(X, ld_pad)
+    Q, bs, bc = tdq.tdq_quantize_act_blocks(Xd, p, want_clip=True)
+    F = torch.full((tdq.f6_bytes(B * T, C),), 0xA5, dtype=torch.uint8, device=U.dev())   # all must be written
+    bs6 = torch.full_like(bs, float("nan"))
+    F, bs6, bc6 = tdq.tdq_quantize_act_blocks_f6(Xd, p, want_clip=True, out=(F, bs6))
+    torch.cuda.synchronize()
+    assert torch.equal(bs6, bs) and torch.equal(bc6, bc)
+    codes = U.unpack_device_codes(Q, C)
+    assert np.array_equal(F.cpu().numpy(), f6_fragments(codes))
+
+
+def test_blocks_f6_path_end_to_end():
+    """Activations -> tdq_quantize_act_blocks_f6 -> tdq_w4a4_linear_blocks_f6: the bits of
+    the nibble route (tdq_quantize_act_blocks -> tdq_w4a4_linear_blocks)."""
+    lc = I.case("cfg2_fc2", B=2)
+    X, _ = I.make_activations(lc)
+    X = np.ascontiguousarray(X[:, :300])
+    W = I.make_weight(lc)
+    _say(f"[f6-blocks-e2e] {lc.name} X={X.shape} W={W.shape}")
+    p = tdq.block_params()
+    Xd = U.to_device(X)
+    Wd = torch.from_numpy(W).to(U.dev())
+    Qw, sw = tdq.tdq_quantize_weight(Wd)
+    Q, bs, _ = tdq.tdq_quantize_act_blocks(Xd, p)
+    Y8 = tdq.tdq_w4a4_linear_blocks(Q, bs, lc.C, Qw, sw)
+    F, bs6, _ = tdq.tdq_quantize_act_blocks_f6(Xd, p)
+    Y6 = tdq.tdq_w4a4_linear_blocks_f6(F, bs6, lc.C, tdq.tdq_pack_codes_f6(Qw, lc.C), lc.N, sw)
+    torch.cuda.synchronize()
+    assert torch.equal(Y6, Y8)
