@@ -357,3 +357,12 @@ def test_blocks_path_full_size_sampled():
     Yref = O.blocks_linear(q_gpu, sg, G_BLK, qw, sw, None)
     tol = _blocks_linear_bound(q_gpu, sg, qw, sw, None, KB)
     assert (np.abs(Y[rd].cpu().numpy().astype(np.float64) - Yref) <= tol).all()
+    # the same launch shapes on the 6-bit format: the whole of its operand and of its output
+    # against the nibble route just checked
+    _say("[blocks full size] the 6-bit route")
+    F, bs6, bc6 = tdq.tdq_quantize_act_blocks_f6(Xd, p, want_clip=True)
+    assert torch.equal(bs6, bs) and torch.equal(bc6, bc)
+    assert torch.equal(F, tdq.tdq_pack_codes_f6(Q, C))
+    Y6 = tdq.tdq_w4a4_linear_blocks_f6(F, bs6, C, tdq.tdq_pack_codes_f6(Qw_d, C), N, ws_d)
+    torch.cuda.synchronize()
+    assert torch.equal(Y6, Y)
