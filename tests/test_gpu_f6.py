@@ -320,3 +320,33 @@ def test_blocks_f6_path_end_to_end():
     Y6 = tdq.tdq_w4a4_linear_blocks_f6(F, bs6, lc.C, tdq.tdq_pack_codes_f6(Qw, lc.C), lc.N, sw)
     torch.cuda.synchronize()
     assert torch.equal(Y6, Y8)
+
+
+@pytest.mark.parametrize("out_dtype,ld_y_pad,ld_s_pad", [
+    (torch.float32, 5, 3), (torch.float16, 3, 1), (torch.float32, 4, 0), (torch.float16, 8, 2)])
+def test_f6_block_scaled_linear_strided_outputs_and_steps(out_dtype, ld_y_pad, ld_s_pad):
+    """Rows of Y and of the steps longer than their data (views of wider buffers): rows of
+    Y that do not start on 16-byte boundaries take the element-wise stores; the padding
+    is left alone."""
+    M, K, N = 300, 200, 260
+    _say(f"[f6-blocks-strided] out={out_dtype} ld_y_pad={ld_y_pad} ld_s_pad={ld_s_pad}")
+    rng = np.random.Generator(np.random.PCG64([ld_y_pad, ld_s_pad, 11]))
+    KB = -(-K // 32)
+    codes = I.random_codes((M, K), 74)
+    qw = I.random_codes((N, K), 75)
+    bscale = np.exp(rng.normal(-3.0, 1.0, (M, KB))).astype(np.float32)
+    bias = rng.normal(0, 0.02, N).astype(np.float32)
+    wide = torch.full((M, KB + ld_s_pad), float("nan"), dtype=torch.float32, device=U.dev())
+    wide[:, :KB] = torch.from_numpy(bscale).to(U.dev())
+    bs_d = wide[:, :KB]
+    ws_d = torch.from_numpy(WS[:N]).to(U.dev())
+    bias_d = torch.from_numpy(bias).to(U.dev())
+    A6 = tdq.tdq_pack_codes_f6(U.pack_to_device(codes), K)
+    B6 = tdq.tdq_pack_codes_f6(U.pack_to_device(qw), K)
+    Ybuf = torch.full((M, N + ld_y_pad), -77.0, dtype=out_dtype, device=U.dev())
+    Y6 = tdq.tdq_w4a4_linear_blocks_f6(A6, bs_d, K, B6, N, ws_d, bias_d, out=Ybuf[:, :N])
+    Y8 = tdq.tdq_w4a4_linear_blocks(U.pack_to_device(codes), bs_d.contiguous(), K, U.pack_to_device(qw),
+                                    ws_d, bias_d, out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(Y6, Y8)
+    assert bool((Ybuf[:, N:] == -77.0).all())
