@@ -350,3 +350,30 @@ def test_f6_block_scaled_linear_strided_outputs_and_steps(out_dtype, ld_y_pad, l
     torch.cuda.synchronize()
     assert torch.equal(Y6, Y8)
     assert bool((Ybuf[:, N:] == -77.0).all())
+
+
+def test_block_scaled_linears_at_the_largest_k():
+    """K = 131072, the largest the block-scaled entry points accept (4096 blocks, 1024
+    stages of the 6-bit kernel): both routes against the oracle, and equal to each other."""
+    M, K, N = 40, 131072, 24
+    _say(f"[blocks-max-K] M={M} K={K} N={N}")
+    rng = np.random.Generator(np.random.PCG64([M, K, N, 13]))
+    KB = K // 32
+    codes = I.random_codes((M, K), 76)
+    qw = I.random_codes((N, K), 77)
+    bscale = np.exp(rng.normal(-3.0, 1.0, (M, KB))).astype(np.float32)
+    bs_d = torch.from_numpy(bscale).to(U.dev())
+    ws_d = torch.from_numpy(WS[:N]).to(U.dev())
+    Qx, Qw = U.pack_to_device(codes), U.pack_to_device(qw)
+    Y8 = tdq.tdq_w4a4_linear_blocks(Qx, bs_d, K, Qw, ws_d)
+    Y6 = tdq.tdq_w4a4_linear_blocks_f6(tdq.tdq_pack_codes_f6(Qx, K), bs_d, K, tdq.tdq_pack_codes_f6(Qw, K),
+                                       N, ws_d)
+    torch.cuda.synchronize()
+    assert torch.equal(Y6, Y8)
+    Yref = O.blocks_linear(codes, bscale, 32, qw, WS[:N], None)
+    tol = _blocks_linear_bound(codes, bscale, qw, WS[:N], None, KB)
+    assert (np.abs(Y6.cpu().numpy().astype(np.float64) - Yref) <= tol).all()
+    # one more code than the limit is refused
+    L = tdq.lib()
+    assert L.tdq_w4a4_linear_blocks_f6(Qx.data_ptr(), bs_d.data_ptr(), KB + 1, M, K + 1, N, Qw.data_ptr(),
+                                       ws_d.data_ptr(), None, Y6.data_ptr(), tdq.TDQ_F32, N, None) == tdq.ERR_SHAPE
