@@ -321,6 +321,13 @@ int tdq_quantize_act_blocks_f6(const void* X, tdq_dtype dt, int32_t B, int32_t T
                                int64_t ld_x, const tdq_params* p, uint8_t* Qx6, float* block_scale,
                                float* block_clip, int64_t ld_s, void* stream);
 
+/* tdq_quantize_act_blocks_chw writing f6 fragments: X as there, the outputs as from
+ * tdq_quantize_act_blocks_f6 on the tokenized map, bit for bit. */
+int tdq_quantize_act_blocks_chw_f6(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
+                                   int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx6,
+                                   float* block_scale, float* block_clip, int64_t ld_s,
+                                   void* stream);
+
 /*
  * tdq_w4a4_linear_blocks on f6-fragment operands: same definition, same bits of Y.  The
  * 6-bit instruction delivers each block's sum as a float, so the per-block rescale costs

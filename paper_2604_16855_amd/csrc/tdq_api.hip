@@ -426,7 +426,34 @@ int tdq_quantize_act_blocks_chw(const void* X, tdq_dtype dt, int32_t B, int32_t 
   const int kq = block_rank(p->zr);
   const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? block_rank(p->base_pct) : TDQ_BLOCK;
   if (launch_quantize_blocks_chw(X, dt, B, C, T, ld_c, ld_b, kq, kp, make_scalars(p), Qx, ld_q,
-                                 block_scale, block_clip, ld_s,
+                                 block_scale, block_clip, ld_s, false,
+                                 static_cast<hipStream_t>(stream)) != hipSuccess)
+    return TDQ_ERR_HIP;
+  return TDQ_OK;
+}
+
+int tdq_quantize_act_blocks_chw_f6(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
+                                   int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx6,
+                                   float* block_scale, float* block_clip, int64_t ld_s,
+                                   void* stream) {
+  if (!X || !p || !Qx6 || !block_scale) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p, true);
+  if (rc != TDQ_OK) return rc;
+  if (B < 1 || T < 1 || C < 1 || B > 65535) return TDQ_ERR_SHAPE;
+  if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
+  if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T) return TDQ_ERR_SHAPE;
+  const int64_t KB = ((int64_t)C + TDQ_BLOCK - 1) / TDQ_BLOCK;
+  if (ld_s < KB) return TDQ_ERR_SHAPE;
+  const size_t esz = dt == TDQ_F16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(Qx6) & 15) return TDQ_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(block_scale) | reinterpret_cast<uintptr_t>(block_clip)) & 3)
+    return TDQ_ERR_ALIGN;
+  const int kq = block_rank(p->zr);
+  const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? block_rank(p->base_pct) : TDQ_BLOCK;
+  if (launch_quantize_blocks_chw(X, dt, B, C, T, ld_c, ld_b, kq, kp, make_scalars(p), Qx6, 0,
+                                 block_scale, block_clip, ld_s, true,
                                  static_cast<hipStream_t>(stream)) != hipSuccess)
     return TDQ_ERR_HIP;
   return TDQ_OK;

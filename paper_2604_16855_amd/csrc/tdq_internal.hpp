@@ -148,7 +148,7 @@ hipError_t launch_quantize_blocks_f6(const void* X, tdq_dtype dt, long long M, i
 hipError_t launch_quantize_blocks_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                       long long ld_b, int kq, int kp, const Scalars& sc, uint8_t* Q,
                                       long long ld_q, float* bscale, float* bclip, long long ld_s,
-                                      hipStream_t st);
+                                      bool f6, hipStream_t st);
 hipError_t launch_fused_small(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                               const Scalars& sc, float* r, double* s1, double* s2, int* gid,
                               float* clip, float* scale, tdq_group_stats* stats,
