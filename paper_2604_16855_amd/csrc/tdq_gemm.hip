@@ -1183,44 +1183,69 @@ hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const floa
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int F6_FRAG = 1536;            // bytes of one (32 rows, 64 codes) block
-// bf6 patterns of the codes 0..7 and -8..-1 (index = two's-complement nibble)
-__device__ __constant__ unsigned char kBf6OfNibble[16] = {0x00, 0x0C, 0x10, 0x12, 0x14, 0x15, 0x16, 0x17,
-                                                          0x38, 0x37, 0x36, 0x35, 0x34, 0x32, 0x30, 0x2C};
 
-// Packed nibbles [R, ld] -> f6 fragments.  One thread per (block, lane): 16 bytes in, 24 out.
+// Packed nibbles [R, ld] -> f6 fragments.  One wavefront per fragment (32 rows x 64 codes),
+// the four wavefronts of a workgroup on four consecutive fragments of the same rows, so
+// that together they read whole 128-byte lines.  Lane l loads the 16 bytes of (row l / 2,
+// half l % 2), the lane that owns (row, half) in the fragment's order fetches them with a
+// lane permute, sign-extends the 32 nibbles, and one conversion instruction (even codes
+// in its first operand, odd ones in its second) packs them.  Codes at and beyond K, rows
+// at and beyond R are zero.
+typedef int v6i_pack __attribute__((ext_vector_type(6)));
 __global__ __launch_bounds__(256) void k_pack_f6(const uint8_t* __restrict__ Q, long long ld, int R,
-                                                 int K, int KB, long long n_threads,
+                                                 int K, int KB, long long n_blocks, int vec_ok,
                                                  uint8_t* __restrict__ F) {
-  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (t >= n_threads) return;
-  const int l = (int)(t & 63);
-  const long long blk = t >> 6;
+  const int l = threadIdx.x & 63;
+  const long long blk = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blk >= n_blocks) return;                             // whole wavefronts only
   const int kb = (int)(blk % KB);
   const long long rb = blk / KB;
-  const long long row = rb * 32 + (l & 31);
-  const int k0 = kb * 64 + 32 * (l >> 5);
-  u32 w[6] = {0, 0, 0, 0, 0, 0};
-  if (row < R) {
+  const long long row = rb * 32 + (l >> 1);
+  const int k0 = kb * 64 + 32 * (l & 1);
+  u32 n[4] = {0u, 0u, 0u, 0u};
+  if (row < R && k0 < K) {
     const uint8_t* src = Q + row * ld + k0 / 2;
-    for (int j = 0; j < 32 && k0 + j < K; ++j) {
-      const u32 nib = (src[j >> 1] >> (4 * (j & 1))) & 0xFu;
-      const u32 e = kBf6OfNibble[nib];
-      const int bit = 6 * j;
-      w[bit >> 5] |= e << (bit & 31);
-      if ((bit & 31) > 26) w[(bit >> 5) + 1] |= e >> (32 - (bit & 31));
+    const int live = K - k0;                               // codes of this piece that exist
+    const int nb = live >= 32 ? 16 : (live + 1) / 2;       // bytes that hold them
+    if (vec_ok && nb == 16) {
+      const uint4 q = *reinterpret_cast<const uint4*>(src);
+      n[0] = q.x; n[1] = q.y; n[2] = q.z; n[3] = q.w;
+    } else {
+      for (int j = 0; j < nb; ++j) n[j >> 2] |= (u32)src[j] << (8 * (j & 3));
+    }
+    if (live < 32) {                                       // the pad nibble of an odd K is not a code
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int keep = live - 8 * w;
+        n[w] &= keep >= 8 ? 0xFFFFFFFFu : (keep <= 0 ? 0u : (1u << (4 * keep)) - 1u);
+      }
     }
   }
-  uint2* dst = reinterpret_cast<uint2*>(F + t * 24);
-  dst[0] = make_uint2(w[0], w[1]);
-  dst[1] = make_uint2(w[2], w[3]);
-  dst[2] = make_uint2(w[4], w[5]);
+  const int from = (2 * (l & 31) + (l >> 5)) * 4;          // the lane that loaded this lane's piece
+  u32 m[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) m[w] = (u32)__builtin_amdgcn_ds_bpermute(from, (int)n[w]);
+  v16f ev, od;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const u32 wd = m[i >> 2];
+    const int sh = 8 * (i & 3);                            // codes 2 i and 2 i + 1: bits sh, sh + 4
+    ev[i] = (float)((int)(wd << (28 - sh)) >> 28);
+    od[i] = (float)((int)(wd << (24 - sh)) >> 28);
+  }
+  const v6i_pack r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(ev, od, 1.0f);
+  uint2* dst = reinterpret_cast<uint2*>(F + (blk * 64 + l) * 24);
+  dst[0] = make_uint2((u32)r[0], (u32)r[1]);
+  dst[1] = make_uint2((u32)r[2], (u32)r[3]);
+  dst[2] = make_uint2((u32)r[4], (u32)r[5]);
 }
 
 hipError_t launch_pack_f6(const uint8_t* Q, long long ld, int R, int K, uint8_t* F, hipStream_t st) {
   const int KB = 2 * ((K + 127) / 128);
-  const long long n_threads = (long long)((R + 31) / 32) * KB * 64;
-  hipLaunchKernelGGL(k_pack_f6, dim3((unsigned)((n_threads + 255) / 256)), dim3(256), 0, st, Q, ld, R,
-                     K, KB, n_threads, F);
+  const long long n_blocks = (long long)((R + 31) / 32) * KB;
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(Q) & 15) == 0 && ld % 16 == 0) ? 1 : 0;
+  hipLaunchKernelGGL(k_pack_f6, dim3((unsigned)((n_blocks + 3) / 4)), dim3(256), 0, st, Q, ld, R, K, KB,
+                     n_blocks, vec_ok, F);
   return hipGetLastError();
 }
 

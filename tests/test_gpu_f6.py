@@ -66,6 +66,24 @@ def test_pack_codes_f6_matches_the_format(R, K):
     assert np.array_equal(F.cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("R,K,ld_pad,off", [(70, 200, 5, 0), (33, 129, 0, 3), (64, 256, 16, 0), (40, 63, 1, 1)])
+def test_pack_codes_f6_unaligned_rows_and_junk_pad_nibble(R, K, ld_pad, off):
+    """Rows that do not start on 16-byte boundaries (a view into a wider buffer) take the
+    byte loads; whatever stands in the unused high nibble of an odd row's last byte and in
+    the bytes behind a row is not read as codes."""
+    codes = I.random_codes((R, K), 90 + R)
+    packed = O.pack_nibbles(codes)                                   # [R, ceil(K / 2)]
+    nb = packed.shape[1]
+    wide = np.full((R, off + nb + ld_pad), 0xEE, dtype=np.uint8)
+    wide[:, off:off + nb] = packed
+    if K % 2:
+        wide[:, off + nb - 1] |= 0xF0                               # junk in the pad nibble
+    Qd = torch.from_numpy(wide).to(U.dev())[:, off:off + nb]
+    F = tdq.tdq_pack_codes_f6(Qd, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(F.cpu().numpy(), f6_fragments(codes))
+
+
 def _f6_linear(codes, qw, gid, scale, B, T, bias=None, out_dtype=torch.float32):
     M, K = codes.shape
     N = qw.shape[0]
