@@ -28,7 +28,7 @@ PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
 PEAK_VALU_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # HBM bytes per launch of the fc1 contraction on the default workload, from the
 # FETCH_SIZE + WRITE_SIZE counters (see profiles/bench_cfg4_hbm_traffic_pmc.txt)
-GEMM_FC1_TRAFFIC_BYTES = 1181485156
+GEMM_FC1_TRAFFIC_BYTES = 1182249898
 
 
 def parse():
