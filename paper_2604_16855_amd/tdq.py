@@ -557,3 +557,11 @@ def tdq_w4a4_linear(Qx: torch.Tensor, gid: Optional[torch.Tensor], scale: torch.
                                out.data_ptr(), _dt(out), out.stride(0), _ptr(acc_dump), _stream())
     _check(rc, "tdq_w4a4_linear")
     return out
+
+
+# the helper entry points under their C names as well
+tdq_version = version
+tdq_status_string = status_string
+tdq_default_params = default_params
+tdq_workspace_bytes = workspace_bytes
+tdq_f6_bytes = f6_bytes

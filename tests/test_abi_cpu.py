@@ -36,6 +36,11 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(L, n), n
 
 
+def test_every_declared_entry_point_has_a_binding_of_the_same_name():
+    for n in _declared():
+        assert callable(getattr(tdq, n, None)), n
+
+
 def test_version_and_strings():
     assert tdq.version() == 100
     assert tdq.status_string(0) == "ok"
