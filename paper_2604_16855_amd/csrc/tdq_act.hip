@@ -13,81 +13,120 @@ namespace tdq {
 // ---------------------------------------------------------------------------
 // K_a: per-token range and moments (one sweep of X)
 //   r_t = max_c |x|  (exact: integer max of the magnitude bit patterns)
-//   s1_t = sum x, s2_t = sum x^2 in binary64.  For fp16 input each lane first adds
-//   its 8 values / 8 squares (a square of an fp16 value is exact in binary32) in
-//   binary32 and then accumulates in binary64.
+//   (mean_t, M2_t) with M2_t = sum_c (x - mean_t)^2, summed about a pivot P taken from
+//   the row (see "Moments" in tdq_device.hpp).  binary16 input: a lane adds the 8
+//   differences x - P of a 16-byte load and their squares in binary32, then accumulates
+//   in binary64; binary32 input: binary64 throughout.
 // ---------------------------------------------------------------------------
-template <typename T, int L>
-__global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, long long ld, int M,
-                                                     int C, int vec_ok, float* __restrict__ r,
-                                                     double* __restrict__ s1,
-                                                     double* __restrict__ s2) {
+template <typename T>
+struct PivotOf { typedef double type; };
+template <>
+struct PivotOf<u16> { typedef float type; };
+
+// The part of a row that one of NL cooperating lanes (index lr) sees: 16-byte pieces
+// lr, lr + NL, ... and, past the last whole piece, single elements.
+template <typename T, int NL>
+__device__ __forceinline__ void row_partial(const T* __restrict__ xp, int lr, int nvec, int C,
+                                            typename PivotOf<T>::type P, u32& kmax, double& a1,
+                                            double& a2) {
   constexpr int V = Elem<T>::V;
-  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long row = gt / L;
-  const int lr = (int)(gt % L);
-  const bool valid = row < M;
-  const T* xp = X + (valid ? row : (long long)(M - 1)) * ld;
-  u32 kmax = 0;
-  double a1 = 0.0, a2 = 0.0;
-  const int nvec = vec_ok ? C / V : 0;
-  us2 kpk = {0, 0};                       // fp16: running max of the magnitude keys, two at a time
-  float one = 1.0f;                       // opaque to the optimizer, so x * one + p stays ONE mixed fma
-  asm volatile("" : "+v"(one));
+  kmax = 0;
+  a1 = 0.0;
+  a2 = 0.0;
+  if constexpr (sizeof(T) == 2) {
+    us2 kpk = {0, 0};                     // running max of the magnitude keys, two at a time
+    float one = 1.0f;                     // opaque to the optimizer, so x * one - P stays ONE mixed fma
+    asm volatile("" : "+v"(one));
+    const float nP = -P;
 #pragma unroll 4
-  for (int v = lr; v < nvec; v += L) {
-    const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
-    if constexpr (sizeof(T) == 2) {
-      // Per element one mixed-precision fma for the sum (x * 1 + p, the fp16 -> fp32
-      // conversion rides in the instruction) and one for the sum of squares (x * x is
-      // exact in binary32, so the fused form rounds exactly like multiply-then-add);
-      // the keys of a pair of elements are maxed with one packed 16-bit instruction.
+    for (int v = lr; v < nvec; v += NL) {
+      const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
+      // Per element: d = x - P as one mixed-precision fma (the fp16 -> fp32 conversion rides
+      // in the instruction), one add for the sum and one fma for the sum of squares; the
+      // keys of a pair of elements are maxed with one packed 16-bit instruction.
       const u32 w[4] = {q.x, q.y, q.z, q.w};
       float p1 = 0.f, p2 = 0.f;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const h2 h = __builtin_bit_cast(h2, w[j]);
         kpk = __builtin_elementwise_max(kpk, __builtin_bit_cast(us2, w[j] & 0x7FFF7FFFu));
-        const float f0 = (float)h[0], f1 = (float)h[1];
-        p1 = __builtin_fmaf(f0, one, p1);
-        p2 = __builtin_fmaf(f0, f0, p2);
-        p1 = __builtin_fmaf(f1, one, p1);
-        p2 = __builtin_fmaf(f1, f1, p2);
+        const float d0 = __builtin_fmaf((float)h[0], one, nP);
+        const float d1 = __builtin_fmaf((float)h[1], one, nP);
+        p1 += d0;
+        p2 = __builtin_fmaf(d0, d0, p2);
+        p1 += d1;
+        p2 = __builtin_fmaf(d1, d1, p2);
       }
       a1 += (double)p1;
       a2 += (double)p2;
-    } else {
+    }
+    const u32 kp = kpk[0] > kpk[1] ? kpk[0] : kpk[1];
+    kmax = kp;
+  } else {
+#pragma unroll 4
+    for (int v = lr; v < nvec; v += NL) {
+      const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
       T e[V];
       Elem<T>::unpack(q, e);
 #pragma unroll
       for (int i = 0; i < V; ++i) {
-        const double f = (double)Elem<T>::val(e[i]);
+        const double d = (double)Elem<T>::val(e[i]) - (double)P;
         const u32 k = Elem<T>::key(e[i]);
         kmax = k > kmax ? k : kmax;
-        a1 += f;
-        a2 += f * f;
+        a1 += d;
+        a2 = fma(d, d, a2);
       }
     }
   }
-  for (int c = nvec * V + lr; c < C; c += L) {   // ragged tail / unaligned rows
+  for (int c = nvec * V + lr; c < C; c += NL) {   // ragged tail / unaligned rows
     const T x = xp[c];
-    const double f = (double)Elem<T>::val(x);
+    const double d = (double)Elem<T>::val(x) - (double)P;
     const u32 k = Elem<T>::key(x);
     kmax = k > kmax ? k : kmax;
-    a1 += f;
-    a2 += f * f;
+    a1 += d;
+    a2 = fma(d, d, a2);
   }
-  if constexpr (sizeof(T) == 2) {
-    const u32 kp = kpk[0] > kpk[1] ? kpk[0] : kpk[1];
-    kmax = kp > kmax ? kp : kmax;
-  }
+}
+
+template <typename T, int L>
+__global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, long long ld, int M,
+                                                     int C, int vec_ok, float* __restrict__ r,
+                                                     double* __restrict__ mean,
+                                                     double* __restrict__ m2) {
+  constexpr int V = Elem<T>::V;
+  typedef typename PivotOf<T>::type PT;
+  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long row = gt / L;
+  const int lr = (int)(gt % L);
+  const bool valid = row < M;
+  const T* xp = X + (valid ? row : (long long)(M - 1)) * ld;
+  const int nvec = vec_ok ? C / V : 0;
+  PT P = row_pivot(xp, C, nvec > 0);
+  u32 kmax;
+  double a1, a2;
+  row_partial<T, L>(xp, lr, nvec, C, P, kmax, a1, a2);
   kmax = group_max_u32<L>(kmax);
-  a1 = group_sum_f64<L>(a1);
+  a1 = group_sum_f64<L>(a1);                       // totals in the row's last lane
   a2 = group_sum_f64<L>(a2);
+  if constexpr (sizeof(T) == 2) {
+    // A pivot far from the row's mean: all rows of this wavefront are summed again, each
+    // about its own mean (uniform branch; the data comes from the cache).
+    const bool far = lr == L - 1 && pivot_is_far(a1, a2, C);
+    if (__ballot(far)) {
+      const float pn = P + (float)(a1 / (double)C);
+      P = __shfl(pn, (int)(threadIdx.x & 63) | (L - 1), 64);
+      u32 k2;
+      row_partial<T, L>(xp, lr, nvec, C, P, k2, a1, a2);
+      a1 = group_sum_f64<L>(a1);
+      a2 = group_sum_f64<L>(a2);
+    }
+  }
   if (lr == L - 1 && valid) {
+    double mu, q;
+    pivot_to_central((double)P, a1, a2, C, mu, q);
     r[row] = Elem<T>::key_to_float(kmax);
-    s1[row] = a1;
-    s2[row] = a2;
+    mean[row] = mu;
+    m2[row] = q;
   }
 }
 
@@ -98,89 +137,60 @@ __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, lo
 template <typename T>
 __global__ __launch_bounds__(256) void k_token_stats_wide(const T* __restrict__ X, long long ld, int M,
                                                           int C, float* __restrict__ r,
-                                                          double* __restrict__ s1,
-                                                          double* __restrict__ s2) {
+                                                          double* __restrict__ mean,
+                                                          double* __restrict__ m2) {
   constexpr int V = Elem<T>::V;
-  __shared__ double sh1[4], sh2[4];
+  typedef typename PivotOf<T>::type PT;
+  __shared__ double sh1[2][4], sh2[2][4];
   __shared__ u32 shk[4];
   const long long row = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* xp = X + row * ld;
-  u32 kmax = 0;
-  double a1 = 0.0, a2 = 0.0;
   const int nvec = C / V;
-  us2 kpk = {0, 0};
-  float one = 1.0f;
-  asm volatile("" : "+v"(one));
-#pragma unroll 4
-  for (int v = tid; v < nvec; v += 256) {
-    const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
-    if constexpr (sizeof(T) == 2) {
-      const u32 w[4] = {q.x, q.y, q.z, q.w};
-      float p1 = 0.f, p2 = 0.f;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const h2 h = __builtin_bit_cast(h2, w[j]);
-        kpk = __builtin_elementwise_max(kpk, __builtin_bit_cast(us2, w[j] & 0x7FFF7FFFu));
-        const float f0 = (float)h[0], f1 = (float)h[1];
-        p1 = __builtin_fmaf(f0, one, p1);
-        p2 = __builtin_fmaf(f0, f0, p2);
-        p1 = __builtin_fmaf(f1, one, p1);
-        p2 = __builtin_fmaf(f1, f1, p2);
-      }
-      a1 += (double)p1;
-      a2 += (double)p2;
-    } else {
-      T e[V];
-      Elem<T>::unpack(q, e);
-#pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const double f = (double)Elem<T>::val(e[i]);
-        const u32 k = Elem<T>::key(e[i]);
-        kmax = k > kmax ? k : kmax;
-        a1 += f;
-        a2 += f * f;
-      }
-    }
-  }
-  for (int c = nvec * V + tid; c < C; c += 256) {
-    const T x = xp[c];
-    const double f = (double)Elem<T>::val(x);
-    const u32 k = Elem<T>::key(x);
-    kmax = k > kmax ? k : kmax;
-    a1 += f;
-    a2 += f * f;
-  }
-  if constexpr (sizeof(T) == 2) {
-    const u32 kp = kpk[0] > kpk[1] ? kpk[0] : kpk[1];
-    kmax = kp > kmax ? kp : kmax;
-  }
+  PT P = row_pivot(xp, C, true);
+  u32 kmax;
+  double a1, a2;
+  row_partial<T, 256>(xp, tid, nvec, C, P, kmax, a1, a2);
   kmax = group_max_u32<64>(kmax);
   a1 = group_sum_f64<64>(a1);
   a2 = group_sum_f64<64>(a2);
-  if (lane == 63) { shk[wave] = kmax; sh1[wave] = a1; sh2[wave] = a2; }
+  if (lane == 63) { shk[wave] = kmax; sh1[0][wave] = a1; sh2[0][wave] = a2; }
   __syncthreads();
+  // every thread adds the four totals in the same order: the same bits everywhere
+  double t1 = sh1[0][0], t2 = sh2[0][0];
+  for (int w = 1; w < 4; ++w) { t1 += sh1[0][w]; t2 += sh2[0][w]; }
+  if constexpr (sizeof(T) == 2) {
+    if (pivot_is_far(t1, t2, C)) {                 // uniform over the workgroup
+      P = P + (float)(t1 / (double)C);
+      u32 k2;
+      row_partial<T, 256>(xp, tid, nvec, C, P, k2, a1, a2);
+      a1 = group_sum_f64<64>(a1);
+      a2 = group_sum_f64<64>(a2);
+      if (lane == 63) { sh1[1][wave] = a1; sh2[1][wave] = a2; }
+      __syncthreads();
+      t1 = sh1[1][0];
+      t2 = sh2[1][0];
+      for (int w = 1; w < 4; ++w) { t1 += sh1[1][w]; t2 += sh2[1][w]; }
+    }
+  }
   if (tid == 0) {
     u32 k = shk[0];
-    double t1 = sh1[0], t2 = sh2[0];
-    for (int w = 1; w < 4; ++w) {
-      k = shk[w] > k ? shk[w] : k;
-      t1 += sh1[w];
-      t2 += sh2[w];
-    }
+    for (int w = 1; w < 4; ++w) k = shk[w] > k ? shk[w] : k;
+    double mu, q;
+    pivot_to_central((double)P, t1, t2, C, mu, q);
     r[row] = Elem<T>::key_to_float(k);
-    s1[row] = t1;
-    s2[row] = t2;
+    mean[row] = mu;
+    m2[row] = q;
   }
 }
 
 template <typename T>
-static hipError_t token_stats_t(const T* X, int M, int C, long long ld, float* r, double* s1,
-                                double* s2, hipStream_t st) {
+static hipError_t token_stats_t(const T* X, int M, int C, long long ld, float* r, double* mean,
+                                double* m2, hipStream_t st) {
   constexpr int V = Elem<T>::V;
   const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % V == 0) ? 1 : 0;
   if (vec_ok && C / V >= 256) {
-    hipLaunchKernelGGL((k_token_stats_wide<T>), dim3(M), dim3(256), 0, st, X, ld, M, C, r, s1, s2);
+    hipLaunchKernelGGL((k_token_stats_wide<T>), dim3(M), dim3(256), 0, st, X, ld, M, C, r, mean, m2);
     return hipGetLastError();
   }
   const int L = lanes_per_row(C, V);
@@ -189,7 +199,7 @@ static hipError_t token_stats_t(const T* X, int M, int C, long long ld, float* r
 #define TDQ_TS(LL)                                                                       \
   case LL:                                                                               \
     hipLaunchKernelGGL((k_token_stats<T, LL>), dim3(grid), dim3(256), 0, st, X, ld, M, C, \
-                       vec_ok, r, s1, s2);                                               \
+                       vec_ok, r, mean, m2);                                             \
     break;
   switch (L) {
     TDQ_TS(1) TDQ_TS(2) TDQ_TS(4) TDQ_TS(8) TDQ_TS(16) TDQ_TS(32) TDQ_TS(64)
@@ -199,27 +209,27 @@ static hipError_t token_stats_t(const T* X, int M, int C, long long ld, float* r
 }
 
 hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long long ld, float* r,
-                              double* s1, double* s2, hipStream_t st) {
+                              double* mean, double* m2, hipStream_t st) {
   if (dt == TDQ_F16)
-    return token_stats_t<u16>(static_cast<const u16*>(X), M, C, ld, r, s1, s2, st);
-  return token_stats_t<float>(static_cast<const float*>(X), M, C, ld, r, s1, s2, st);
+    return token_stats_t<u16>(static_cast<const u16*>(X), M, C, ld, r, mean, m2, st);
+  return token_stats_t<float>(static_cast<const float*>(X), M, C, ld, r, mean, m2, st);
 }
 
 // ---------------------------------------------------------------------------
 // K_assign: one workgroup per image.
 //   key_t = bits(r_t); hi = max key; lo = max(min key, hi - 24 octaves);
 //   gid_t = key_t <= lo ? 0 : (key_t - lo) * G / (hi - lo + 1)      (64-bit integers)
-// then per token set: token count, c_base = max r_t, and the merged moments ->
-// sigma = sqrt(S2/n - (S1/n)^2) + eps_std in binary64, rank k = ceil(zr n).
+// then per token set: token count, c_base = max r_t, and the tokens' moments merged about
+// the image's pivot -> sigma = sqrt(S2/n - (S1/n)^2) + eps_std in binary64, rank k = ceil(zr n).
 // Also clears this image's histogram slices and records whether the image holds
 // a non-finite value (its largest range key is Inf/NaN).
 // ---------------------------------------------------------------------------
 constexpr int kAssignThreads = 1024;
 
 __global__ __launch_bounds__(kAssignThreads) void k_assign(
-    const float* __restrict__ r, const double* __restrict__ s1, const double* __restrict__ s2,
-    int T, int G, int* __restrict__ gid, SetAcc* __restrict__ part, u32* __restrict__ img_flag,
-    u32* __restrict__ status) {
+    const float* __restrict__ r, const double* __restrict__ mean, const double* __restrict__ m2,
+    int T, int C, int G, int* __restrict__ gid, SetAcc* __restrict__ part,
+    u32* __restrict__ img_flag, u32* __restrict__ status) {
   extern __shared__ __attribute__((aligned(16))) unsigned char assign_lds[];
   __shared__ u32 s_min[kAssignThreads / 64], s_max[kAssignThreads / 64];
   __shared__ u32 s_lohi[2];
@@ -229,7 +239,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
   const int b = blockIdx.y, sub = blockIdx.x, S = gridDim.x;
   const int tid = threadIdx.x;
   const int NW = blockDim.x >> 6;
-  assign_tokens(r + (long long)b * T, s1 + (long long)b * T, s2 + (long long)b * T, T, G,
+  assign_tokens(r + (long long)b * T, mean + (long long)b * T, m2 + (long long)b * T, T, C, G,
                 gid + (long long)b * T, wacc, s_min, s_max, s_lohi, sub, S);
   if (tid == 0 && sub == 0) {
     img_flag[b] = s_lohi[1] >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
@@ -272,14 +282,14 @@ int assign_split(int T) {
   return s < 1 ? 1 : (s > kAssignSplitMax ? kAssignSplitMax : s);
 }
 
-hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int G,
-                         int* gid, void* part, unsigned* img_flag, unsigned* status,
+hipError_t launch_assign(const float* r, const double* mean, const double* m2, int B, int T, int C,
+                         int G, int* gid, void* part, unsigned* img_flag, unsigned* status,
                          hipStream_t st) {
   int nw = 2048 / G;                       // keep the per-wavefront accumulators under 48 KiB
   nw = nw > kAssignThreads / 64 ? kAssignThreads / 64 : (nw < 1 ? 1 : nw);
   const size_t lds = (size_t)nw * G * sizeof(SetAcc);
-  hipLaunchKernelGGL(k_assign, dim3(assign_split(T), B), dim3(nw * 64), lds, st, r, s1, s2, T, G,
-                     gid, static_cast<SetAcc*>(part), img_flag, status);
+  hipLaunchKernelGGL(k_assign, dim3(assign_split(T), B), dim3(nw * 64), lds, st, r, mean, m2, T, C,
+                     G, gid, static_cast<SetAcc*>(part), img_flag, status);
   return hipGetLastError();
 }
 

@@ -44,8 +44,8 @@ WorkspaceLayout make_layout(int B, int T, int G, const LevelPlan& lp) {
   w.status = off;   off = align256(off + 64 * sizeof(unsigned));
   w.img_flag = off; off = align256(off + (size_t)B * sizeof(unsigned));
   w.r = off;        off = align256(off + M * sizeof(float));
-  w.s1 = off;       off = align256(off + M * sizeof(double));
-  w.s2 = off;       off = align256(off + M * sizeof(double));
+  w.mean = off;     off = align256(off + M * sizeof(double));
+  w.m2 = off;       off = align256(off + M * sizeof(double));
   w.part = off;     off = align256(off + assign_partial_bytes(B, G));
   w.grp = off;      off = align256(off + BG * sizeof(GroupWork));
   w.hist = off;
@@ -114,14 +114,14 @@ static int calibrate_after_stats(const void* X, tdq_dtype dt, int32_t B, int32_t
   unsigned* status = reinterpret_cast<unsigned*>(ws + wl.status);
   unsigned* img_flag = reinterpret_cast<unsigned*>(ws + wl.img_flag);
   float* r = reinterpret_cast<float*>(ws + wl.r);
-  double* s1 = reinterpret_cast<double*>(ws + wl.s1);
-  double* s2 = reinterpret_cast<double*>(ws + wl.s2);
+  double* mean = reinterpret_cast<double*>(ws + wl.mean);
+  double* m2 = reinterpret_cast<double*>(ws + wl.m2);
   GroupWork* grp = reinterpret_cast<GroupWork*>(ws + wl.grp);
   unsigned* hist = reinterpret_cast<unsigned*>(ws + wl.hist);
   const Scalars sc = make_scalars(p);
 
   void* part = ws + wl.part;
-  if (launch_assign(r, s1, s2, B, T, G, group_id, part, img_flag, status, st) != hipSuccess)
+  if (launch_assign(r, mean, m2, B, T, C, G, group_id, part, img_flag, status, st) != hipSuccess)
     return TDQ_ERR_HIP;
 
   // One rank select per rank wanted of every set: first the base radius Q_p(|x|) when a
@@ -234,8 +234,8 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
   if (launch_token_stats(X, dt, B * T, C, ld_x, reinterpret_cast<float*>(ws + wl.r),
-                         reinterpret_cast<double*>(ws + wl.s1),
-                         reinterpret_cast<double*>(ws + wl.s2), st) != hipSuccess)
+                         reinterpret_cast<double*>(ws + wl.mean),
+                         reinterpret_cast<double*>(ws + wl.m2), st) != hipSuccess)
     return TDQ_ERR_HIP;
   return calibrate_after_stats(X, dt, B, T, C, ld_x, p, group_id, clip, scale, stats, workspace, lp,
                                wl, st);
@@ -266,8 +266,8 @@ int tdq_calibrate_groups_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, 
   char* ws = static_cast<char*>(workspace);
   if (launch_tokenize_stats_chw(X, dt, B, C, T, ld_c, ld_b, Xt, ld_xt,
                                 reinterpret_cast<float*>(ws + wl.r),
-                                reinterpret_cast<double*>(ws + wl.s1),
-                                reinterpret_cast<double*>(ws + wl.s2), st) != hipSuccess)
+                                reinterpret_cast<double*>(ws + wl.mean),
+                                reinterpret_cast<double*>(ws + wl.m2), st) != hipSuccess)
     return TDQ_ERR_HIP;
   return calibrate_after_stats(Xt, dt, B, T, C, ld_xt, p, group_id, clip, scale, stats, workspace,
                                lp, wl, st);
@@ -314,8 +314,8 @@ int tdq_calibrate_quantize_fused(const void* X, tdq_dtype dt, int32_t B, int32_t
   if (reinterpret_cast<uintptr_t>(image_flags) & 3) return TDQ_ERR_ALIGN;
   char* ws = static_cast<char*>(workspace);
   if (launch_fused_small(X, dt, B, T, C, ld_x, G, make_scalars(p),
-                         reinterpret_cast<float*>(ws + wl.r), reinterpret_cast<double*>(ws + wl.s1),
-                         reinterpret_cast<double*>(ws + wl.s2), group_id, clip, scale, stats,
+                         reinterpret_cast<float*>(ws + wl.r), reinterpret_cast<double*>(ws + wl.mean),
+                         reinterpret_cast<double*>(ws + wl.m2), group_id, clip, scale, stats,
                          image_flags, Qx, ld_q, static_cast<hipStream_t>(stream)) != hipSuccess)
     return TDQ_ERR_HIP;
   return TDQ_OK;

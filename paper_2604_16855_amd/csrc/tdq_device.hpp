@@ -126,15 +126,67 @@ __device__ __forceinline__ u32 group_sum_u32(u32 v) {
   return v;
 }
 
+// ---------------------------------------------------------------------------
+// Moments.  The dispersion of a set is the population standard deviation of all its
+// elements (Sec. 4.2), and the bar on it is 1e-6 relative whatever the data's offset.
+// A plain sum of squares loses (mean / sigma)^2 units of its last place when it is turned
+// into a variance, so nothing here is summed about zero:
+//   * a token's row is summed about a pivot P taken from the row itself (S1 = sum (x - P),
+//     S2 = sum (x - P)^2) and leaves the sweep as (mean, M2) = (P + S1 / C, S2 - S1^2 / C),
+//     M2 = sum (x - mean)^2;
+//   * the tokens of a set are merged about the mean of the image's first token, P_b:
+//     a token adds C (mean - P_b) and M2 + C (mean - P_b)^2 to the set's two sums.
+// Both conversions are binary64 and lose (distance to the pivot / sigma)^2 units of 2^-53.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void pivot_to_central(double P, double S1, double S2, int C,
+                                                 double& mean, double& m2) {
+  const double n = (double)C;
+  mean = P + S1 / n;
+  const double v = S2 - S1 * S1 / n;
+  m2 = v > 0.0 ? v : 0.0;
+}
+
+// True when a row summed about P should be summed again about its mean: the pivot lies
+// more than sqrt(8) row standard deviations from the mean, so the binary32 partial sums
+// of a binary16 row (3 * 2^-24 relative to sum (x - P)^2 each) could cost the row's M2
+// more than 1e-6.  False for NaN.
+__device__ __forceinline__ bool pivot_is_far(double S1, double S2, int C) {
+  const double n = (double)C;
+  const double off = S1 * S1 / n;            // C (mean - P)^2
+  return off > 8.0 * (S2 - off);
+}
+
+// Pivot of a binary16 row: the median of its first three values (one outlier among
+// them does not become the pivot).  `wide` = the row is 8-byte aligned and C >= 4.
+__device__ __forceinline__ float row_pivot(const u16* __restrict__ xp, int C, bool wide) {
+  u32 w0, w1;
+  if (wide) {
+    const uint2 pw = *reinterpret_cast<const uint2*>(xp);
+    w0 = pw.x;
+    w1 = pw.y;
+  } else {
+    const int i1 = C > 1 ? 1 : 0, i2 = C > 2 ? 2 : i1;
+    w0 = (u32)xp[0] | ((u32)xp[i1] << 16);
+    w1 = xp[i2];
+  }
+  return __builtin_amdgcn_fmed3f(h2f(w0 & 0xFFFFu), h2f(w0 >> 16), h2f(w1 & 0xFFFFu));
+}
+// Pivot of a binary32 row: its first value (the row is summed in binary64, where any
+// value of the row is close enough).
+__device__ __forceinline__ double row_pivot(const float* __restrict__ xp, int, bool) {
+  return (double)xp[0];
+}
+
 // Partial sums of one token set over part of an image's tokens.
 struct SetAcc {
-  double s1, s2;      // sum x, sum x^2
+  double s1, s2;      // sum (x - P_b), sum (x - P_b)^2 with P_b the image's pivot
   u32 cnt, kmax;      // tokens, largest range key
 };
 
 // Merges the S partial records of set j of image b (in index order, so the result is
 // bitwise repeatable) into the set's working record: n, c_base (DSTG base radius,
-// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2), and the rank this pass
+// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2; the records' sums are taken
+// about the image's pivot, which the variance does not depend on), and the rank this pass
 // looks for: k = ceil(zr n), or ceil(p n) in the base-radius pass.
 __device__ inline GroupWork merge_partials(const SetAcc* __restrict__ part, int b, int j, int S,
                                            int G, int C, const Scalars& sc, int pass) {
@@ -186,8 +238,8 @@ __device__ __forceinline__ u32 wave_min_u32(u32 v) {
   return v;
 }
 
-__device__ inline void assign_tokens(const float* __restrict__ rb, const double* __restrict__ s1b,
-                                     const double* __restrict__ s2b, int T, int G,
+__device__ inline void assign_tokens(const float* __restrict__ rb, const double* __restrict__ meanb,
+                                     const double* __restrict__ m2b, int T, int C, int G,
                                      int* __restrict__ gb, SetAcc* wacc, u32* s_min, u32* s_max,
                                      u32* s_lohi, int sub, int S) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -221,6 +273,11 @@ __device__ inline void assign_tokens(const float* __restrict__ rb, const double*
   __syncthreads();
   const u32 lo = s_lohi[0], hi = s_lohi[1];
   const unsigned long long width = (unsigned long long)(hi - lo) + 1ull;
+  // the image's pivot: the mean of its first token (zero if that is not finite, in
+  // which case the image's results are undefined anyway and its flag is raised)
+  double pb = meanb[0];
+  pb = (pb - pb == 0.0) ? pb : 0.0;
+  const double cn = (double)C;
 
   // Wavefront w of workgroup `sub` owns the token batches sub NW + w, + S NW, ... (64
   // tokens each).  Inside a batch the tokens of one set are summed with a fixed tree and
@@ -235,20 +292,21 @@ __device__ inline void assign_tokens(const float* __restrict__ rb, const double*
   if (bt0 < n_batches && bt0 * 64 + lane < T) {
     const int t = bt0 * 64 + lane;
     nk = __float_as_uint(rb[t]);
-    n1 = s1b[t];
-    n2 = s2b[t];
+    n1 = meanb[t];
+    n2 = m2b[t];
   }
   for (int bt = bt0; bt < n_batches; bt += bstep) {
     const int t = bt * 64 + lane;
     const bool live = t < T;
     const u32 k = nk;
-    const double v1 = n1, v2 = n2;
+    const double dm = n1 - pb;
+    const double v1 = cn * dm, v2 = n2 + cn * dm * dm;   // the token's sums about the image's pivot
     {
       const int tn = t + bstep * 64;
       if (bt + bstep < n_batches && tn < T) {
         nk = __float_as_uint(rb[tn]);
-        n1 = s1b[tn];
-        n2 = s2b[tn];
+        n1 = meanb[tn];
+        n2 = m2b[tn];
       }
     }
     int g = -1;

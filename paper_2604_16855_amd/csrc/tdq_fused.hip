@@ -2,7 +2,7 @@
 // bandwidth, sets the time (a few hundred kilobytes per image): what tdq_calibrate_groups
 // followed by tdq_quantize_act compute, in ONE kernel, one workgroup of 1024 threads per
 // image, the steps separated by workgroup barriers instead of kernel boundaries:
-//   A  per-token range and moments                      (Sec. 4.2)
+//   A  per-token range, mean and centred second moment  (Sec. 4.2)
 //   B  token -> token set, per-set sums                 (assign_tokens)
 //   C  per set: n, sigma, rank k                        (merge_partials)
 //   D  k-th smallest |x| of every set: radix select on the magnitude bit pattern, 8 bits
@@ -22,8 +22,8 @@ constexpr int kFusedMaxG = TDQ_FUSED_MAX_GROUPS;
 template <typename T>
 __global__ __launch_bounds__(kFusedThreads) void k_fused_small(
     const T* __restrict__ X, long long ld, int T_, int C, int G, int L, int vec_ok, int q_vec_ok,
-    Scalars sc, int with_base, float* __restrict__ r, double* __restrict__ s1,
-    double* __restrict__ s2, int* __restrict__ gid, float* __restrict__ clip,
+    Scalars sc, int with_base, float* __restrict__ r, double* __restrict__ mean,
+    double* __restrict__ m2, int* __restrict__ gid, float* __restrict__ clip,
     float* __restrict__ scale, tdq_group_stats* __restrict__ stats, u32* __restrict__ image_flags,
     uint8_t* __restrict__ Q, long long ld_q) {
   constexpr int V = Elem<T>::V;
@@ -41,8 +41,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_small(
   const int rsub = tid / L, rpp = kFusedThreads / L;
   const T* Xb = X + (long long)b * T_ * ld;
   float* rb = r + (long long)b * T_;
-  double* s1b = s1 + (long long)b * T_;
-  double* s2b = s2 + (long long)b * T_;
+  double* meanb = mean + (long long)b * T_;
+  double* m2b = m2 + (long long)b * T_;
   int* gb = gid + (long long)b * T_;
   const int nvec = vec_ok ? C / V : 0;
 
@@ -54,26 +54,29 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_small(
     const T* xp = Xb + (long long)(valid ? row : T_ - 1) * ld;
     u32 kmax = 0;
     double a1 = 0.0, a2 = 0.0;
+    // binary64 sums about the row's first value (any value of the row is a good enough
+    // pivot in binary64; see "Moments" in tdq_device.hpp)
+    const double P = (double)Elem<T>::val(xp[0]);
     for (int v = lr; v < nvec; v += L) {
       const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
       T e[V];
       Elem<T>::unpack(q, e);
 #pragma unroll
       for (int i = 0; i < V; ++i) {
-        const double f = (double)Elem<T>::val(e[i]);
+        const double d = (double)Elem<T>::val(e[i]) - P;
         const u32 k = Elem<T>::key(e[i]);
         kmax = k > kmax ? k : kmax;
-        a1 += f;
-        a2 = fma(f, f, a2);
+        a1 += d;
+        a2 = fma(d, d, a2);
       }
     }
     for (int c = nvec * V + lr; c < C; c += L) {
       const T x = xp[c];
-      const double f = (double)Elem<T>::val(x);
+      const double d = (double)Elem<T>::val(x) - P;
       const u32 k = Elem<T>::key(x);
       kmax = k > kmax ? k : kmax;
-      a1 += f;
-      a2 = fma(f, f, a2);
+      a1 += d;
+      a2 = fma(d, d, a2);
     }
     for (int m = L >> 1; m > 0; m >>= 1) {       // butterfly: all L lanes end with the same bits
       const u32 ok = (u32)__shfl_xor((int)kmax, m, 64);
@@ -82,15 +85,17 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_small(
       a2 += __shfl_xor(a2, m, 64);
     }
     if (lr == 0 && valid) {
+      double mu, q;
+      pivot_to_central(P, a1, a2, C, mu, q);
       rb[row] = Elem<T>::key_to_float(kmax);
-      s1b[row] = a1;
-      s2b[row] = a2;
+      meanb[row] = mu;
+      m2b[row] = q;
     }
   }
   __syncthreads();                               // the workgroup's global writes are visible to it
 
   // ---- B
-  assign_tokens(rb, s1b, s2b, T_, G, gb, wacc, s_min, s_max, s_lohi, 0, 1);
+  assign_tokens(rb, meanb, m2b, T_, C, G, gb, wacc, s_min, s_max, s_lohi, 0, 1);
   if (tid == 0 && image_flags) image_flags[b] = s_lohi[1] >= 0x7F800000u ? TDQ_DEV_NONFINITE : 0u;
 
   // one rank select per rank wanted: the percentile base radius first (if asked for)
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_small(
 
 template <typename T>
 static hipError_t fused_t(const T* X, int B, int T_, int C, long long ld, int G, const Scalars& sc,
-                          float* r, double* s1, double* s2, int* gid, float* clip, float* scale,
+                          float* r, double* mean, double* m2, int* gid, float* clip, float* scale,
                           tdq_group_stats* stats, unsigned* image_flags, uint8_t* Q, long long ld_q,
                           hipStream_t st) {
   constexpr int V = Elem<T>::V;
@@ -217,19 +222,19 @@ static hipError_t fused_t(const T* X, int B, int T_, int C, long long ld, int G,
   const int L = lanes_per_row(C, 8);
   const int with_base = sc.base_pct > 0.0 ? 1 : 0;
   hipLaunchKernelGGL((k_fused_small<T>), dim3(B), dim3(kFusedThreads), 0, st, X, ld, T_, C, G, L,
-                     vec_ok, q_vec_ok, sc, with_base, r, s1, s2, gid, clip, scale, stats, image_flags,
+                     vec_ok, q_vec_ok, sc, with_base, r, mean, m2, gid, clip, scale, stats, image_flags,
                      Q, ld_q);
   return hipGetLastError();
 }
 
 hipError_t launch_fused_small(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
-                              const Scalars& sc, float* r, double* s1, double* s2, int* gid,
+                              const Scalars& sc, float* r, double* mean, double* m2, int* gid,
                               float* clip, float* scale, tdq_group_stats* stats,
                               unsigned* image_flags, uint8_t* Q, long long ld_q, hipStream_t st) {
   if (dt == TDQ_F16)
-    return fused_t<u16>(static_cast<const u16*>(X), B, T, C, ld, G, sc, r, s1, s2, gid, clip, scale,
+    return fused_t<u16>(static_cast<const u16*>(X), B, T, C, ld, G, sc, r, mean, m2, gid, clip, scale,
                         stats, image_flags, Q, ld_q, st);
-  return fused_t<float>(static_cast<const float*>(X), B, T, C, ld, G, sc, r, s1, s2, gid, clip, scale,
+  return fused_t<float>(static_cast<const float*>(X), B, T, C, ld, G, sc, r, mean, m2, gid, clip, scale,
                         stats, image_flags, Q, ld_q, st);
 }
 

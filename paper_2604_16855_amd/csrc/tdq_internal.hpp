@@ -64,8 +64,8 @@ struct WorkspaceLayout {
                      // pass kPassZr and pass kPassBase (resolved by the per-set radix select)
   size_t img_flag;   // uint32[B]     per-image non-finite flag
   size_t r;          // float[M]      per-token range
-  size_t s1;         // double[M]     per-token sum x
-  size_t s2;         // double[M]     per-token sum x^2
+  size_t mean;       // double[M]     per-token mean
+  size_t m2;         // double[M]     per-token sum (x - mean)^2
   size_t part;       // per-workgroup partial set records of the assignment
   size_t grp;        // GroupWork[B*G]
   size_t hist;       // uint32 [levels][B*G][1 << bits[level]]
@@ -96,7 +96,7 @@ constexpr int kPassBase = 1;
 
 // ---- launch wrappers (each returns the hipError_t of its launch) -------------
 hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long long ld,
-                              float* r, double* s1, double* s2, hipStream_t st);
+                              float* r, double* mean, double* m2, hipStream_t st);
 // Token-set assignment.  An image is shared by assign_split(T) workgroups, each of
 // which leaves one partial record per set in `part`; the records are merged into
 // GroupWork either by launch_finalize_groups or, for binary16 input, by the first
@@ -104,8 +104,8 @@ hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long lo
 constexpr int kAssignSplitMax = 8;
 int assign_split(int T);
 size_t assign_partial_bytes(int B, int G);
-hipError_t launch_assign(const float* r, const double* s1, const double* s2, int B, int T, int G,
-                         int* gid, void* part, unsigned* img_flag, unsigned* status,
+hipError_t launch_assign(const float* r, const double* mean, const double* m2, int B, int T, int C,
+                         int G, int* gid, void* part, unsigned* img_flag, unsigned* status,
                          hipStream_t st);
 // Arms the radix levels for one pass: working record of every set (rank of this pass;
 // keep_base = keep the base radius an earlier pass left) and cleared level histograms.
@@ -150,15 +150,15 @@ hipError_t launch_quantize_blocks_chw(const void* X, tdq_dtype dt, int B, int C,
                                       long long ld_q, float* bscale, float* bclip, long long ld_s,
                                       bool f6, hipStream_t st);
 hipError_t launch_fused_small(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
-                              const Scalars& sc, float* r, double* s1, double* s2, int* gid,
+                              const Scalars& sc, float* r, double* mean, double* m2, int* gid,
                               float* clip, float* scale, tdq_group_stats* stats,
                               unsigned* image_flags, uint8_t* Q, long long ld_q, hipStream_t st);
 hipError_t launch_range_disparity(const void* X, tdq_dtype dt, int B, int T, int C, long long ld,
                                   float* token_median, float* token_max, float* disparity,
                                   float* max_abs, hipStream_t st);
 hipError_t launch_tokenize_stats_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
-                                     long long ld_b, void* Xt, long long ld_xt, float* r, double* s1,
-                                     double* s2, hipStream_t st);
+                                     long long ld_b, void* Xt, long long ld_xt, float* r, double* mean,
+                                     double* m2, hipStream_t st);
 hipError_t launch_quantize_f6(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                               const int* gid, const float* clip, const float* scale, uint8_t* F,
                               hipStream_t st);

@@ -10,6 +10,8 @@
 // read side: 8 (4) two- (four-) byte reads per 16-byte store; rows of the LDS tile are 8
 // bytes longer than the data, which leaves those reads with two-way bank conflicts at
 // most.
+#include <type_traits>
+
 #include "tdq_device.hpp"
 
 namespace tdq {
@@ -105,17 +107,23 @@ hipError_t launch_tokenize_chw(const void* X, tdq_dtype dt, int B, int C, int T,
 // ---------------------------------------------------------------------------
 // The re-layout fused with the statistics sweep of the token-set path: one read of the
 // feature map yields the token-major copy Xt AND every token's range and moments
-// (r_t = max_c |x|, sum x, sum x^2 in binary64; Sec. 4.2), so a convolutional input costs
+// (r_t = max_c |x|, mean_t, M2_t = sum_c (x - mean_t)^2; Sec. 4.2), so a convolutional input costs
 // the token-set path one extra write of X, not an extra read and write.  A workgroup
 // owns TT consecutive tokens of one image and walks the channel axis in tiles of 64:
 // every thread keeps the partial statistics of its 4 tokens across the tiles; at the end
-// the lanes that share a token (adjacent ones) are reduced with DPP.
+// the lanes that share a token (adjacent ones) are reduced with DPP.  The sums are taken
+// about a per-token pivot taken from the first tile, see "Moments" in tdq_device.hpp:
+// binary32 input, the token's first channel; binary16 input, the mean of its first
+// min(C, 64) channels.  The map is read once, so a token cannot be summed again about a
+// better pivot as in the token-major sweep; the mean of 64 of its values lies within
+// sigma_t sqrt(C / 64) of the token's mean (Cauchy-Schwarz), which bounds what the
+// binary32 partial sums can cost its M2 at (1 + C / 64) * 3 * 2^-24 per partial.
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
     const T* __restrict__ X, long long ld_c, long long ld_b, int C, int T_, T* __restrict__ Xt,
-    long long ld_xt, int vin_ok, int vout_ok, float* __restrict__ r, double* __restrict__ s1,
-    double* __restrict__ s2) {
+    long long ld_xt, int vin_ok, int vout_ok, float* __restrict__ r, double* __restrict__ mean,
+    double* __restrict__ m2) {
   constexpr int E = 16 / (int)sizeof(T);
   constexpr int TC = 64;
   constexpr int TT = 16 * E;
@@ -131,8 +139,10 @@ __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
   const int q = tid % PQ;
   u32 kmax[NP];
   double a1[NP], a2[NP];
+  typedef typename std::conditional<sizeof(T) == 2, float, double>::type PT;
+  PT P[NP];
 #pragma unroll
-  for (int i = 0; i < NP; ++i) { kmax[i] = 0; a1[i] = 0.0; a2[i] = 0.0; }
+  for (int i = 0; i < NP; ++i) { kmax[i] = 0; a1[i] = 0.0; a2[i] = 0.0; P[i] = 0; }
 
   // the next tile's global loads are in flight while the current one is processed
   const int lp = tid & 15, ltok = t0 + (tid & 15) * E;
@@ -163,6 +173,21 @@ __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
     __syncthreads();
     if (c0 + TC < C) load_tile(c0 + TC);
     const int c = c0 + q * E;
+    if (c0 == 0) {                               // the tokens' pivots, from the first tile
+#pragma unroll
+      for (int i = 0; i < NP; ++i) {
+        const int tl = tid / PQ + TPP * i;
+        if constexpr (sizeof(T) == 2) {
+          float sum = 0.f;                       // channels past C are zeros in the tile
+#pragma unroll
+          for (int k = 0; k < E; ++k) sum += Elem<T>::val(tile[q * E + k][tl]);
+          sum = xor_reduce_sum<PQ, float>(sum);  // the same bits in all lanes of the token
+          P[i] = sum / (float)(C < TC ? C : TC);
+        } else {
+          P[i] = (double)Elem<T>::val(tile[0][tl]);
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int tl = tid / PQ + TPP * i;
@@ -170,18 +195,20 @@ __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
       __attribute__((aligned(16))) T v[E];
 #pragma unroll
       for (int k = 0; k < E; ++k) v[k] = tile[q * E + k][tl];
-      // channels beyond C are zeros in the tile: they change neither maximum nor sums
+      // channels beyond C are zeros in the tile: they do not change the maximum, and are
+      // kept out of the sums
       if constexpr (sizeof(T) == 2) {
-        // as in the token-major statistics sweep: the 8 values and their squares (exact
-        // in binary32) are first summed in binary32, then accumulated in binary64
+        // as in the token-major statistics sweep: the 8 differences and their squares are
+        // first summed in binary32, then accumulated in binary64
         float p1 = 0.f, p2 = 0.f;
 #pragma unroll
         for (int k = 0; k < E; ++k) {
           const float f = Elem<T>::val(v[k]);
           const u32 key = Elem<T>::key(v[k]);
           kmax[i] = key > kmax[i] ? key : kmax[i];
-          p1 += f;
-          p2 = __builtin_fmaf(f, f, p2);
+          const float d = c + k < C ? f - P[i] : 0.f;
+          p1 += d;
+          p2 = __builtin_fmaf(d, d, p2);
         }
         a1[i] += (double)p1;
         a2[i] += (double)p2;
@@ -191,8 +218,9 @@ __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
           const double f = (double)Elem<T>::val(v[k]);
           const u32 key = Elem<T>::key(v[k]);
           kmax[i] = key > kmax[i] ? key : kmax[i];
-          a1[i] += f;
-          a2[i] = fma(f, f, a2[i]);
+          const double d = c + k < C ? f - P[i] : 0.0;
+          a1[i] += d;
+          a2[i] = fma(d, d, a2[i]);
         }
       }
       if (tok < T_) {
@@ -216,16 +244,18 @@ __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
     const int tok = t0 + tid / PQ + TPP * i;
     if (q == PQ - 1 && tok < T_) {               // the group's last lane holds the totals
       const long long row = (long long)b * T_ + tok;
+      double mu, qq;
+      pivot_to_central((double)P[i], t1, t2, C, mu, qq);
       r[row] = Elem<T>::key_to_float(km);
-      s1[row] = t1;
-      s2[row] = t2;
+      mean[row] = mu;
+      m2[row] = qq;
     }
   }
 }
 
 template <typename T>
 static hipError_t tokenize_stats_t(const T* X, int B, int C, int T_, long long ld_c, long long ld_b,
-                                   T* Xt, long long ld_xt, float* r, double* s1, double* s2,
+                                   T* Xt, long long ld_xt, float* r, double* mean, double* m2,
                                    hipStream_t st) {
   constexpr int E = 16 / (int)sizeof(T);
   const int vin_ok =
@@ -233,18 +263,18 @@ static hipError_t tokenize_stats_t(const T* X, int B, int C, int T_, long long l
   const int vout_ok = ((reinterpret_cast<uintptr_t>(Xt) & 15) == 0 && ld_xt % E == 0) ? 1 : 0;
   const dim3 grid((unsigned)((T_ + 16 * E - 1) / (16 * E)), (unsigned)B);
   hipLaunchKernelGGL((k_tokenize_stats_chw<T>), grid, dim3(256), 0, st, X, ld_c, ld_b, C, T_, Xt,
-                     ld_xt, vin_ok, vout_ok, r, s1, s2);
+                     ld_xt, vin_ok, vout_ok, r, mean, m2);
   return hipGetLastError();
 }
 
 hipError_t launch_tokenize_stats_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
-                                     long long ld_b, void* Xt, long long ld_xt, float* r, double* s1,
-                                     double* s2, hipStream_t st) {
+                                     long long ld_b, void* Xt, long long ld_xt, float* r, double* mean,
+                                     double* m2, hipStream_t st) {
   if (dt == TDQ_F16)
     return tokenize_stats_t<u16>(static_cast<const u16*>(X), B, C, T, ld_c, ld_b,
-                                 static_cast<u16*>(Xt), ld_xt, r, s1, s2, st);
+                                 static_cast<u16*>(Xt), ld_xt, r, mean, m2, st);
   return tokenize_stats_t<float>(static_cast<const float*>(X), B, C, T, ld_c, ld_b,
-                                 static_cast<float*>(Xt), ld_xt, r, s1, s2, st);
+                                 static_cast<float*>(Xt), ld_xt, r, mean, m2, st);
 }
 
 }  // namespace tdq

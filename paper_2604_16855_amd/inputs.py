@@ -213,3 +213,24 @@ def random_codes(shape, seed: int, lo: int = -8, hi: int = 7) -> np.ndarray:
     """Uniform int8 codes in [lo, hi] — for contraction-only tests."""
     rng = np.random.Generator(np.random.PCG64([seed, 77]))
     return rng.integers(lo, hi + 1, size=shape, dtype=np.int8)
+
+
+def offset_activations(B: int, T: int, C: int, dtype: str, ratio: float, seed: int,
+                       token_jitter: float = 0.0, outlier_head: bool = False) -> np.ndarray:
+    """X[B, T, C] whose values sit far from zero: x = mu_t + s_t * N(0, 1) with a per-token
+    spread s_t (log-normal around 0.25, so tokens fall into different token sets) and a
+    mean mu_t = ratio * 0.25 * (1 + token_jitter * u_t), u_t ~ U(-1, 1).  This is the regime
+    where the step-to-dispersion bound of Eq. (tau_constraint) binds and where a variance
+    computed from raw sums of squares cancels.  `outlier_head` puts two large values of
+    opposite offset at the start of every third token's row."""
+    rng = np.random.Generator(np.random.PCG64([seed, 1 << 21]))
+    s = 0.25 * rng.lognormal(0.0, 0.5, size=(B, T, 1))
+    mu = ratio * 0.25 * (1.0 + token_jitter * rng.uniform(-1.0, 1.0, size=(B, T, 1)))
+    X = mu + s * rng.normal(0.0, 1.0, size=(B, T, C))
+    if outlier_head and C >= 3:
+        X[:, ::3, 0] += 40.0 * s[:, ::3, 0]
+        X[:, ::3, 1] += 55.0 * s[:, ::3, 0]
+    if dtype == "f16":
+        np.clip(X, -FP16_MAX, FP16_MAX, out=X)
+        return X.astype(np.float16)
+    return X.astype(np.float32)
