@@ -23,74 +23,123 @@ struct PivotOf { typedef double type; };
 template <>
 struct PivotOf<u16> { typedef float type; };
 
+// One 16-byte piece of a row added to a lane's partial sums about the pivot P.
+template <typename T>
+struct RowAcc;
+template <>
+struct RowAcc<u16> {
+  us2 kpk = {0, 0};                     // running max of the magnitude keys, two at a time
+  double a1 = 0.0, a2 = 0.0;
+  float one, nP;
+  __device__ __forceinline__ explicit RowAcc(float P) : nP(-P) {
+    one = 1.0f;                         // opaque to the optimizer, so x * one - P stays ONE mixed fma
+    asm volatile("" : "+v"(one));
+  }
+  // Per element: d = x - P as one mixed-precision fma (the fp16 -> fp32 conversion rides in
+  // the instruction), one add for the sum and one fma for the sum of squares; the keys of a
+  // pair of elements are maxed with one packed 16-bit instruction.
+  __device__ __forceinline__ void add(const uint4& q) {
+    const u32 w[4] = {q.x, q.y, q.z, q.w};
+    float p1, p2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const h2 h = __builtin_bit_cast(h2, w[j]);
+      kpk = __builtin_elementwise_max(kpk, __builtin_bit_cast(us2, w[j] & 0x7FFF7FFFu));
+      const float d0 = __builtin_fmaf((float)h[0], one, nP);
+      const float d1 = __builtin_fmaf((float)h[1], one, nP);
+      if (j == 0) {
+        p1 = d0;
+        p2 = d0 * d0;
+      } else {
+        p1 += d0;
+        p2 = __builtin_fmaf(d0, d0, p2);
+      }
+      p1 += d1;
+      p2 = __builtin_fmaf(d1, d1, p2);
+    }
+    a1 += (double)p1;
+    a2 += (double)p2;
+  }
+  __device__ __forceinline__ void add_one(u16 x, u32& kmax) {
+    const double d = (double)h2f(x) + (double)nP;
+    const u32 k = x & 0x7FFFu;
+    kmax = k > kmax ? k : kmax;
+    a1 += d;
+    a2 = fma(d, d, a2);
+  }
+  __device__ __forceinline__ u32 key_max() const { return kpk[0] > kpk[1] ? kpk[0] : kpk[1]; }
+};
+template <>
+struct RowAcc<float> {
+  u32 km = 0;
+  double a1 = 0.0, a2 = 0.0;
+  double P;
+  __device__ __forceinline__ explicit RowAcc(double P_) : P(P_) {}
+  __device__ __forceinline__ void add(const uint4& q) {
+    const u32 w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double d = (double)__uint_as_float(w[i]) - P;
+      const u32 k = w[i] & 0x7FFFFFFFu;
+      km = k > km ? k : km;
+      a1 += d;
+      a2 = fma(d, d, a2);
+    }
+  }
+  __device__ __forceinline__ void add_one(float x, u32& kmax) {
+    const double d = (double)x - P;
+    const u32 k = __float_as_uint(x) & 0x7FFFFFFFu;
+    kmax = k > kmax ? k : kmax;
+    a1 += d;
+    a2 = fma(d, d, a2);
+  }
+  __device__ __forceinline__ u32 key_max() const { return km; }
+};
+
 // The part of a row that one of NL cooperating lanes (index lr) sees: 16-byte pieces
-// lr, lr + NL, ... and, past the last whole piece, single elements.
+// lr, lr + NL, ... and, past the last whole piece, single elements.  Every lane has
+// nvec / NL whole rounds (a uniform count, so the branches below are scalar) and the
+// first nvec % NL lanes one more piece; the rounds are taken four, then two, then one
+// at a time with the loads of a step issued together, so a lane has several loads in
+// flight however short its share of the row is.
 template <typename T, int NL>
 __device__ __forceinline__ void row_partial(const T* __restrict__ xp, int lr, int nvec, int C,
                                             typename PivotOf<T>::type P, u32& kmax, double& a1,
                                             double& a2) {
   constexpr int V = Elem<T>::V;
-  kmax = 0;
-  a1 = 0.0;
-  a2 = 0.0;
-  if constexpr (sizeof(T) == 2) {
-    us2 kpk = {0, 0};                     // running max of the magnitude keys, two at a time
-    float one = 1.0f;                     // opaque to the optimizer, so x * one - P stays ONE mixed fma
-    asm volatile("" : "+v"(one));
-    const float nP = -P;
-#pragma unroll 4
-    for (int v = lr; v < nvec; v += NL) {
-      const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
-      // Per element: d = x - P as one mixed-precision fma (the fp16 -> fp32 conversion rides
-      // in the instruction), one add for the sum and one fma for the sum of squares; the
-      // keys of a pair of elements are maxed with one packed 16-bit instruction.
-      const u32 w[4] = {q.x, q.y, q.z, q.w};
-      float p1 = 0.f, p2 = 0.f;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const h2 h = __builtin_bit_cast(h2, w[j]);
-        kpk = __builtin_elementwise_max(kpk, __builtin_bit_cast(us2, w[j] & 0x7FFF7FFFu));
-        const float d0 = __builtin_fmaf((float)h[0], one, nP);
-        const float d1 = __builtin_fmaf((float)h[1], one, nP);
-        p1 += d0;
-        p2 = __builtin_fmaf(d0, d0, p2);
-        p1 += d1;
-        p2 = __builtin_fmaf(d1, d1, p2);
-      }
-      a1 += (double)p1;
-      a2 += (double)p2;
-    }
-    const u32 kp = kpk[0] > kpk[1] ? kpk[0] : kpk[1];
-    kmax = kp;
-  } else {
-#pragma unroll 4
-    for (int v = lr; v < nvec; v += NL) {
-      const uint4 q = *reinterpret_cast<const uint4*>(xp + (long long)v * V);
-      T e[V];
-      Elem<T>::unpack(q, e);
-#pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const double d = (double)Elem<T>::val(e[i]) - (double)P;
-        const u32 k = Elem<T>::key(e[i]);
-        kmax = k > kmax ? k : kmax;
-        a1 += d;
-        a2 = fma(d, d, a2);
-      }
-    }
+  RowAcc<T> acc(P);
+  const uint4* xv = reinterpret_cast<const uint4*>(xp);
+  int v = lr;
+  int rounds = nvec / NL;
+  for (; rounds >= 4; rounds -= 4, v += 4 * NL) {
+    const uint4 q0 = xv[v], q1 = xv[v + NL], q2 = xv[v + 2 * NL], q3 = xv[v + 3 * NL];
+    acc.add(q0);
+    acc.add(q1);
+    acc.add(q2);
+    acc.add(q3);
   }
-  for (int c = nvec * V + lr; c < C; c += NL) {   // ragged tail / unaligned rows
-    const T x = xp[c];
-    const double d = (double)Elem<T>::val(x) - (double)P;
-    const u32 k = Elem<T>::key(x);
-    kmax = k > kmax ? k : kmax;
-    a1 += d;
-    a2 = fma(d, d, a2);
+  if (rounds >= 2) {
+    const uint4 q0 = xv[v], q1 = xv[v + NL];
+    acc.add(q0);
+    acc.add(q1);
+    v += 2 * NL;
+    rounds -= 2;
   }
+  if (rounds >= 1) {
+    acc.add(xv[v]);
+    v += NL;
+  }
+  if (v < nvec) acc.add(xv[v]);
+  kmax = acc.key_max();
+  for (int c = nvec * V + lr; c < C; c += NL) acc.add_one(xp[c], kmax);   // ragged tail / unaligned rows
+  a1 = acc.a1;
+  a2 = acc.a2;
 }
 
 template <typename T, int L>
 __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, long long ld, int M,
-                                                     int C, int vec_ok, float* __restrict__ r,
+                                                     int C, double inv_n, int vec_ok,
+                                                     float* __restrict__ r,
                                                      double* __restrict__ mean,
                                                      double* __restrict__ m2) {
   constexpr int V = Elem<T>::V;
@@ -113,7 +162,7 @@ __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, lo
     // about its own mean (uniform branch; the data comes from the cache).
     const bool far = lr == L - 1 && pivot_is_far(a1, a2, C);
     if (__ballot(far)) {
-      const float pn = P + (float)(a1 / (double)C);
+      const float pn = P + (float)(a1 * inv_n);
       P = __shfl(pn, (int)(threadIdx.x & 63) | (L - 1), 64);
       u32 k2;
       row_partial<T, L>(xp, lr, nvec, C, P, k2, a1, a2);
@@ -123,7 +172,7 @@ __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, lo
   }
   if (lr == L - 1 && valid) {
     double mu, q;
-    pivot_to_central((double)P, a1, a2, C, mu, q);
+    pivot_to_central((double)P, a1, a2, inv_n, mu, q);
     r[row] = Elem<T>::key_to_float(kmax);
     mean[row] = mu;
     m2[row] = q;
@@ -136,7 +185,8 @@ __global__ __launch_bounds__(256) void k_token_stats(const T* __restrict__ X, lo
 // totals are combined through LDS in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void k_token_stats_wide(const T* __restrict__ X, long long ld, int M,
-                                                          int C, float* __restrict__ r,
+                                                          int C, double inv_n,
+                                                          float* __restrict__ r,
                                                           double* __restrict__ mean,
                                                           double* __restrict__ m2) {
   constexpr int V = Elem<T>::V;
@@ -161,7 +211,7 @@ __global__ __launch_bounds__(256) void k_token_stats_wide(const T* __restrict__ 
   for (int w = 1; w < 4; ++w) { t1 += sh1[0][w]; t2 += sh2[0][w]; }
   if constexpr (sizeof(T) == 2) {
     if (pivot_is_far(t1, t2, C)) {                 // uniform over the workgroup
-      P = P + (float)(t1 / (double)C);
+      P = P + (float)(t1 * inv_n);
       u32 k2;
       row_partial<T, 256>(xp, tid, nvec, C, P, k2, a1, a2);
       a1 = group_sum_f64<64>(a1);
@@ -177,11 +227,23 @@ __global__ __launch_bounds__(256) void k_token_stats_wide(const T* __restrict__ 
     u32 k = shk[0];
     for (int w = 1; w < 4; ++w) k = shk[w] > k ? shk[w] : k;
     double mu, q;
-    pivot_to_central((double)P, t1, t2, C, mu, q);
+    pivot_to_central((double)P, t1, t2, inv_n, mu, q);
     r[row] = Elem<T>::key_to_float(k);
     mean[row] = mu;
     m2[row] = q;
   }
+}
+
+// Lanes per row of the statistics sweep: enough that a wavefront's load instruction
+// covers whole 128-byte lines (8 lanes), otherwise as few as leave every lane about 8
+// pieces -- the reduction over the row's lanes costs as many vector instructions as 2
+// pieces do, and with few pieces per lane it, not the memory system, sets the pace.
+static int stats_lanes_per_row(int C, int V) {
+  const int nvec = (C + V - 1) / V;
+  int L = 1;
+  while (L < nvec && L < 8) L <<= 1;
+  while (L < 64 && L * 8 < nvec) L <<= 1;
+  return L;
 }
 
 template <typename T>
@@ -190,16 +252,17 @@ static hipError_t token_stats_t(const T* X, int M, int C, long long ld, float* r
   constexpr int V = Elem<T>::V;
   const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % V == 0) ? 1 : 0;
   if (vec_ok && C / V >= 256) {
-    hipLaunchKernelGGL((k_token_stats_wide<T>), dim3(M), dim3(256), 0, st, X, ld, M, C, r, mean, m2);
+    hipLaunchKernelGGL((k_token_stats_wide<T>), dim3(M), dim3(256), 0, st, X, ld, M, C,
+                       1.0 / (double)C, r, mean, m2);
     return hipGetLastError();
   }
-  const int L = lanes_per_row(C, V);
+  const int L = stats_lanes_per_row(C, V);
   const long long threads = (long long)M * L;
   const unsigned grid = (unsigned)((threads + 255) / 256);
 #define TDQ_TS(LL)                                                                       \
   case LL:                                                                               \
     hipLaunchKernelGGL((k_token_stats<T, LL>), dim3(grid), dim3(256), 0, st, X, ld, M, C, \
-                       vec_ok, r, mean, m2);                                             \
+                       1.0 / (double)C, vec_ok, r, mean, m2);                            \
     break;
   switch (L) {
     TDQ_TS(1) TDQ_TS(2) TDQ_TS(4) TDQ_TS(8) TDQ_TS(16) TDQ_TS(32) TDQ_TS(64)

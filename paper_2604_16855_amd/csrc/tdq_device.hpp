@@ -138,22 +138,23 @@ __device__ __forceinline__ u32 group_sum_u32(u32 v) {
 //     a token adds C (mean - P_b) and M2 + C (mean - P_b)^2 to the set's two sums.
 // Both conversions are binary64 and lose (distance to the pivot / sigma)^2 units of 2^-53.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void pivot_to_central(double P, double S1, double S2, int C,
+// inv_n = 1 / C (rounded once, by the caller: a binary64 division costs a wavefront about
+// thirty instructions, as much as a quarter of a short row's sweep).
+__device__ __forceinline__ void pivot_to_central(double P, double S1, double S2, double inv_n,
                                                  double& mean, double& m2) {
-  const double n = (double)C;
-  mean = P + S1 / n;
-  const double v = S2 - S1 * S1 / n;
+  const double t = S1 * inv_n;               // mean - P
+  mean = P + t;
+  const double v = S2 - S1 * t;
   m2 = v > 0.0 ? v : 0.0;
 }
 
 // True when a row summed about P should be summed again about its mean: the pivot lies
 // more than sqrt(8) row standard deviations from the mean, so the binary32 partial sums
 // of a binary16 row (3 * 2^-24 relative to sum (x - P)^2 each) could cost the row's M2
-// more than 1e-6.  False for NaN.
+// more than 1e-6.  With off = S1^2 / C = C (mean - P)^2 the test off > 8 (S2 - off) is
+// 9 S1^2 > 8 C S2.  False for NaN.
 __device__ __forceinline__ bool pivot_is_far(double S1, double S2, int C) {
-  const double n = (double)C;
-  const double off = S1 * S1 / n;            // C (mean - P)^2
-  return off > 8.0 * (S2 - off);
+  return 9.0 * (S1 * S1) > (8.0 * (double)C) * S2;
 }
 
 // Pivot of a binary16 row: the median of its first three values (one outlier among

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_small(
     }
     if (lr == 0 && valid) {
       double mu, q;
-      pivot_to_central(P, a1, a2, C, mu, q);
+      pivot_to_central(P, a1, a2, 1.0 / (double)C, mu, q);
       rb[row] = Elem<T>::key_to_float(kmax);
       meanb[row] = mu;
       m2b[row] = q;

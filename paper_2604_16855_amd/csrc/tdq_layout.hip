@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void k_tokenize_stats_chw(
     if (q == PQ - 1 && tok < T_) {               // the group's last lane holds the totals
       const long long row = (long long)b * T_ + tok;
       double mu, qq;
-      pivot_to_central((double)P[i], t1, t2, C, mu, qq);
+      pivot_to_central((double)P[i], t1, t2, 1.0 / (double)C, mu, qq);
       r[row] = Elem<T>::key_to_float(km);
       mean[row] = mu;
       m2[row] = qq;
