@@ -60,6 +60,9 @@ typedef enum {
 #define TDQ_FLAG_EXACT_SELECT 256u
 
 #define TDQ_MAX_GROUPS 256
+/* Largest K of the whole-K contraction: its int32 accumulator holds 256 * acc (the codes
+ * enter the matrix instruction as 16 * code), and |acc| <= 64 K, so 2^14 K < 2^31. */
+#define TDQ_MAX_K 131071
 #define TDQ_FUSED_MAX_GROUPS 64 /* most token sets per image of tdq_calibrate_quantize_fused */
 #define TDQ_BLOCK 32 /* channel block g of the per-(token, block) entry points (Sec. 5 setup) */
 
@@ -262,7 +265,7 @@ int tdq_group_diagnostics(const void* X, tdq_dtype dt, int32_t B, int32_t T, int
  * ld_q, ld_w multiples of 16 with ld >= 16*ceil(K/32) (rows are read in 16-byte
  * pieces; bytes past ceil(K/2) are ignored).  Y [B*T, ld_y] of y_dt (fp32 or fp16).
  * acc_dump [B*T, N] int32 or NULL.  bias [N] or NULL.  group_id may be NULL when
- * G == 1.
+ * G == 1.  K <= TDQ_MAX_K, else TDQ_ERR_SHAPE.
  */
 int tdq_w4a4_linear(const uint8_t* Qx, int64_t ld_q, const int32_t* group_id, const float* scale,
                     int32_t B, int32_t T, int32_t K, int32_t N, int32_t G, const uint8_t* Qw,

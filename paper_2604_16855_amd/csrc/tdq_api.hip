@@ -490,7 +490,7 @@ int tdq_w4a4_linear(const uint8_t* Qx, int64_t ld_q, const int32_t* group_id, co
   if (y_dt != TDQ_F16 && y_dt != TDQ_F32) return TDQ_ERR_DTYPE;
   if (B < 1 || T < 1 || K < 1 || N < 1) return TDQ_ERR_SHAPE;
   if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
-  if (K > 131072) return TDQ_ERR_SHAPE;     // 256 * 64 * K must stay below 2^31
+  if (K > TDQ_MAX_K) return TDQ_ERR_SHAPE;  // 256 * 64 * K must stay below 2^31
   if (G < 1 || G > TDQ_MAX_GROUPS) return TDQ_ERR_PARAM;
   if (!group_id && G != 1) return TDQ_ERR_NULL;
   const int64_t row_bytes = 16 * (((int64_t)K + 31) / 32);

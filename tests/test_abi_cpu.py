@@ -123,6 +123,8 @@ def test_quantize_and_linear_reject_bad_arguments():
     assert call(gid=None) == tdq.ERR_NULL          # G > 1 needs group ids
     assert call(K=0) == tdq.ERR_SHAPE
     assert call(K=200000) == tdq.ERR_SHAPE
+    # the int32 accumulator holds 256 * acc and |acc| <= 64 K: K = 2^17 could reach 2^31
+    assert call(K=131072, ld_q=65536, ld_w=65536) == tdq.ERR_SHAPE
     assert call(ld_q=16) == tdq.ERR_SHAPE          # 64 codes need 32 bytes
     assert call(ld_q=40) == tdq.ERR_ALIGN
     assert call(Qw=FAKE + 4) == tdq.ERR_ALIGN
@@ -178,6 +180,8 @@ def test_block_linear_rejects_bad_arguments():
     assert call(bs=None) == tdq.ERR_NULL
     assert call(M=0) == tdq.ERR_SHAPE
     assert call(K=200000) == tdq.ERR_SHAPE
+    # the int32 accumulator holds 256 * acc and |acc| <= 64 K: K = 2^17 could reach 2^31
+    assert call(K=131072, ld_q=65536, ld_w=65536) == tdq.ERR_SHAPE
     assert call(ld_s=1) == tdq.ERR_SHAPE           # 64 codes are 2 blocks
     assert call(ld_q=16) == tdq.ERR_SHAPE
     assert call(ld_w=40) == tdq.ERR_ALIGN

@@ -109,8 +109,9 @@ def test_cfg2_activation_path_full_batch():
     U.assert_calibration_matches(g, X, p)
 
 
-@pytest.mark.parametrize("name", ["cfg3_s2_kv", "cfg3_s4_fc1", "cfg3_s3_q"])
+@pytest.mark.parametrize("name", sorted(n for n in I.CASES if n.startswith("cfg3_")))
 def test_cfg3_shapes(name):
+    """Every distinct linear of the 4-stage encoder set (20 shapes), two images each."""
     lc = I.case(name, B=2)
     X, _ = I.make_activations(lc)
     _full_path(name, tdq.default_params(lc.G), X, I.make_weight(lc), I.make_bias(lc))
@@ -288,12 +289,15 @@ def test_token_permutation_invariance_on_gpu():
 
 # ------------------------------------------------- full size, sampled checks
 @pytest.mark.timeout(900)
-def test_cfg4_full_size_sampled():
-    """ViT-L-shaped stress at its full size in the launch configuration the
-    benchmark times; the oracle checks two whole images of the calibration and
-    sampled rows of codes and outputs."""
-    lc = I.case("cfg4_fc1_h10")
-    _say("[cfg4] generating inputs")
+@pytest.mark.parametrize("name,out_dtype", [("cfg4_fc1_h10", torch.float16), ("cfg4_fc2_h10", torch.float32)])
+def test_cfg4_full_size_sampled(name, out_dtype):
+    """ViT-L-shaped stress at its full size, both linears, in the launch configuration the
+    benchmark times (fc1 with binary16 output, fc2 with binary32 output; the same kernels:
+    statistics sweep, single-sweep rank select, quantizer, wide-stage contraction); the
+    oracle checks two whole images of the calibration and sampled rows of codes and
+    outputs."""
+    lc = I.case(name)
+    _say(f"[cfg4] {name}: generating inputs")
     X, _ = I.make_activations(lc, workers=16)
     W = I.make_weight(lc)
     p = tdq.default_params(lc.G)
@@ -303,9 +307,10 @@ def test_cfg4_full_size_sampled():
     gid_d, clip_d, scale_d, stats_d, ws = tdq.tdq_calibrate_groups(Xd, p, want_stats=True)
     Q = tdq.tdq_quantize_act(Xd, p, gid_d, clip_d, scale_d)
     Qw_d, ws_d = tdq.tdq_quantize_weight(torch.from_numpy(W).to(U.dev()))
-    Y = tdq.tdq_w4a4_linear(Q, gid_d, scale_d, B, T, C, Qw_d, ws_d)
+    Y = tdq.tdq_w4a4_linear(Q, gid_d, scale_d, B, T, C, Qw_d, ws_d, None, out_dtype)
     torch.cuda.synchronize()
     assert tdq.device_status(ws) == 0
+    _say(f"[cfg4] sets resolved by the per-set radix select: {tdq.exact_select_sets(ws)}")
     gid, clip, scale = gid_d.cpu().numpy(), clip_d.cpu().numpy(), scale_d.cpu().numpy()
     stats = tdq.stats_to_numpy(stats_d).reshape(B, G)
     op = U.oracle_params(p)
@@ -321,9 +326,13 @@ def test_cfg4_full_size_sampled():
         g1, c1, s1, st1 = O.calibrate_groups(X[b:b + 1], op)
         assert np.array_equal(gid[b], g1[0])
         for j in range(G):
+            assert stats[b, j]["n"] == st1[0][j]["n"]
             if st1[0][j]["n"]:
                 assert stats[b, j]["thr"] == st1[0][j]["thr"]
                 assert stats[b, j]["k"] == st1[0][j]["k"]
+                assert stats[b, j]["c_base"] == st1[0][j]["c_base"]
+                assert abs(float(stats[b, j]["sigma"]) - float(st1[0][j]["sigma"])) \
+                    <= U.SCALE_RTOL * float(st1[0][j]["sigma"])
         assert np.allclose(clip[b], c1[0], rtol=1e-6, atol=0)
         assert np.allclose(scale[b], s1[0], rtol=1e-6, atol=0)
         rows = np.random.Generator(np.random.PCG64(b)).choice(T, 48, replace=False)
@@ -335,28 +344,59 @@ def test_cfg4_full_size_sampled():
                              exact)
         acc_ref, Y_ref = O.w4a4_linear(q_gpu, scale[b][gid[b, rows]], qw_ref, sw_ref)
         Y_gpu = Y[b * T + torch.from_numpy(rows).to(U.dev())].cpu().numpy()
+        if out_dtype == torch.float16:
+            Y_ref = Y_ref.astype(np.float16)
         assert np.array_equal(Y_gpu, Y_ref)
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["cfg4_fc1_h2", "cfg4_fc1_h25", "cfg4_fc2_h2", "cfg4_fc2_h25"])
+def test_cfg4_heavy_sweep_calibration(name):
+    """The heavy-tail sweep of the stress configuration (2 % and 25 % heavy tokens; 10 % is
+    the case above): calibration of the whole batch on the GPU, two images against the
+    oracle; the count of sets whose sampled key interval missed is reported."""
+    lc = I.case(name)
+    _say(f"[cfg4-sweep] {name}: generating inputs")
+    X, _ = I.make_activations(lc, workers=16)
+    p = tdq.default_params(lc.G)
+    B, T, C, G = lc.B, lc.T, lc.C, lc.G
+    Xd = torch.from_numpy(X).to(U.dev())
+    gid_d, clip_d, scale_d, stats_d, ws = tdq.tdq_calibrate_groups(Xd, p, want_stats=True)
+    torch.cuda.synchronize()
+    assert tdq.device_status(ws) == 0
+    _say(f"[cfg4-sweep] {name}: sets resolved by the per-set radix select: {tdq.exact_select_sets(ws)}")
+    stats = tdq.stats_to_numpy(stats_d).reshape(B, G)
+    assert int(stats["n"].sum()) == B * T * C
+    for b in (1, B - 2):
+        g = dict(gid=gid_d[b:b + 1].cpu().numpy(), clip=clip_d[b:b + 1].cpu().numpy(),
+                 scale=scale_d[b:b + 1].cpu().numpy(), stats=stats[b:b + 1].reshape(-1))
+        U.assert_calibration_matches(g, X[b:b + 1], p)
+
+
 # ------------------------------------- large-tile contraction, sampled checks
-@pytest.mark.parametrize("out_dtype,with_bias,ld_pad,K", [(torch.float32, True, 0, 256),
-                                                          (torch.float16, False, 0, 256),
-                                                          (torch.float16, True, 8, 256),
-                                                          (torch.float32, False, 2, 256),
-                                                          (torch.float32, True, 0, 320),
-                                                          (torch.float16, False, 6, 200),
-                                                          (torch.float32, True, 0, 384),
-                                                          (torch.float16, True, 0, 128),
-                                                          (torch.float16, False, 0, 768)])
-def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad, K):
+@pytest.mark.parametrize("out_dtype,with_bias,ld_pad,K,N", [(torch.float32, True, 0, 256, 4096),
+                                                            (torch.float16, False, 0, 256, 4096),
+                                                            (torch.float16, True, 8, 256, 4096),
+                                                            (torch.float32, False, 2, 256, 4096),
+                                                            (torch.float32, True, 0, 320, 4096),
+                                                            (torch.float16, False, 6, 200, 4096),
+                                                            (torch.float32, True, 0, 384, 4096),
+                                                            (torch.float16, True, 0, 128, 4096),
+                                                            (torch.float16, False, 0, 768, 4096),
+                                                            (torch.float32, True, 0, 256, 4096 + 40),
+                                                            (torch.float16, False, 0, 128, 4096 + 40),
+                                                            (torch.float16, True, 2, 320, 4096 + 40),
+                                                            (torch.float32, False, 0, 512, 4096 + 200)])
+def test_large_tile_contraction_sampled(out_dtype, with_bias, ld_pad, K, N):
     """Shapes that take the large-tile kernels (many 256x256 tiles; K a multiple of
     256 for the wide-stage pipelined one, K = 384 and 128 for the 128-code-stage one,
     K = 320 and 200 for the generic one with its K tail; 768 = three wide stages)
     without the accumulator dump, so interior tiles take the epilogue's fast
-    path and the ragged last row of tiles the bounds-checked one.  ld_pad gives Y a
-    padded leading dimension, whose padding must stay untouched.  The oracle checks
-    whole tiles' worth of rows plus a random sample."""
-    M, N = 8192 + 37, 4096
+    path and the ragged last row of tiles the bounds-checked one; N = 4096 + 40 / + 200
+    adds a ragged last COLUMN of tiles.  ld_pad gives Y a padded leading dimension, whose
+    padding must stay untouched.  The oracle checks whole tiles' worth of rows plus a
+    random sample."""
+    M = 8192 + 37
     _say(f"[gemm-large] M={M} K={K} N={N} out={out_dtype} bias={with_bias} ld_pad={ld_pad}")
     qx = I.random_codes((M, K), 101)
     qw = I.random_codes((N, K), 102)
@@ -524,3 +564,90 @@ def test_range_disparity_degenerate():
     Dr, medr, mxr = O.range_disparity(X)
     assert np.array_equal(D.cpu().numpy(), Dr) and np.isinf(Dr[0]) and Dr[1] == 1.0 and np.isinf(Dr[2])
     assert np.array_equal(med.cpu().numpy(), medr) and np.array_equal(mx.cpu().numpy(), mxr)
+
+
+# ------------------------------------------ the quotient at rounding boundaries
+def _ulp_step(a: np.ndarray, j: int) -> np.ndarray:
+    """Positive binary32 values moved j units in the last place."""
+    return (a.astype(np.float32).view(np.int32) + np.int32(j)).view(np.float32)
+
+
+def _adversarial_steps(n: int, seed: int) -> np.ndarray:
+    """n binary32 steps: all-ones and all-zeros mantissas at several exponents, the
+    1e-8 floor and its neighbours, one past a power of two, and random ones."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    fixed = []
+    for e in (-30, -26, -20, -7, -1, 0, 1, 5, 9):
+        fixed += [np.ldexp(1.0, e), np.nextafter(np.float32(np.ldexp(1.0, e)), np.float32(0)),
+                  np.nextafter(np.float32(np.ldexp(1.0, e)), np.float32(np.inf)),
+                  np.ldexp(1.5, e), np.ldexp(1.0 + 2.0 ** -12, e), np.ldexp(2.0 - 2.0 ** -12, e)]
+    fixed += [1e-8, np.nextafter(np.float32(1e-8), np.float32(1)), 3.0 / 7.0, 1.0 / 3.0, 0.1]
+    d = np.array(fixed, dtype=np.float32)
+    extra = np.exp2(rng.uniform(-20, 8, n - d.size)).astype(np.float32)
+    extra[::3] = (extra[::3].view(np.int32) | np.int32(0x7FFFFF)).view(np.float32)   # all-ones mantissas
+    return np.concatenate([d, extra])[:n]
+
+
+@pytest.mark.parametrize("clip_mult", [7.0, 1e6])
+def test_quotient_at_rounding_boundaries_f32(clip_mult):
+    """The quantizer replaces the division x~ / Delta by a reciprocal and two fused
+    multiply-adds; the code must still be that of the correctly rounded quotient
+    (Eqs. clipx, dequant; ties to even).  Every token is its own set with an adversarial
+    step; its row holds, for every k in -8..7, the binary32 numbers around (k + 1/2) Delta
+    (the boundary between codes k and k + 1), and a few tiny and huge values."""
+    B, G = 4, 256
+    T = G
+    d = _adversarial_steps(B * G, 21).reshape(B, G)
+    ks = np.arange(-8, 8, dtype=np.float64) + 0.5
+    offs = np.arange(-3, 4)
+    base = (ks[None, None, :] * d[:, :, None].astype(np.float64)).astype(np.float32)     # [B, G, 16]
+    mag = np.abs(base)
+    cols = [np.copysign(_ulp_step(mag, int(j)), base) for j in offs]
+    X = np.stack(cols, axis=-1).reshape(B, T, -1)
+    tail = np.array([0.0, -0.0, 1e-30, -1e-30, 1e-38, 3e38, -3e38, 1.0], dtype=np.float32)
+    X = np.concatenate([X, np.broadcast_to(tail, (B, T, tail.size))], axis=-1).astype(np.float32)
+    C = X.shape[-1]
+    gid = np.broadcast_to(np.arange(T, dtype=np.int32), (B, T)).copy()
+    clip = (d * np.float32(clip_mult)).astype(np.float32)
+    p = tdq.default_params(G)
+    _say(f"[quotient-f32] B={B} T={T} C={C} clip = {clip_mult} * step")
+    Q = tdq.tdq_quantize_act(U.to_device(X), p, torch.from_numpy(gid).to(U.dev()),
+                             torch.from_numpy(clip).to(U.dev()), torch.from_numpy(d).to(U.dev()))
+    torch.cuda.synchronize()
+    q_ref = O.quantize_act(X, gid, clip, d, U.oracle_params(p)).reshape(B * T, C)
+    q = U.unpack_device_codes(Q, C)
+    bad = np.argwhere(q != q_ref)
+    assert bad.size == 0, f"{len(bad)} codes differ, first at row {bad[0][0]} (step " \
+                          f"{d.reshape(-1)[bad[0][0]]!r}), x = {X.reshape(B * T, C)[tuple(bad[0])]!r}"
+    # a radius of 7 steps keeps x~ / Delta inside [-7, 7]; a wide one reaches the clamp at -8
+    assert set(np.unique(q_ref)) == set(range(-7 if clip_mult == 7.0 else -8, 8))
+
+
+def test_quotient_at_rounding_boundaries_f16():
+    """The same for binary16 input: x = (2k + 1) a with a small dyadic a is exact in
+    binary16, and the step 2a moved by -2..2 units in the last place puts every x of the
+    row exactly on, just below or just above a rounding boundary."""
+    B, G = 5, 64
+    T = G
+    rng = np.random.Generator(np.random.PCG64(22))
+    a = (rng.integers(1, 64, (B, G)) * np.exp2(rng.integers(-12, 3, (B, G)))).astype(np.float32)
+    d = np.empty((B, G), np.float32)
+    for b in range(B):
+        d[b] = _ulp_step(2.0 * a[b], b - 2)
+    k2 = np.arange(-15, 16, 2, dtype=np.float32)                         # 2k + 1, k = -8..7
+    X = (a[:, :, None] * k2[None, None, :]).astype(np.float16)
+    assert np.array_equal(X.astype(np.float32), a[:, :, None] * k2[None, None, :])
+    X = np.concatenate([X, np.zeros((B, T, 16), np.float16)], axis=-1)   # 32 channels
+    C = X.shape[-1]
+    gid = np.broadcast_to(np.arange(T, dtype=np.int32), (B, T)).copy()
+    clip = (d * np.float32(1e3)).astype(np.float32)
+    p = tdq.default_params(G)
+    _say(f"[quotient-f16] B={B} T={T} C={C}")
+    Q = tdq.tdq_quantize_act(U.to_device(X), p, torch.from_numpy(gid).to(U.dev()),
+                             torch.from_numpy(clip).to(U.dev()), torch.from_numpy(d).to(U.dev()))
+    torch.cuda.synchronize()
+    q_ref = O.quantize_act(X, gid, clip, d, U.oracle_params(p)).reshape(B * T, C)
+    assert np.array_equal(U.unpack_device_codes(Q, C), q_ref)
+    # image 2 has the unmoved steps: every x is a tie, rounded to the even neighbour
+    tie = q_ref.reshape(B, T, C)[2, :, :16]
+    assert (tie[:, :15] % 2 == 0).all() and (tie[:, 15] == 7).all()      # 7.5 -> 8, clamped to 7

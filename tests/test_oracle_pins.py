@@ -480,8 +480,49 @@ def test_linear_equals_float_linear_on_dequantized_operands():
     ref = xhat @ what.T + bias.astype(np.float64)
     noise = np.abs(xhat) @ np.abs(what).T + np.abs(bias)
     assert (np.abs(out["Y"] - ref) <= 1e-5 * noise + 1e-30).all()
-    # and x_hat is the paper's quantize-dequantize of X with those radii
+    # and x_hat is the paper's quantize-dequantize of X with those radii (Eqs. clipx,
+    # dequant), token by token with the radius and step of the token's own set, looked up
+    # here by explicit indexing (not through `row_scales`)
+    for b in range(2):
+        for t in range(60):
+            j = int(out["gid"][b, t])
+            c, d = np.float32(out["clip"][b, j]), np.float32(out["scale"][b, j])
+            xt = np.clip(X[b, t], -c, c)
+            q = np.clip(np.rint((xt / d).astype(np.float32)), -8, 7)
+            assert np.array_equal(q, out["qx"][b, t].astype(np.float32)), (b, t)
+            assert np.array_equal((q * d).astype(np.float64), xhat[b * 60 + t].astype(np.float32)), (b, t)
+            assert (np.abs(xhat[b * 60 + t] - xt) <= d / 2 * (1 + 1e-6)).all()      # Proposition 1
     assert np.abs(out["acc"]).max() <= 56 * 48
+
+
+def test_row_scales_hand_values():
+    """The step of a row is the step of ITS image's token set: two images whose tokens sit
+    in different sets, values written out by hand.  A transposed or image-blind lookup
+    gives another list."""
+    gid = np.array([[0, 2, 1], [1, 1, 0]], dtype=np.int32)
+    scale = np.array([[1.0, 2.0, 3.0], [10.0, 20.0, 30.0]], dtype=np.float32)
+    assert O.row_scales(gid, scale).tolist() == [1.0, 3.0, 2.0, 20.0, 20.0, 10.0]
+    assert O.row_scales(gid, scale).dtype == np.float32
+    # one set per image: every row of an image takes that image's single step
+    assert O.row_scales(np.zeros((2, 2), np.int32), np.array([[5.0], [7.0]], np.float32)).tolist() \
+        == [5.0, 5.0, 7.0, 7.0]
+
+
+def test_zero_bin_mass_and_sqnr_hand_values():
+    """Eq. (rho0_def): the share of elements with |x| <= Delta / 2, boundary included;
+    it is the share of zero codes under round-to-nearest (Sec. 3.1), and the value
+    `dcrp_group` reports.  SQNR = 10 log10(sum x^2 / sum (x - x_hat)^2) on a 3-4-5 case."""
+    x = np.array([0.0, 0.25, -0.5, 0.625, 2.0, -0.375], dtype=np.float32)
+    assert O.zero_bin_mass(x, 1.0) == 4 / 6            # 0, 0.25, -0.5 (on the boundary), -0.375
+    assert O.zero_bin_mass(x, 0.5) == 2 / 6
+    codes = O.quantize_codes(x, 7.0, 1.0)
+    assert codes.tolist() == [0, 0, 0, 1, 2, 0] and (codes == 0).mean() == O.zero_bin_mass(x, 1.0)
+    rng = _rng(85)
+    v = rng.laplace(0, 1, 500).astype(np.float32)
+    s = O.dcrp_group(v, O.Params())
+    assert s["rho0"] == np.float32(O.zero_bin_mass(v, s["scale"]))
+    assert abs(O.sqnr_db(np.array([3.0, 4.0]), np.array([3.0, 3.0])) - 10 * np.log10(25.0)) < 1e-12
+    assert abs(O.sqnr_db(np.array([1.0, -1.0]), np.array([0.9, -1.1])) - 20.0) < 1e-9
 
 
 def test_tokenize_chw_by_explicit_index_loops():
