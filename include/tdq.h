@@ -119,7 +119,7 @@ size_t tdq_workspace_bytes(int32_t B, int32_t T, int32_t C, tdq_dtype dt, const 
 /*
  * DSTG statistics + token-set assignment + DCRP projection.
  *
- *  1. per token: range r_t = max_c |x_tc| and the moments sum x, sum x^2
+ *  1. per token: range r_t = max_c |x_tc|, mean and sum (x - mean)^2
  *     (Sec. 4.2: base radius and within-group dispersion);
  *  2. per image: gid[t] in [0, G) from the bit pattern of r_t — G equal-width
  *     bins between the image's smallest and largest key, the lower end raised to
@@ -140,6 +140,27 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
                          int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
                          float* scale, tdq_group_stats* stats, void* workspace,
                          size_t workspace_bytes, void* stream);
+
+/*
+ * tdq_calibrate_groups for callers that cannot allocate or pass scratch memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same results; the calibration scratch is a static device array of
+ * TDQ_STATIC_SCRATCH_BYTES inside the library (every GPU the library runs on holds one
+ * until the process ends).  The call allocates nothing and frees nothing; the first call
+ * on a device looks the array's address up once.  Shapes whose
+ * tdq_workspace_bytes(B, T, C, dt, p) exceeds TDQ_STATIC_SCRATCH_BYTES are refused with
+ * TDQ_ERR_WORKSPACE (use tdq_calibrate_groups with a workspace of your own).  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or threads) race; calls ordered on one stream do not.
+ * status [4] device out or NULL: word 0 the device status word (TDQ_DEV_*), words 1 and 2
+ * the counts of token sets resolved by the per-set radix select (zr pass, base-radius
+ * pass), word 3 zero.  Other arguments as tdq_calibrate_groups.
+ */
+#define TDQ_STATIC_SCRATCH_BYTES (16u << 20)
+int tdq_calibrate_groups_static(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                                int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                                float* scale, tdq_group_stats* stats, uint32_t* status,
+                                void* stream);
 
 /*
  * Quantize + pack (Eqs. clipx, dequant): for row t of image b with j = gid,

@@ -1,6 +1,7 @@
 // C ABI of libtdq: argument validation on the host, workspace layout, and the
 // launch sequence of each entry point.  Nothing here computes on the data.
 #include <math.h>
+#include <atomic>
 #include <stdlib.h>
 #include <string.h>
 
@@ -169,6 +170,44 @@ static int calibrate_after_stats(const void* X, tdq_dtype dt, int32_t B, int32_t
   return TDQ_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Library-owned calibration scratch for tdq_calibrate_groups_static.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the device address is looked up
+// once per device (each GPU has its own copy at its own address) and that pointer is what
+// the kernels get.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[TDQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, or nullptr (with *rc set).
+static void* scratch_of_current_device(int* rc) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *rc = TDQ_ERR_HIP;
+    return nullptr;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    // two threads racing here look up the same address; either store is the right one
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      *rc = TDQ_ERR_HIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *rc = TDQ_OK;
+  return ptr;
+}
+
+// The status area of the scratch, handed to the caller's buffer (a kernel, not a copy
+// call: a caller may be capturing a graph).
+__global__ void k_export_status(const unsigned* __restrict__ status, unsigned* __restrict__ out) {
+  const int i = threadIdx.x;
+  if (i < 4) out[i] = i < 3 ? status[i] : 0u;
+}
+
 }  // namespace tdq
 
 using namespace tdq;
@@ -239,6 +278,35 @@ int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int3
     return TDQ_ERR_HIP;
   return calibrate_after_stats(X, dt, B, T, C, ld_x, p, group_id, clip, scale, stats, workspace, lp,
                                wl, st);
+}
+
+int tdq_calibrate_groups_static(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
+                                int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
+                                float* scale, tdq_group_stats* stats, uint32_t* status,
+                                void* stream) {
+  if (!X || !p || !group_id || !clip || !scale) return TDQ_ERR_NULL;
+  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
+  int rc = check_params(p);
+  if (rc != TDQ_OK) return rc;
+  rc = check_shape(B, T, C, ld_x);
+  if (rc != TDQ_OK) return rc;
+  if (reinterpret_cast<uintptr_t>(status) & 3) return TDQ_ERR_ALIGN;
+  const LevelPlan lp = make_level_plan(dt, p->n_groups);
+  const WorkspaceLayout wl = make_layout(B, T, p->n_groups, lp);
+  if (wl.total > (size_t)TDQ_STATIC_SCRATCH_BYTES) return TDQ_ERR_WORKSPACE;
+  void* ws = scratch_of_current_device(&rc);
+  if (!ws) return rc;
+  // the kernels of tdq_calibrate_groups clear every part of the workspace they add into
+  // (set records, histograms, counters), so what the last call left behind does not matter
+  rc = tdq_calibrate_groups(X, dt, B, T, C, ld_x, p, group_id, clip, scale, stats, ws,
+                            TDQ_STATIC_SCRATCH_BYTES, stream);
+  if (rc != TDQ_OK) return rc;
+  if (status) {
+    hipLaunchKernelGGL(k_export_status, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<const unsigned*>(static_cast<char*>(ws) + wl.status), status);
+    if (hipGetLastError() != hipSuccess) return TDQ_ERR_HIP;
+  }
+  return TDQ_OK;
 }
 
 int tdq_calibrate_groups_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,

@@ -72,6 +72,9 @@ def lib() -> C.CDLL:
     L.tdq_calibrate_groups.restype = C.c_int
     L.tdq_calibrate_groups.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                        vp, vp, vp, sz, vp]
+    L.tdq_calibrate_groups_static.restype = C.c_int
+    L.tdq_calibrate_groups_static.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp,
+                                              vp, vp, vp, vp, vp]
     L.tdq_quantize_act.restype = C.c_int
     L.tdq_quantize_act.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp, vp,
                                    vp, i64, vp]
@@ -203,6 +206,23 @@ def tdq_calibrate_groups(X: torch.Tensor, p: Params, workspace: Optional[torch.T
                                     workspace.data_ptr(), workspace.numel(), _stream())
     _check(rc, "tdq_calibrate_groups")
     return gid, clip, scale, stats, workspace
+
+
+STATIC_SCRATCH_BYTES = 16 << 20     # TDQ_STATIC_SCRATCH_BYTES
+
+
+def tdq_calibrate_groups_static(X: torch.Tensor, p: Params, out, stats: Optional[torch.Tensor] = None,
+                                status: Optional[torch.Tensor] = None) -> None:
+    """tdq_calibrate_groups on the library's static scratch.  Allocates nothing: the caller
+    passes every buffer — out = (group_id[B,T] int32, clip[B,G] f32, scale[B,G] f32), stats
+    (uint8 [B*G, 48]) or None, status (int32 [4]) or None.  Asynchronous on the current
+    stream."""
+    B, T, Cc, ld = _btc(X)
+    gid, clip, scale = out
+    rc = lib().tdq_calibrate_groups_static(X.data_ptr(), _dt(X), B, T, Cc, ld, C.byref(p),
+                                           gid.data_ptr(), clip.data_ptr(), scale.data_ptr(),
+                                           _ptr(stats), _ptr(status), _stream())
+    _check(rc, "tdq_calibrate_groups_static")
 
 
 def tdq_calibrate_quantize_fused(X: torch.Tensor, p: Params,

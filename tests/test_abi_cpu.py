@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported():
     assert {"tdq_calibrate_groups", "tdq_quantize_act", "tdq_w4a4_linear",
             "tdq_quantize_act_blocks", "tdq_w4a4_linear_blocks", "tdq_tokenize_chw", "tdq_quantize_act_blocks_chw",
             "tdq_calibrate_quantize_fused", "tdq_range_disparity",
-            "tdq_calibrate_groups_chw", "tdq_w4a4_linear_f6", "tdq_quantize_act_f6",
+            "tdq_calibrate_groups_chw", "tdq_calibrate_groups_static", "tdq_w4a4_linear_f6", "tdq_quantize_act_f6",
             "tdq_pack_codes_f6", "tdq_f6_bytes", "tdq_w4a4_linear_blocks_f6",
             "tdq_quantize_act_blocks_f6", "tdq_quantize_act_blocks_chw_f6",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
@@ -135,6 +135,29 @@ def test_quantize_and_linear_reject_bad_arguments():
     assert w(None, 8, 8, 8, FAKE, 4, FAKE, None) == tdq.ERR_NULL
     assert w(FAKE, 8, 8, 4, FAKE, 4, FAKE, None) == tdq.ERR_SHAPE
     assert w(FAKE, 8, 8, 8, FAKE, 3, FAKE, None) == tdq.ERR_SHAPE
+
+
+def test_static_scratch_entry_point_rejects_bad_arguments():
+    """tdq_calibrate_groups_static checks its arguments like tdq_calibrate_groups and refuses,
+    before touching the device, a shape whose scratch exceeds the static array."""
+    f = tdq.lib().tdq_calibrate_groups_static
+    p = tdq.default_params(32)
+
+    def call(X=FAKE, dt=0, B=2, T=64, Cc=64, ld=64, q=None, gid=FAKE, clip=FAKE, scale=FAKE, status=None):
+        return f(X, dt, B, T, Cc, ld, C.byref(q or p), gid, clip, scale, None, status, None)
+
+    assert call(X=None) == tdq.ERR_NULL
+    assert call(scale=None) == tdq.ERR_NULL
+    assert call(dt=7) == tdq.ERR_DTYPE
+    assert call(ld=63) == tdq.ERR_SHAPE
+    assert call(status=FAKE + 2) == tdq.ERR_ALIGN
+    q = tdq.default_params(32)
+    q.zr = 1.5
+    assert call(q=q) == tdq.ERR_PARAM
+    assert tdq.workspace_bytes(64, 16384, 64, tdq.TDQ_F16, p) > tdq.STATIC_SCRATCH_BYTES
+    assert call(B=64, T=16384) == tdq.ERR_WORKSPACE
+    src = open(HEADER).read()
+    assert re.search(r"#define\s+TDQ_STATIC_SCRATCH_BYTES\s+\(16u << 20\)", src)
 
 
 def test_block_quantizer_rejects_bad_arguments():
