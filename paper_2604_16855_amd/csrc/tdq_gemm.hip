@@ -372,25 +372,30 @@ __device__ __forceinline__ void expand_half(Operands<MT, NT>& dst, const Frags<M
 // instruction cannot start before the previous one has left the matrix pipe, so the
 // vector work of a bundle is split between the shadows of its matrix instructions
 // (matrix, three vector, matrix, three vector + memory) rather than queued behind both.
-template <int EXP_SET, int MT, int NT, typename MEM>
+// ZERO: the matrix instructions start a fresh accumulation (C operand 0) instead of adding
+// to acc: the first half-slab of a tile in a kernel that keeps its accumulators across tiles.
+template <int EXP_SET, int MT, int NT, bool ZERO = false, typename MEM>
 __device__ __forceinline__ void half_slab(v16i (&acc)[MT][NT], const Operands<MT, NT>& cur,
                                           Operands<MT, NT>& nxt, const Frags<MT, NT>& f, u32 hi,
                                           MEM mem) {
   constexpr int NB = MT + NT, NM = MT * NT;
+  const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     const int lo = (b * NM) / NB, up = ((b + 1) * NM) / NB, mid = lo + (up - lo + 1) / 2;
 #pragma unroll
     for (int m = lo; m < mid; ++m) {
       const int i = m / NT, j = m % NT;
-      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], ZERO ? zero : acc[i][j],
+                                                        0, 0, 0);
     }
     expand_half<EXP_SET, 0>(nxt, f, b, hi);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int m = mid; m < up; ++m) {
       const int i = m / NT, j = m % NT;
-      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i], cur.b[j], ZERO ? zero : acc[i][j],
+                                                        0, 0, 0);
     }
     expand_half<EXP_SET, 1>(nxt, f, b, hi);
     mem(b);
@@ -405,6 +410,99 @@ __device__ __forceinline__ void dma16(const uint8_t* gptr, unsigned lds_base) {
                : "memory");
 }
 
+// The same with a wavefront-uniform 64-bit base and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16s(const uint8_t* base, unsigned off, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(off), "s"(base), "s"(lds_base)
+               : "memory");
+}
+
+// 64 floats from 64 addresses -> 64 consecutive floats of LDS
+__device__ __forceinline__ void dma4s(const float* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_base)
+               : "memory");
+}
+
+// Output of a wavefront's (32 MT) x (32 NT) part of a tile that lies wholly inside Y:
+// y = (float(acc) * row scale) * column scale (+ bias), each product rounded to binary32.
+// Register r of a 32x32 accumulator fragment held by lane l is element
+// (row 8*(r/4) + 4*(l/32) + r%4, column l%32).  Every address is a wavefront-uniform row
+// pointer plus one per-lane 32-bit offset.  wtile = &Y[first row][first column] of the
+// wavefront's part.
+// RAW_ROW: sRow holds the plain row scales and the factor 2^-8 that takes the 256 out of the
+// int8 accumulators is applied here (exact).  FENCED: the instruction scheduler may not
+// move code across the pairs of rows, which keeps the registers this function needs at
+// any one time to a few dozen (for a caller that has many values of its own to keep).
+template <typename OUT, int MT, int NT, typename ACC, bool BIAS, bool RAW_ROW = false,
+          bool FENCED = false>
+__device__ __forceinline__ void tile_store_fast(ACC (&acc)[MT][NT], const float* sRow,
+                                                const float* sCol, const float* sBias, int lane,
+                                                int wm, int wn, OUT* __restrict__ wtile,
+                                                long long ld_y) {
+  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+  const unsigned lane_offu = (unsigned)(rquad * (int)ld_y + ccol);
+  float ws[NT], bs[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    ws[j] = sCol[wn * 32 * NT + j * 32 + ccol];
+    bs[j] = sBias[wn * 32 * NT + j * 32 + ccol];
+  }
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 rs4 =
+          *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
+      const float f8 = RAW_ROW ? 0.00390625f : 1.0f;
+      const float rsv[4] = {rs4.x * f8, rs4.y * f8, rs4.z * f8, rs4.w * f8};
+      // Two rows at a time.  The NT column blocks of one row are stored back to back:
+      // together they cover whole cache lines of Y, written within a few instructions of
+      // each other.
+#pragma unroll
+      for (int t = 0; t < 4; t += 2) {
+        OUT* row0 = wtile + (long long)(i * 32 + q * 8 + t) * ld_y + lane_offu;   // uniform + lane
+        OUT* row1 = row0 + ld_y;
+        float y0[NT], y1[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          auto a0 = acc[i][j][4 * q + t], a1 = acc[i][j][4 * q + t + 1];
+          if (FENCED) {
+            // the accumulators are read where they are used (the compiler would otherwise
+            // copy whole 16-register fragments out of the accumulation registers up front)
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[i][j][4 * q + t]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[i][j][4 * q + t + 1]));
+          }
+          y0[j] = ((float)a0 * rsv[t]) * ws[j];
+          y1[j] = ((float)a1 * rsv[t + 1]) * ws[j];
+          if (BIAS) {
+            y0[j] = y0[j] + bs[j];
+            y1[j] = y1[j] + bs[j];
+          }
+        }
+        if constexpr (sizeof(OUT) == 2) {
+          // one packed conversion rounds the two rows' binary32 results to binary16
+          h2v p[NT];
+#pragma unroll
+          for (int j = 0; j < NT; ++j) p[j] = round_pair_to_half(y0[j], y1[j]);
+#pragma unroll
+          for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][0], row0 + j * 32);
+#pragma unroll
+          for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][1], row1 + j * 32);
+        } else {
+#pragma unroll
+          for (int j = 0; j < NT; ++j) store_out<OUT>(row0 + j * 32, y0[j]);
+#pragma unroll
+          for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
+        }
+        if (FENCED) __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+}
+
 // Epilogue of the pipelined kernels.  Register r of a 32x32 accumulator fragment held
 // by lane l is element (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
 template <typename OUT, int MT, int NT, typename ACC = v16i>
@@ -417,64 +515,11 @@ __device__ __forceinline__ void pipe_epilogue(ACC (&acc)[MT][NT], const float* s
   const int ccol = lane & 31, rquad = (lane >> 5) * 4;
   const bool inside = m0 + BM <= M && n0 + BN <= N;
   if (inside && !acc_dump && (long long)(BM + 8) * ld_y < (1ll << 31) / (long long)sizeof(OUT)) {
-    // Fast path: whole tile inside Y.  Every address is a wavefront-uniform row pointer
-    // plus one per-lane 32-bit offset, and the bias branch is taken once, not per element.
-    const unsigned lane_offu = (unsigned)(rquad * (int)ld_y + ccol);
-    auto body = [&](auto with_bias) {
-      float ws[NT], bs[NT];
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        ws[j] = sCol[wn * 32 * NT + j * 32 + ccol];
-        bs[j] = sBias[wn * 32 * NT + j * 32 + ccol];
-      }
-      OUT* wtile = Y + (long long)(m0 + wm * 32 * MT) * ld_y + (n0 + wn * 32 * NT);
-#pragma unroll
-      for (int i = 0; i < MT; ++i) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float4 rs4 =
-              *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
-          const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
-          // Two rows at a time.  The NT column blocks of one row are stored back to
-          // back: together they cover whole cache lines of Y, written within a few
-          // instructions of each other.
-#pragma unroll
-          for (int t = 0; t < 4; t += 2) {
-            OUT* row0 = wtile + (long long)(i * 32 + q * 8 + t) * ld_y + lane_offu;   // uniform + lane
-            OUT* row1 = row0 + ld_y;
-            float y0[NT], y1[NT];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-              y0[j] = ((float)acc[i][j][4 * q + t] * rsv[t]) * ws[j];
-              y1[j] = ((float)acc[i][j][4 * q + t + 1] * rsv[t + 1]) * ws[j];
-              if (decltype(with_bias)::value) {
-                y0[j] = y0[j] + bs[j];
-                y1[j] = y1[j] + bs[j];
-              }
-            }
-            if constexpr (sizeof(OUT) == 2) {
-              // one packed conversion rounds the two rows' binary32 results to binary16
-              h2v p[NT];
-#pragma unroll
-              for (int j = 0; j < NT; ++j) p[j] = round_pair_to_half(y0[j], y1[j]);
-#pragma unroll
-              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][0], row0 + j * 32);
-#pragma unroll
-              for (int j = 0; j < NT; ++j) __builtin_nontemporal_store(p[j][1], row1 + j * 32);
-            } else {
-#pragma unroll
-              for (int j = 0; j < NT; ++j) store_out<OUT>(row0 + j * 32, y0[j]);
-#pragma unroll
-              for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
-            }
-          }
-        }
-      }
-    };
+    OUT* wtile = Y + (long long)(m0 + wm * 32 * MT) * ld_y + (n0 + wn * 32 * NT);
     if (bias)
-      body(std::true_type{});
+      tile_store_fast<OUT, MT, NT, ACC, true>(acc, sRow, sCol, sBias, lane, wm, wn, wtile, ld_y);
     else
-      body(std::false_type{});
+      tile_store_fast<OUT, MT, NT, ACC, false>(acc, sRow, sCol, sBias, lane, wm, wn, wtile, ld_y);
     return;
   }
 #pragma unroll
@@ -811,6 +856,233 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_wide(
                              acc_dump);
 }
 
+// ---------------------------------------------------------------------------
+// Rolling variant of the wide-stage kernel for shapes of many whole tiles (M and N
+// multiples of 256, an even number of 256-code stages): a workgroup is persistent and
+// walks its share of the tiles, and the stream of stages never drains between tiles --
+// the loads of the next tile's first two stages are issued during the current tile's last
+// two, like any other stage's, and the next tile's token-set ids and scales are fetched
+// during those two stages into registers.  What a tile boundary
+// still costs is the output phase itself (the matrix pipe idles while a single wavefront
+// per SIMD converts and stores 256 results per lane); the workgroup launch, the two
+// dependent loads of the scales and the first stage's load latency are gone.
+//
+// Operand addresses are a uniform 64-bit base (tile, stage) plus a 32-bit per-lane offset
+// that does not depend on the tile, so changing tile costs no vector work.
+// Stores and loads share one in-order counter (vmcnt): the only wait for loads that has
+// output stores before it is the first stage barrier of the next tile, about a hundred
+// matrix instructions after the last store was issued.
+// Tile order: as in the other kernels every XCD takes whole rows of tiles; inside an XCD
+// consecutive workgroups take consecutive tiles, so at any time an XCD's CUs work on a
+// few rows of tiles whose operands its L2 holds.
+// ---------------------------------------------------------------------------
+template <typename OUT>
+__global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_roll(
+    const uint8_t* __restrict__ Qx, long long ld_q, const int* __restrict__ gid,
+    const float* __restrict__ scale, int M, int T, int K, int N, int G,
+    const uint8_t* __restrict__ Qw, long long ld_w, const float* __restrict__ w_scale,
+    const float* __restrict__ bias, OUT* __restrict__ Y, long long ld_y, int m_tiles, int n_tiles,
+    double inv_T) {
+  constexpr int MT = 4, NT = 4, BM = 256, BN = 256, NB = MT + NT;
+  constexpr int BKW = 128;                     // packed bytes of K per stage (256 codes)
+  constexpr int SLOT = (BM + BN) * BKW;        // 64 KiB: A rows then B rows, 128 B each
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[2 * SLOT];
+  // scales of the tile being computed and of the next one (sets alternate from tile to
+  // tile), and the next tile's token-set ids
+  __shared__ __attribute__((aligned(256))) float sRow[2][BM], sCol[2][BN], sBias[2][BN];
+  __shared__ __attribute__((aligned(256))) int sGid[BM];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int k_tiles = (K / 2) / BKW;           // even, >= 2 (host)
+
+  // this workgroup's tiles: index list of its XCD, every (gridDim / 8)-th entry
+  const int xcd = blockIdx.x % XCDS, wslot = blockIdx.x / XCDS, per_xcd = gridDim.x / XCDS;
+  const int xcd_tiles = (m_tiles / XCDS) * n_tiles;          // m_tiles is a multiple of 8 (host)
+  const int n_my = wslot < xcd_tiles ? (xcd_tiles - wslot + per_xcd - 1) / per_xcd : 0;
+  if (n_my == 0) return;
+  auto tile_m0 = [&](int it) { return (((wslot + it * per_xcd) / n_tiles) * XCDS + xcd) * BM; };
+  auto tile_n0 = [&](int it) { return ((wslot + it * per_xcd) % n_tiles) * BN; };
+
+  // per-lane byte offsets of this lane's piece of load i (rows 32 i + 8 w + (l >> 3))
+  unsigned offA[2 * MT], offB[2 * NT];
+  {
+    const int rl0 = 8 * wave + (lane >> 3);
+    const int c = (lane & 7) ^ ((rl0 >> 1) & 7);      // logical piece stored at position l & 7
+#pragma unroll
+    for (int i = 0; i < 2 * MT; ++i) offA[i] = (unsigned)((32 * i + rl0) * ld_q + c * 16);
+#pragma unroll
+    for (int i = 0; i < 2 * NT; ++i) offB[i] = (unsigned)((32 * i + rl0) * ld_w + c * 16);
+  }
+  const unsigned ring_base =
+      (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)ring;
+  const unsigned dma_base = __builtin_amdgcn_readfirstlane(ring_base + wave * 1024);
+
+  // uniform operand bases of the current and the next tile
+  const uint8_t* curA = Qx + (long long)tile_m0(0) * ld_q;
+  const uint8_t* curB = Qw + (long long)tile_n0(0) * ld_w;
+  const uint8_t* nxtA = curA;
+  const uint8_t* nxtB = curB;
+  // stage `rel` counted from the current tile's first: past its end it is a stage of the
+  // next tile (or, after the last tile, a harmless re-load into a slot nobody reads)
+  auto dma_piece = [&](int slot, int rel, int e) {      // slot, e compile-time; e = 0 .. 15
+    const bool next = rel >= k_tiles;
+    const long long ko = (long long)(next ? rel - k_tiles : rel) * BKW;
+    if (e < 2 * MT)
+      dma16s((next ? nxtA : curA) + ko, offA[e], dma_base + slot * SLOT + e * 4096);
+    else
+      dma16s((next ? nxtB : curB) + ko, offB[e - 2 * MT],
+             dma_base + slot * SLOT + BM * BKW + (e - 2 * MT) * 4096);
+  };
+
+  // Fragment reads.  Lane (row r' = l & 31, half h = l >> 5) of fragment e reads piece
+  // 2 ks + h of row 32 e + r' (+ the wavefront's offset); the swizzle only depends on r'.
+  // The per-lane LDS address of (operand, ks) is kept in a register; slot and fragment are
+  // added as one opaque base per half-slab plus an immediate, so that the compiler cannot
+  // turn the 64 (slot, ks, fragment) addresses into 64 registers hoisted out of the loops.
+  const int frow = lane & 31, fh = lane >> 5, swz = (frow >> 1) & 7;
+  unsigned a_ks[4], b_ks[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int off = ((2 * ks + fh) ^ swz) * 16;
+    a_ks[ks] = (unsigned)((wm * 128 + frow) * BKW + off);
+    b_ks[ks] = (unsigned)(BM * BKW + (wn * 128 + frow) * BKW + off);
+  }
+  unsigned rd_a = 0, rd_b = 0;               // bases of the half-slab's reads (bytes into the ring)
+  auto read_base = [&](int slot, int ks) {    // slot, ks compile-time
+    rd_a = a_ks[ks] + (unsigned)(slot * SLOT);
+    rd_b = b_ks[ks] + (unsigned)(slot * SLOT);
+    asm volatile("" : "+v"(rd_a), "+v"(rd_b));
+  };
+  auto read_piece = [&](Frags<MT, NT>& f, int e) {   // e compile-time
+    if (e < MT)
+      f.a[e] = *reinterpret_cast<const uint4*>(&ring[rd_a + (unsigned)(e * 4096)]);
+    else
+      f.b[e - MT] = *reinterpret_cast<const uint4*>(&ring[rd_b + (unsigned)((e - MT) * 4096)]);
+  };
+
+  Frags<MT, NT> f0;                         // the two that cross a tile boundary: the first
+  Operands<MT, NT> s0;                      // slab of the next stage, read and half expanded
+  u32 hi;                                   // 0xF0F0F0F0 in a scalar register
+  asm volatile("s_mov_b32 %0, 0xf0f0f0f0" : "=s"(hi));
+
+  // sources that are valid to load from whether or not the optional arrays exist
+  const float* bias_src = bias ? bias : w_scale;
+  const float* gid_src = reinterpret_cast<const float*>(gid ? gid : reinterpret_cast<const int*>(scale));
+  // Scalars of a tile -- token-set id and scale of row tid, scale and bias of column tid --
+  // travel global -> LDS by direct loads as well, so no register holds them while the
+  // matrix stream runs: `ids` and the column entries first; one stage later (the ids have
+  // landed) the row scales that depend on them.  Image of a row: floor((m + 1/2) / T) in
+  // binary64, exact for m, T < 2^31.  An id read from LDS before the first fetch has landed
+  // is clamped into range (its row scale is overwritten before anyone uses it).
+  const unsigned lds_of_wave = (unsigned)(wave * 256);
+  auto lds_addr = [&](const void* ptr) {
+    return __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) const uint8_t*)ptr + lds_of_wave);
+  };
+  auto fetch_ids_cols = [&](int set, int m_first, int n_first) {
+    dma4s(gid_src, gid ? (unsigned)(m_first + tid) * 4u : 0u, lds_addr(sGid));
+    dma4s(w_scale, (unsigned)(n_first + tid) * 4u, lds_addr(sCol[set]));
+    dma4s(bias_src, (unsigned)(n_first + tid) * 4u, lds_addr(sBias[set]));
+  };
+  auto fetch_row_scales = [&](int set, int m_first) {
+    int g = gid ? sGid[tid] : 0;
+    g = g < 0 ? 0 : (g > G - 1 ? G - 1 : g);
+    const int img = (int)(((double)(m_first + tid) + 0.5) * inv_T);
+    dma4s(scale, (unsigned)(img * G + g) * 4u, lds_addr(sRow[set]));
+  };
+
+  // ---- first tile: fill the stream
+  {
+#pragma unroll
+    for (int e = 0; e < 2 * NB; ++e) dma_piece(0, 0, e);
+#pragma unroll
+    for (int e = 0; e < NB; ++e) dma_piece(1, 1, e);
+    fetch_ids_cols(0, tile_m0(0), tile_n0(0));
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    fetch_row_scales(0, tile_m0(0));
+    read_base(0, 0);
+#pragma unroll
+    for (int e = 0; e < NB; ++e) read_piece(f0, e);
+#pragma unroll
+    for (int e = 0; e < NB; ++e) expand_one<0>(s0, f0, e, hi);
+  }
+
+  // One stage; see k_w4a4_gemm_wide.  FIRST: the tile's first stage (fresh accumulators).
+#define TDQ_RSTAGE(kt, CUR, OTH, FIRST, AFTER_BARRIER)                                            \
+  do {                                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    read_base(CUR, 1);                                                                           \
+    half_slab<1, MT, NT, FIRST>(acc, s0, s1, f0, hi, [&](int b) { read_piece(f1, b); });         \
+    half_slab<0>(acc, s1, s0, f1, hi, [&](int b) { dma_piece(OTH, (kt) + 1, NB + b); });         \
+    read_base(CUR, 2);                                                                           \
+    half_slab<1>(acc, s0, s1, f1, hi, [&](int b) { read_piece(f0, b); });                        \
+    half_slab<0>(acc, s1, s0, f0, hi, [&](int) {});                                              \
+    read_base(CUR, 3);                                                                           \
+    half_slab<1>(acc, s0, s1, f0, hi, [&](int b) { read_piece(f1, b); });                        \
+    half_slab<0>(acc, s1, s0, f1, hi, [&](int) {});                                              \
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                  \
+    __syncthreads();                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    AFTER_BARRIER;                                                                               \
+    read_base(OTH, 0);                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    half_slab<1>(acc, s0, s1, f1, hi, [&](int b) { read_piece(f0, b); });                        \
+    half_slab<0>(acc, s1, s0, f0, hi, [&](int b) { dma_piece(CUR, (kt) + 2, b); });              \
+  } while (0)
+
+  for (int it = 0; it < n_my; ++it) {
+    v16i acc[MT][NT];                       // started afresh by the tile's first half-slab
+    Frags<MT, NT> f1;
+    Operands<MT, NT> s1;
+    const int m0 = tile_m0(it), n0 = tile_n0(it);
+    const bool more = it + 1 < n_my;
+    if (more) {
+      nxtA = Qx + (long long)tile_m0(it + 1) * ld_q;
+      nxtB = Qw + (long long)tile_n0(it + 1) * ld_w;
+    }
+    // The next tile's scalars, fetched after EVERY stage barrier (no branch inside the
+    // stream): ids and column entries, and the row scales for the ids that the stage before
+    // delivered -- the last stage's fetches are the ones that count, and they land before
+    // the next tile's first stage barrier, long before its output phase.  After the last
+    // tile they re-fetch its own.
+    const int set = it & 1;
+    const int nm0 = tile_m0(more ? it + 1 : it), nn0 = tile_n0(more ? it + 1 : it);
+    auto fetch_next = [&]() {
+      fetch_row_scales(set ^ 1, nm0);
+      fetch_ids_cols(set ^ 1, nm0, nn0);
+    };
+
+    TDQ_RSTAGE(0, 0, 1, true, fetch_next());
+    TDQ_RSTAGE(1, 1, 0, false, fetch_next());
+    for (int kt = 2; kt < k_tiles; kt += 2) {
+      TDQ_RSTAGE(kt, 0, 1, false, fetch_next());
+      TDQ_RSTAGE(kt + 1, 1, 0, false, fetch_next());
+    }
+    // Output phase of this tile (whole tiles only).  The lane index is made opaque per
+    // tile: everything the output phase derives from it would otherwise be hoisted out of
+    // the tile loop and live in (spilled) registers throughout the matrix stream.
+    {
+      int lane_o = lane;
+      asm volatile("" : "+v"(lane_o));
+      OUT* wtile = Y + (long long)(m0 + wm * 128) * ld_y + (n0 + wn * 128);
+      if (bias)
+        tile_store_fast<OUT, MT, NT, v16i, true, true, true>(acc, sRow[set], sCol[set], sBias[set], lane_o,
+                                                       wm, wn, wtile, ld_y);
+      else
+        tile_store_fast<OUT, MT, NT, v16i, false, true, true>(acc, sRow[set], sCol[set], sBias[set], lane_o,
+                                                        wm, wn, wtile, ld_y);
+    }
+    curA = nxtA;
+    curB = nxtB;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing of ours may still be landing
+#undef TDQ_RSTAGE
+}
+
 template <typename OUT, int MT, int NT>
 static void launch_tile(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale, int M,
                         int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
@@ -852,11 +1124,49 @@ static void launch_wide(const uint8_t* Qx, long long ld_q, const int* gid, const
                      acc_dump, m_tiles, n_tiles);
 }
 
+// Compute units of the current device (0 if the query fails), looked up once per device.
+static int compute_units() {
+  static int cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  int cu = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+  if (cu == 0) {
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    __atomic_store_n(&cached[dev], cu, __ATOMIC_RELAXED);
+  }
+  return cu;
+}
+
+template <typename OUT>
+static void launch_roll(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale, int M,
+                        int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
+                        const float* w_scale, const float* bias, void* Y, long long ld_y, int wgs,
+                        hipStream_t st) {
+  hipLaunchKernelGGL((k_w4a4_gemm_roll<OUT>), dim3(wgs), dim3(GEMM_THREADS), 0, st, Qx, ld_q, gid,
+                     scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, static_cast<OUT*>(Y), ld_y,
+                     M / 256, N / 256, 1.0 / (double)T);
+}
+
 hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, const float* scale,
                             int M, int T, int K, int N, int G, const uint8_t* Qw, long long ld_w,
                             const float* w_scale, const float* bias, void* Y, tdq_dtype y_dt,
                             long long ld_y, int* acc_dump, hipStream_t st) {
   const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  // Whole tiles only, an even number of 256-code stages, rows of tiles in multiples of the
+  // 8 XCDs, and at least 8 tiles for each of one persistent workgroup per CU: the rolling
+  // kernel.  (One workgroup fits a CU, so more workgroups than CUs would run in turns.)
+  if (!acc_dump && M % 256 == 0 && N % 256 == 0 && K % 512 == 0 && (M / 256) % XCDS == 0 &&
+      256ll * ld_q < (1ll << 32) && 256ll * ld_w < (1ll << 32)) {
+    const int wgs = (compute_units() / XCDS) * XCDS;
+    if (wgs >= XCDS && big_tiles >= 8ll * wgs) {
+      if (y_dt == TDQ_F32)
+        launch_roll<float>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y, wgs, st);
+      else
+        launch_roll<_Float16>(Qx, ld_q, gid, scale, M, T, K, N, G, Qw, ld_w, w_scale, bias, Y, ld_y,
+                              wgs, st);
+      return hipGetLastError();
+    }
+  }
   // big tiles once they can fill the 256 CUs at least twice over; the pipelined kernels
   // need whole stages of K: 256 codes (measured 2 to 3 % faster), else 128
   const int mode = big_tiles >= 512 ? (K % 256 == 0 ? 3 : K % 128 == 0 ? 2 : 1) : 0;
@@ -1440,19 +1750,6 @@ hipError_t launch_w4a4_gemm_f6(const uint8_t* A6, const uint8_t* B6, int K, cons
 //   data).  No branch inside the stage: a branch would end the basic block and the
 //   compiler would regroup the instructions.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void dma16s(const uint8_t* sbase, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(voff), "s"(sbase), "s"(lds_base)
-               : "memory");
-}
-// 64 floats from 64 addresses -> 64 consecutive floats of LDS
-__device__ __forceinline__ void dma4s(const float* sbase, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-               :
-               : "v"(voff), "s"(sbase), "s"(lds_base)
-               : "memory");
-}
 
 template <typename OUT>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks_f6(
