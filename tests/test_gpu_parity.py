@@ -651,3 +651,56 @@ def test_quotient_at_rounding_boundaries_f16():
     # image 2 has the unmoved steps: every x is a tie, rounded to the even neighbour
     tie = q_ref.reshape(B, T, C)[2, :, :16]
     assert (tie[:, :15] % 2 == 0).all() and (tie[:, 15] == 7).all()      # 7.5 -> 8, clamped to 7
+
+
+# ------------------------- persistent (rolling) contraction, sampled checks
+@pytest.mark.parametrize("K,out_dtype,with_bias,T,G,ld_pad", [(512, torch.float32, False, 128, 8, 0),
+                                                              (512, torch.float16, True, 4096, 1, 0),
+                                                              (1024, torch.float16, False, 2048, 32, 8),
+                                                              (1536, torch.float32, True, 256, 5, 4),
+                                                              (2048, torch.float16, True, 16384, 3, 0)])
+def test_rolling_contraction_sampled(K, out_dtype, with_bias, T, G, ld_pad):
+    """Shapes of whole 256 x 256 tiles, at least eight for every CU, an even number of
+    256-code stages: the persistent kernel whose stage stream runs across tile boundaries
+    (2, 4, 6 and 8 stages per tile; several images per tile and several tiles per image;
+    one token set without an id array).  Sampled rows of every kind of tile position
+    against the oracle, bit for bit; Y's padding untouched."""
+    M, N = 16384, 8192
+    _say(f"[gemm-roll] M={M} K={K} N={N} out={out_dtype} bias={with_bias} T={T} G={G} ld_pad={ld_pad}")
+    qx = I.random_codes((M, K), 201)
+    qw = I.random_codes((N, K), 202)
+    rng = np.random.Generator(np.random.PCG64(203))
+    B = M // T
+    gid = rng.integers(0, G, (B, T)).astype(np.int32)
+    scale = rng.uniform(0.01, 2.0, (B, G)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    bias = rng.normal(0, 0.5, N).astype(np.float32) if with_bias else None
+    Ybuf = torch.full((M, N + ld_pad), -77.0, dtype=out_dtype, device=U.dev())
+    Y = tdq.tdq_w4a4_linear(U.pack_to_device(qx), None if G == 1 else torch.from_numpy(gid).to(U.dev()),
+                            torch.from_numpy(scale).to(U.dev()), B, T, K, U.pack_to_device(qw),
+                            torch.from_numpy(sw).to(U.dev()),
+                            None if bias is None else torch.from_numpy(bias).to(U.dev()),
+                            out_dtype, out=Ybuf[:, :N])
+    torch.cuda.synchronize()
+    if ld_pad:
+        assert (Ybuf[:, N:] == -77.0).all(), "wrote past the row end"
+    # every tile row of the first and last workgroup rounds, rows at tile and image borders, and
+    # a random sample; all N columns (every tile column)
+    rows = np.unique(np.concatenate([np.arange(0, 16), np.arange(250, 262), np.arange(2040, 2056),
+                                     np.arange(M - 300, M - 250), np.arange(M - 8, M),
+                                     rng.choice(M, 160, replace=False)]))
+    _, Y_ref = O.w4a4_linear(qx[rows], O.row_scales(gid, scale)[rows], qw, sw, bias)
+    if out_dtype == torch.float16:
+        Y_ref = Y_ref.astype(np.float16)
+    Y_gpu = Y[torch.from_numpy(rows).to(U.dev())].cpu().numpy()
+    assert np.array_equal(Y_gpu, Y_ref)
+    # and the whole output against the non-persistent kernels (they take over when an
+    # accumulator dump is asked for), bit for bit
+    acc = torch.empty((M, N), dtype=torch.int32, device=U.dev())
+    Y2 = tdq.tdq_w4a4_linear(U.pack_to_device(qx), None if G == 1 else torch.from_numpy(gid).to(U.dev()),
+                             torch.from_numpy(scale).to(U.dev()), B, T, K, U.pack_to_device(qw),
+                             torch.from_numpy(sw).to(U.dev()),
+                             None if bias is None else torch.from_numpy(bias).to(U.dev()),
+                             out_dtype, acc_dump=acc)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y)
