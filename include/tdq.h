@@ -366,6 +366,29 @@ int tdq_w4a4_linear_blocks_f6(const uint8_t* Qx6, const float* block_scale, int6
                               const float* bias, void* Y, tdq_dtype y_dt, int64_t ld_y, void* stream);
 
 /*
+ * Measurement probes (not part of the method): kernels of known traffic or known
+ * arithmetic, for a benchmark that wants to measure on the device, in the same run, what
+ * the memory system and the execution units sustain beside the published peaks.  One
+ * launch per call, asynchronous; buf is device memory, 16-byte aligned, owned by the caller.
+ *   TDQ_PROBE_READ        reads bytes - 4096 bytes of buf, 16 per thread (bytes a multiple
+ *                         of 4096)
+ *   TDQ_PROBE_COPY        copies the first half of buf to the second (bytes a multiple of
+ *                         8192): bytes / 2 read and bytes / 2 written
+ *   TDQ_PROBE_MFMA_I8     grid workgroups of 4 wavefronts, each issuing iters x 16
+ *                         v_mfma_i32_32x32x32_i8 (65536 integer operations each) on
+ *                         operands taken from buf (its contents choose the data: zeros,
+ *                         random bytes); bytes >= 8192 grid + 4096
+ *   TDQ_PROBE_FMA_1WAVE,  grid workgroups of 256 / 512 / 1024 threads (1 / 2 / 4 wavefronts
+ *   _2WAVES, _4WAVES      per SIMD of a CU), every wavefront issuing iters x 16 independent
+ *                         v_fma_f32; buf holds 128 floats (multiplier, addend per lane),
+ *                         bytes >= 8192
+ * Returns TDQ_OK or TDQ_ERR_NULL / ALIGN / SHAPE / PARAM / HIP.
+ */
+enum { TDQ_PROBE_READ = 0, TDQ_PROBE_COPY = 1, TDQ_PROBE_MFMA_I8 = 2, TDQ_PROBE_FMA_1WAVE = 3,
+       TDQ_PROBE_FMA_2WAVES = 4, TDQ_PROBE_FMA_4WAVES = 5 };
+int tdq_probe(int32_t kind, void* buf, size_t bytes, int32_t iters, int32_t grid, void* stream);
+
+/*
  * Static symmetric per-output-channel weight quantization (Eq. weight_quant),
  * done once offline:  s_o = max(max_i |W_oi|, 1e-8) / 7,
  * Qw = clamp(rint(W / s_o), -8, 7) packed.  W [N, K] fp32 (device),

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtdq.so")
 SOURCES = ["tdq_api.hip", "tdq_act.hip", "tdq_rank.hip", "tdq_blocks.hip", "tdq_layout.hip", "tdq_fused.hip",
-           "tdq_gemm.hip"]
+           "tdq_gemm.hip", "tdq_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -1,0 +1,123 @@
+// Measurement probes: kernels of known traffic or known arithmetic, launched through one
+// C-ABI entry point so that the benchmark can measure, in the same run and on the same
+// device as the method's kernels, what the memory system and the execution units sustain
+// (the second denominators beside the published peaks).  Not part of the method.
+#include "tdq_internal.hpp"
+
+namespace tdq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// One 16-byte load per thread; the result is kept alive by a store that never happens.
+__global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ p, size_t n,
+                                                    unsigned* __restrict__ sink) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    const uint4 v = p[i];
+    if ((v.x ^ v.y ^ v.z ^ v.w) == 0x9E3779B9u && v.x == 0x7F4A7C15u) sink[0] = v.y;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_probe_copy(const uint4* __restrict__ p,
+                                                    uint4* __restrict__ q, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) q[i] = p[i];
+}
+
+// Register-only stream of the int8 matrix instruction of the contraction: a wavefront
+// loads its two operands once (16 bytes per lane each, whatever the buffer holds: zeros
+// or random bytes) and issues iters x 16 independent v_mfma_i32_32x32x32_i8, one
+// wavefront per SIMD (256 accumulator registers).
+__global__ __launch_bounds__(256, 1) void k_probe_mfma_i8(const uint4* __restrict__ src, int iters,
+                                                          int* __restrict__ sink) {
+  const int tid = threadIdx.x;
+  const uint4 qa = src[(size_t)blockIdx.x * 512 + tid], qb = src[(size_t)blockIdx.x * 512 + 256 + tid];
+  const v4i a = {(int)qa.x, (int)qa.y, (int)qa.z, (int)qa.w};
+  const v4i b = {(int)qb.x, (int)qb.y, (int)qb.z, (int)qb.w};
+  v16i acc[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+      acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[t], 0, 0, 0);
+  }
+  int x = 0;
+#pragma unroll
+  for (int t = 0; t < 16; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x ^= acc[t][r];
+  if (x == 0x5bd1e995 && iters < 0) sink[tid] = x;
+}
+
+// Register-only stream of binary32 fused multiply-adds, 16 independent chains per lane
+// (no packed instructions): iters x 16 v_fma_f32 per wavefront.  THREADS = 256 puts one
+// wavefront on every SIMD of a CU, 512 two, 1024 four.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_probe_fma(const float* __restrict__ src, int iters,
+                                                       float* __restrict__ sink) {
+  float c[16];
+  const float m = src[threadIdx.x & 63], a = src[64 + (threadIdx.x & 63)];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) c[t] = (float)t;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) c[t] = __builtin_fmaf(c[t], m, a);
+  }
+  float x = 0.f;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) x += c[t];
+  if (x == 12345.678f && iters < 0) sink[threadIdx.x] = x;
+}
+
+}  // namespace tdq
+
+using namespace tdq;
+
+extern "C" int tdq_probe(int32_t kind, void* buf, size_t bytes, int32_t iters, int32_t grid,
+                         void* stream) {
+  if (!buf) return TDQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(buf) & 15) return TDQ_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (kind) {
+    case TDQ_PROBE_READ: {
+      if (bytes < 4096 || bytes % 4096) return TDQ_ERR_SHAPE;
+      const size_t n = (bytes - 4096) / 16;          // the last 4 KiB hold the sink word
+      hipLaunchKernelGGL(k_probe_read, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                         static_cast<const uint4*>(buf), n,
+                         reinterpret_cast<unsigned*>(static_cast<char*>(buf) + bytes - 4096));
+      break;
+    }
+    case TDQ_PROBE_COPY: {
+      if (bytes < 8192 || bytes % 8192) return TDQ_ERR_SHAPE;
+      const size_t n = bytes / 32;                   // first half -> second half
+      hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                         static_cast<const uint4*>(buf), static_cast<uint4*>(buf) + n, n);
+      break;
+    }
+    case TDQ_PROBE_MFMA_I8: {
+      if (grid < 1 || iters < 1 || bytes < (size_t)grid * 8192 + 4096) return TDQ_ERR_SHAPE;
+      hipLaunchKernelGGL(k_probe_mfma_i8, dim3(grid), dim3(256), 0, st, static_cast<const uint4*>(buf),
+                         iters, reinterpret_cast<int*>(static_cast<char*>(buf) + (size_t)grid * 8192));
+      break;
+    }
+    case TDQ_PROBE_FMA_1WAVE:
+    case TDQ_PROBE_FMA_2WAVES:
+    case TDQ_PROBE_FMA_4WAVES: {
+      if (grid < 1 || iters < 1 || bytes < 8192) return TDQ_ERR_SHAPE;
+      float* f = static_cast<float*>(buf);
+      if (kind == TDQ_PROBE_FMA_1WAVE)
+        hipLaunchKernelGGL(k_probe_fma<256>, dim3(grid), dim3(256), 0, st, f, iters, f + 1024);
+      else if (kind == TDQ_PROBE_FMA_2WAVES)
+        hipLaunchKernelGGL(k_probe_fma<512>, dim3(grid), dim3(512), 0, st, f, iters, f + 1024);
+      else
+        hipLaunchKernelGGL(k_probe_fma<1024>, dim3(grid), dim3(1024), 0, st, f, iters, f + 1024);
+      break;
+    }
+    default: return TDQ_ERR_PARAM;
+  }
+  return hipGetLastError() == hipSuccess ? TDQ_OK : TDQ_ERR_HIP;
+}

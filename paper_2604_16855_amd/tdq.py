@@ -122,6 +122,8 @@ def lib() -> C.CDLL:
     L.tdq_group_diagnostics.restype = C.c_int
     L.tdq_group_diagnostics.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp, vp,
                                         vp, vp, vp, vp]
+    L.tdq_probe.restype = C.c_int
+    L.tdq_probe.argtypes = [C.c_int32, vp, sz, C.c_int32, C.c_int32, vp]
     L.tdq_quantize_weight.restype = C.c_int
     L.tdq_quantize_weight.argtypes = [vp, i32, i32, i64, vp, i64, vp, vp]
     _lib = L
@@ -547,6 +549,15 @@ def tdq_w4a4_linear_blocks_f6(Qx6: torch.Tensor, block_scale: torch.Tensor, K: i
                                          out.data_ptr(), _dt(out), out.stride(0), _stream())
     _check(rc, "tdq_w4a4_linear_blocks_f6")
     return out
+
+
+PROBE_READ, PROBE_COPY, PROBE_MFMA_I8, PROBE_FMA_1WAVE, PROBE_FMA_2WAVES, PROBE_FMA_4WAVES = 0, 1, 2, 3, 4, 5
+
+
+def tdq_probe(kind: int, buf: torch.Tensor, iters: int = 1, grid: int = 1) -> None:
+    """One launch of a measurement probe on `buf` (uint8 device tensor); see tdq.h."""
+    rc = lib().tdq_probe(kind, buf.data_ptr(), buf.numel() * buf.element_size(), iters, grid, _stream())
+    _check(rc, "tdq_probe")
 
 
 def tdq_quantize_weight(W: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -160,6 +160,17 @@ def test_static_scratch_entry_point_rejects_bad_arguments():
     assert re.search(r"#define\s+TDQ_STATIC_SCRATCH_BYTES\s+\(16u << 20\)", src)
 
 
+def test_probe_rejects_bad_arguments():
+    f = tdq.lib().tdq_probe
+    assert f(0, None, 8192, 1, 1, None) == tdq.ERR_NULL
+    assert f(0, FAKE + 4, 8192, 1, 1, None) == tdq.ERR_ALIGN
+    assert f(9, FAKE, 8192, 1, 1, None) == tdq.ERR_PARAM
+    assert f(tdq.PROBE_READ, FAKE, 1000, 1, 1, None) == tdq.ERR_SHAPE
+    assert f(tdq.PROBE_COPY, FAKE, 4096, 1, 1, None) == tdq.ERR_SHAPE
+    assert f(tdq.PROBE_MFMA_I8, FAKE, 8192, 1, 4, None) == tdq.ERR_SHAPE      # 4 workgroups need 36 KiB
+    assert f(tdq.PROBE_FMA_1WAVE, FAKE, 8192, 0, 1, None) == tdq.ERR_SHAPE
+
+
 def test_block_quantizer_rejects_bad_arguments():
     L = tdq.lib()
     f = L.tdq_quantize_act_blocks
