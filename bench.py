@@ -496,24 +496,12 @@ def blocks_leg(layers, torch, tdq, iters=10, warm=5):
                 tt += ev[0].elapsed_time(ev[1])
                 tc += ev[1].elapsed_time(ev[2])
         tt, tc = tt / iters, tc / iters
-        F = torch.empty((tdq.f6_bytes(lc.M, lc.C),), dtype=torch.uint8, device=L.X.device)
-        tc6 = 0.0
-        for it in range(warm + iters):
-            ev[0].record()
-            tdq.tdq_quantize_act_blocks_chw_f6(Xc, p, out=(F, bs))
-            ev[1].record()
-            torch.cuda.synchronize()
-            if it >= warm:
-                tc6 += ev[0].elapsed_time(ev[1])
-        tc6 /= iters
         xb = e * (2 if lc.dtype == "f16" else 4)
         res["layers"][-1]["conv_layout"] = {
             "tokenize_ms": round(tt, 4), "tokenize_gbs": round(2 * xb / (tt * 1e-3) / 1e9, 1),
             "quantize_blocks_chw_ms": round(tc, 4),
-            "quantize_blocks_chw_gbs": round(qbytes / (tc * 1e-3) / 1e9, 1),
-            "quantize_blocks_chw_f6_ms": round(tc6, 4),
-            "quantize_blocks_chw_f6_gbs": round(q6bytes / (tc6 * 1e-3) / 1e9, 1)}
-        del bs, Q, Xt, F
+            "quantize_blocks_chw_gbs": round(qbytes / (tc * 1e-3) / 1e9, 1)}
+        del bs, Q, Xt
     res["ms_per_pass"] = round(tot, 4)
     res["ms_per_pass_f6_route"] = round(tot6, 4)
     # the token-set path overwrote nothing it needs: L.Y is rewritten by the next step

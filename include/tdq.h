@@ -63,6 +63,7 @@ typedef enum {
 /* Largest K of the whole-K contraction: its int32 accumulator holds 256 * acc (the codes
  * enter the matrix instruction as 16 * code), and |acc| <= 64 K, so 2^14 K < 2^31. */
 #define TDQ_MAX_K 131071
+#define TDQ_MAX_IMAGES 65535
 #define TDQ_FUSED_MAX_GROUPS 64 /* most token sets per image of tdq_calibrate_quantize_fused */
 #define TDQ_BLOCK 32 /* channel block g of the per-(token, block) entry points (Sec. 5 setup) */
 
@@ -135,6 +136,8 @@ size_t tdq_workspace_bytes(int32_t B, int32_t T, int32_t C, tdq_dtype dt, const 
  * X        [B*T, ld_x] of dt, ld_x >= C (elements)
  * group_id [B*T] out, clip [B*G] out, scale [B*G] out, stats [B*G] out or NULL.
  * An empty token set gets clip = scale = eps_scale.
+ * Every entry point that takes (B, T, C) refuses B > TDQ_MAX_IMAGES or B T > 2^30 with
+ * TDQ_ERR_SHAPE (images index a 16-bit grid axis of several kernels).
  */
 int tdq_calibrate_groups(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
                          int64_t ld_x, const tdq_params* p, int32_t* group_id, float* clip,
@@ -262,7 +265,7 @@ int tdq_calibrate_quantize_fused(const void* X, tdq_dtype dt, int32_t B, int32_t
                                  void* stream);
 
 /*
- * Diagnostics of the paper's Sec. 3.2 per (image, token set), as exact element counts
+ * Diagnostics of the paper's Sec. 3.1 (Preliminaries) per (image, token set), as exact element counts
  * for the radii and steps given: zero_count = elements whose code is 0 (zero-bin mass
  * rho_0 = zero_count / n, Eq. rho0_def; the code is computed exactly as
  * tdq_quantize_act computes it), clipped_count = elements with |x| > c.  The
@@ -344,13 +347,6 @@ int tdq_w4a4_linear_f6(const uint8_t* Qx6, const int32_t* group_id, const float*
 int tdq_quantize_act_blocks_f6(const void* X, tdq_dtype dt, int32_t B, int32_t T, int32_t C,
                                int64_t ld_x, const tdq_params* p, uint8_t* Qx6, float* block_scale,
                                float* block_clip, int64_t ld_s, void* stream);
-
-/* tdq_quantize_act_blocks_chw writing f6 fragments: X as there, the outputs as from
- * tdq_quantize_act_blocks_f6 on the tokenized map, bit for bit. */
-int tdq_quantize_act_blocks_chw_f6(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
-                                   int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx6,
-                                   float* block_scale, float* block_clip, int64_t ld_s,
-                                   void* stream);
 
 /*
  * tdq_w4a4_linear_blocks on f6-fragment operands: same definition, same bits of Y.  The

@@ -19,6 +19,8 @@ LevelPlan make_level_plan(tdq_dtype dt, int G) {
   while ((G << (max_bits + 1)) <= kHistLdsWords && max_bits + 1 <= kMaxLevelBits) ++max_bits;
   if (max_bits < 1) max_bits = 1;
   int n = (lp.key_bits + max_bits - 1) / max_bits;
+  static_assert(31 <= 5 * kMaxLevels && ((TDQ_MAX_GROUPS << 5) <= kHistLdsWords),
+                "the level arrays must hold the plan of the largest set count");
   lp.n_levels = n;
   int left = lp.key_bits;
   for (int l = 0; l < n; ++l) {
@@ -78,7 +80,7 @@ static int check_params(const tdq_params* p, bool blocks = false) {
 }
 
 static int check_shape(int32_t B, int32_t T, int32_t C, int64_t ld_x) {
-  if (B < 1 || T < 1 || C < 1) return TDQ_ERR_SHAPE;
+  if (B < 1 || T < 1 || C < 1 || B > TDQ_MAX_IMAGES) return TDQ_ERR_SHAPE;
   if (ld_x < C) return TDQ_ERR_SHAPE;
   if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
   return TDQ_OK;
@@ -320,7 +322,7 @@ int tdq_calibrate_groups_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, 
   if (rc != TDQ_OK) return rc;
   rc = check_shape(B, T, C, ld_xt);
   if (rc != TDQ_OK) return rc;
-  if (B > 65535) return TDQ_ERR_SHAPE;
+  if (B > TDQ_MAX_IMAGES) return TDQ_ERR_SHAPE;
   if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T) return TDQ_ERR_SHAPE;
   const int G = p->n_groups;
   const LevelPlan lp = make_level_plan(dt, G);
@@ -411,7 +413,7 @@ int tdq_tokenize_chw(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t 
                      int64_t ld_b, void* Xt, int64_t ld_xt, void* stream) {
   if (!X || !Xt) return TDQ_ERR_NULL;
   if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
-  if (B < 1 || T < 1 || C < 1 || B > 65535) return TDQ_ERR_SHAPE;
+  if (B < 1 || T < 1 || C < 1 || B > TDQ_MAX_IMAGES) return TDQ_ERR_SHAPE;
   if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
   if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T || ld_xt < C) return TDQ_ERR_SHAPE;
   const size_t esz = dt == TDQ_F16 ? 2 : 4;
@@ -482,7 +484,7 @@ int tdq_quantize_act_blocks_chw(const void* X, tdq_dtype dt, int32_t B, int32_t 
   if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
   int rc = check_params(p, true);
   if (rc != TDQ_OK) return rc;
-  if (B < 1 || T < 1 || C < 1 || B > 65535) return TDQ_ERR_SHAPE;
+  if (B < 1 || T < 1 || C < 1 || B > TDQ_MAX_IMAGES) return TDQ_ERR_SHAPE;
   if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
   if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T) return TDQ_ERR_SHAPE;
   const int64_t KB = ((int64_t)C + TDQ_BLOCK - 1) / TDQ_BLOCK;
@@ -494,34 +496,7 @@ int tdq_quantize_act_blocks_chw(const void* X, tdq_dtype dt, int32_t B, int32_t 
   const int kq = block_rank(p->zr);
   const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? block_rank(p->base_pct) : TDQ_BLOCK;
   if (launch_quantize_blocks_chw(X, dt, B, C, T, ld_c, ld_b, kq, kp, make_scalars(p), Qx, ld_q,
-                                 block_scale, block_clip, ld_s, false,
-                                 static_cast<hipStream_t>(stream)) != hipSuccess)
-    return TDQ_ERR_HIP;
-  return TDQ_OK;
-}
-
-int tdq_quantize_act_blocks_chw_f6(const void* X, tdq_dtype dt, int32_t B, int32_t C, int32_t T,
-                                   int64_t ld_c, int64_t ld_b, const tdq_params* p, uint8_t* Qx6,
-                                   float* block_scale, float* block_clip, int64_t ld_s,
-                                   void* stream) {
-  if (!X || !p || !Qx6 || !block_scale) return TDQ_ERR_NULL;
-  if (dt != TDQ_F16 && dt != TDQ_F32) return TDQ_ERR_DTYPE;
-  int rc = check_params(p, true);
-  if (rc != TDQ_OK) return rc;
-  if (B < 1 || T < 1 || C < 1 || B > 65535) return TDQ_ERR_SHAPE;
-  if ((int64_t)B * T > (int64_t)1 << 30) return TDQ_ERR_SHAPE;
-  if (ld_c < T || ld_b < (int64_t)(C - 1) * ld_c + T) return TDQ_ERR_SHAPE;
-  const int64_t KB = ((int64_t)C + TDQ_BLOCK - 1) / TDQ_BLOCK;
-  if (ld_s < KB) return TDQ_ERR_SHAPE;
-  const size_t esz = dt == TDQ_F16 ? 2 : 4;
-  if (reinterpret_cast<uintptr_t>(X) % esz) return TDQ_ERR_ALIGN;
-  if (reinterpret_cast<uintptr_t>(Qx6) & 15) return TDQ_ERR_ALIGN;
-  if ((reinterpret_cast<uintptr_t>(block_scale) | reinterpret_cast<uintptr_t>(block_clip)) & 3)
-    return TDQ_ERR_ALIGN;
-  const int kq = block_rank(p->zr);
-  const int kp = (p->base_pct > 0.0 && p->base_pct < 1.0) ? block_rank(p->base_pct) : TDQ_BLOCK;
-  if (launch_quantize_blocks_chw(X, dt, B, C, T, ld_c, ld_b, kq, kp, make_scalars(p), Qx6, 0,
-                                 block_scale, block_clip, ld_s, true,
+                                 block_scale, block_clip, ld_s,
                                  static_cast<hipStream_t>(stream)) != hipSuccess)
     return TDQ_ERR_HIP;
   return TDQ_OK;

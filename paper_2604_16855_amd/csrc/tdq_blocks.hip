@@ -541,13 +541,7 @@ hipError_t launch_quantize_blocks_f6(const void* X, tdq_dtype dt, long long M, i
 // reads; rows 8 bytes longer than the data keep them to two-way bank conflicts) and
 // runs block_core.  Codes and steps are token-major, as from the token-major sweep.
 // ---------------------------------------------------------------------------
-// F6: the codes leave as f6 fragments (Q is then the fragment buffer, ld_q unused), as
-// from k_quantize_blocks_f6: the nibble words of a tile (TT tokens x TC / 32 blocks) are
-// staged in LDS and every thread turns (token, block) entries into 24 bytes of bf6
-// patterns at the place of the entry's row and half in its fragment.  Rows of the last
-// row block past B T are written as zeros by the workgroup of the last tile of the last
-// image; blocks past ceil(C / 32) are zero codes of the tile that covers them.
-template <typename T, int TC, bool F6>
+template <typename T, int TC>
 __global__ __launch_bounds__(256) void k_quantize_blocks_chw(
     const T* __restrict__ X, long long ld_c, long long ld_b, int C, int T_, int vin_ok, int q_vec_ok,
     int kq, int kp, Scalars sc, uint8_t* __restrict__ Q, long long ld_q, float* __restrict__ bscale,
@@ -559,9 +553,7 @@ __global__ __launch_bounds__(256) void k_quantize_blocks_chw(
   constexpr int TT = 16 * E;                               // tokens per tile
   constexpr int PITCH = TT + 8 / (int)sizeof(T);
   constexpr int QPT = TC / (kBlk * NB);                    // quads per token and tile
-  constexpr int TB = TC / kBlk;                            // blocks per tile
   __shared__ __attribute__((aligned(16))) T tile[TC][PITCH];
-  __shared__ __attribute__((aligned(16))) u32 sN[F6 ? TB * TT * 4 : 4];   // [block][token][4 words]
 
   const int t0 = blockIdx.x * TT, b = blockIdx.y;
   const int tid = threadIdx.x, ql = tid & 3;
@@ -618,55 +610,12 @@ __global__ __launch_bounds__(256) void k_quantize_blocks_chw(
 #pragma unroll
       for (int s = 0; s < NB; ++s) {
         const int kb = c0 / kBlk + sub * NB + s;
-        if constexpr (F6) {
-          const bool ok = tok_ok && kb < KB;
-          if (ok && ql == s) {
-            bscale[row * ld_s + kb] = ds[s];
-            if (bclip) bclip[row * ld_s + kb] = cs[s];
-          }
-          sN[((sub * NB + s) * TT + tl) * 4 + ql] = ok ? word[s] : 0u;
-        } else {
-          if (tok_ok && kb < KB)
-            block_store(word[s], cs[s], ds[s], ql == s, row, kb, ql, C, q_vec_ok, Q, ld_q, bscale,
-                        bclip, ld_s);
-        }
+        if (tok_ok && kb < KB)
+          block_store(word[s], cs[s], ds[s], ql == s, row, kb, ql, C, q_vec_ok, Q, ld_q, bscale,
+                      bclip, ld_s);
       }
     }
     __syncthreads();
-    if constexpr (F6) {
-      const long long M = (long long)gridDim.y * T_;
-      const int KB64 = 2 * ((C + 127) / 128);
-      auto put = [&](long long row, int blk, const uint4& w4) {
-        const u32 w[4] = {w4.x, w4.y, w4.z, w4.w};
-        blk_v16f ev, od;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const u32 wd = w[i >> 2];
-          const int sh = 8 * (i & 3);                      // codes 2 i and 2 i + 1: bits sh, sh + 4
-          ev[i] = (float)((int)(wd << (28 - sh)) >> 28);
-          od[i] = (float)((int)(wd << (24 - sh)) >> 28);
-        }
-        const blk_v6i r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(ev, od, 1.0f);
-        const int kb64 = (c0 / kBlk + blk) >> 1;
-        const long long l = (row & 31) + 32 * ((c0 / kBlk + blk) & 1);
-        uint2* dst = reinterpret_cast<uint2*>(Q + (((row >> 5) * KB64 + kb64) * 64 + l) * 24);
-        dst[0] = make_uint2((u32)r[0], (u32)r[1]);
-        dst[1] = make_uint2((u32)r[2], (u32)r[3]);
-        dst[2] = make_uint2((u32)r[4], (u32)r[5]);
-      };
-      for (int e = tid; e < TB * TT; e += 256) {
-        const int blk = e / TT, tl = e % TT;
-        if (t0 + tl < T_)
-          put((long long)b * T_ + t0 + tl, blk, *reinterpret_cast<const uint4*>(&sN[(blk * TT + tl) * 4]));
-      }
-      // zero rows that fill the last row block
-      if (b == (int)gridDim.y - 1 && t0 + TT >= T_) {
-        const int pad = (int)(((M + 31) & ~31ll) - M);
-        for (int e = tid; e < pad * TB; e += 256)
-          put(M + e / TB, e % TB, make_uint4(0u, 0u, 0u, 0u));
-      }
-      // (the next tile's passes write sN only after the barrier that follows its loads)
-    }
   }
 }
 
@@ -674,7 +623,7 @@ template <typename T>
 static hipError_t quantize_blocks_chw_t(const T* X, int B, int C, int T_, long long ld_c,
                                         long long ld_b, int kq, int kp, const Scalars& sc,
                                         uint8_t* Q, long long ld_q, float* bscale, float* bclip,
-                                        long long ld_s, bool f6, hipStream_t st) {
+                                        long long ld_s, hipStream_t st) {
   constexpr int E = 16 / (int)sizeof(T);
   const int vin_ok =
       ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld_c % E == 0 && ld_b % E == 0) ? 1 : 0;
@@ -682,24 +631,20 @@ static hipError_t quantize_blocks_chw_t(const T* X, int B, int C, int T_, long l
   const dim3 grid((unsigned)((T_ + 16 * E - 1) / (16 * E)), (unsigned)B);
   // 128-channel tiles: 256-channel ones (whole 128-byte lines of codes per token) measured
   // 20 % slower, with half as many workgroups per CU to hide the tile loads
-  if (f6)
-    hipLaunchKernelGGL((k_quantize_blocks_chw<T, 128, true>), grid, dim3(256), 0, st, X, ld_c, ld_b, C,
-                       T_, vin_ok, q_vec_ok, kq, kp, sc, Q, ld_q, bscale, bclip, ld_s);
-  else
-    hipLaunchKernelGGL((k_quantize_blocks_chw<T, 128, false>), grid, dim3(256), 0, st, X, ld_c, ld_b, C,
-                       T_, vin_ok, q_vec_ok, kq, kp, sc, Q, ld_q, bscale, bclip, ld_s);
+  hipLaunchKernelGGL((k_quantize_blocks_chw<T, 128>), grid, dim3(256), 0, st, X, ld_c, ld_b, C, T_,
+                     vin_ok, q_vec_ok, kq, kp, sc, Q, ld_q, bscale, bclip, ld_s);
   return hipGetLastError();
 }
 
 hipError_t launch_quantize_blocks_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                       long long ld_b, int kq, int kp, const Scalars& sc, uint8_t* Q,
                                       long long ld_q, float* bscale, float* bclip, long long ld_s,
-                                      bool f6, hipStream_t st) {
+                                      hipStream_t st) {
   if (dt == TDQ_F16)
     return quantize_blocks_chw_t<u16>(static_cast<const u16*>(X), B, C, T, ld_c, ld_b, kq, kp, sc, Q,
-                                      ld_q, bscale, bclip, ld_s, f6, st);
+                                      ld_q, bscale, bclip, ld_s, st);
   return quantize_blocks_chw_t<float>(static_cast<const float*>(X), B, C, T, ld_c, ld_b, kq, kp, sc, Q,
-                                      ld_q, bscale, bclip, ld_s, f6, st);
+                                      ld_q, bscale, bclip, ld_s, st);
 }
 
 }  // namespace tdq

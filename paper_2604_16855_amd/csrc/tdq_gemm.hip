@@ -1451,9 +1451,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void k_w4a4_gemm_blocks(
     }
 }
 
-#ifndef TDQ_BLK_SBY
-#define TDQ_BLK_SBY 128
-#endif
+constexpr int kBlkStageBytes = 128;      // packed bytes of K per stage of the block-scaled kernel
 hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const float* bscale,
                                    long long ld_s, int M, int K, int N, const uint8_t* Qw,
                                    long long ld_w, const float* w_scale, const float* bias, void* Y,
@@ -1462,11 +1460,11 @@ hipError_t launch_w4a4_gemm_blocks(const uint8_t* Qx, long long ld_q, const floa
   const long long m_groups = (m_tiles + XCDS - 1) / XCDS;
   const unsigned grid = (unsigned)(m_groups * XCDS * n_tiles);
   if (y_dt == TDQ_F32)
-    hipLaunchKernelGGL((k_w4a4_gemm_blocks<float, TDQ_BLK_SBY>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q,
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks<float, kBlkStageBytes>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx, ld_q,
                        bscale, ld_s, M, K, N, Qw, ld_w, w_scale, bias, static_cast<float*>(Y), ld_y,
                        m_tiles, n_tiles);
   else
-    hipLaunchKernelGGL((k_w4a4_gemm_blocks<_Float16, TDQ_BLK_SBY>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx,
+    hipLaunchKernelGGL((k_w4a4_gemm_blocks<_Float16, kBlkStageBytes>), dim3(grid), dim3(GEMM_THREADS), 0, st, Qx,
                        ld_q, bscale, ld_s, M, K, N, Qw, ld_w, w_scale, bias,
                        static_cast<_Float16*>(Y), ld_y, m_tiles, n_tiles);
   return hipGetLastError();

@@ -13,7 +13,8 @@ namespace tdq {
 constexpr int kQMax = 7;
 constexpr int kQMin = -8;
 constexpr int kOctaveFloor = 24;       // assignment: keys > 24 octaves below the top share set 0
-constexpr int kMaxLevels = 6;          // radix-select levels (31-bit key / >= 6 bits per level)
+constexpr int kMaxLevels = 7;          // radix-select levels: a 31-bit key at >= 5 bits per level
+                                       // (256 sets x 2^5 bins fill the LDS histogram)
 constexpr int kHistLdsWords = 8192;    // 32 KiB of LDS histogram per workgroup
 constexpr int kMaxLevelBits = 11;
 
@@ -148,7 +149,7 @@ hipError_t launch_quantize_blocks_f6(const void* X, tdq_dtype dt, long long M, i
 hipError_t launch_quantize_blocks_chw(const void* X, tdq_dtype dt, int B, int C, int T, long long ld_c,
                                       long long ld_b, int kq, int kp, const Scalars& sc, uint8_t* Q,
                                       long long ld_q, float* bscale, float* bclip, long long ld_s,
-                                      bool f6, hipStream_t st);
+                                      hipStream_t st);
 hipError_t launch_fused_small(const void* X, tdq_dtype dt, int B, int T, int C, long long ld, int G,
                               const Scalars& sc, float* r, double* mean, double* m2, int* gid,
                               float* clip, float* scale, tdq_group_stats* stats,

@@ -87,9 +87,6 @@ def lib() -> C.CDLL:
     L.tdq_quantize_act_blocks_f6.restype = C.c_int
     L.tdq_quantize_act_blocks_f6.argtypes = [vp, C.c_int, i32, i32, i32, i64, C.POINTER(Params), vp,
                                              vp, vp, i64, vp]
-    L.tdq_quantize_act_blocks_chw_f6.restype = C.c_int
-    L.tdq_quantize_act_blocks_chw_f6.argtypes = [vp, C.c_int, i32, i32, i32, i64, i64, C.POINTER(Params),
-                                                 vp, vp, vp, i64, vp]
     L.tdq_w4a4_linear_blocks.restype = C.c_int
     L.tdq_w4a4_linear_blocks.argtypes = [vp, i64, vp, i64, i64, i32, i32, vp, i64, vp, vp, vp,
                                          C.c_int, i64, vp]
@@ -358,39 +355,9 @@ def tdq_quantize_act_blocks_chw(X: torch.Tensor, p: Params, want_clip: bool = Fa
     return Qx, bs, bc
 
 
-def tdq_quantize_act_blocks_chw_f6(X: torch.Tensor, p: Params, want_clip: bool = False,
-                                   out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
-    """tdq_quantize_act_blocks_f6 on a feature map X[B, C, H, W] read in place:
-    -> (Qx6[f6_bytes(B*H*W, C)], block_scale[B*H*W, KB], block_clip or None)."""
-    B, Cc, T, ld_c, ld_b = _bct(X)
-    KB = (Cc + 31) // 32
-    if out is None:
-        Qx6 = torch.empty((f6_bytes(B * T, Cc),), dtype=torch.uint8, device=X.device)
-        bs = torch.empty((B * T, KB), dtype=torch.float32, device=X.device)
-    else:
-        Qx6, bs = out
-    if Qx6.numel() < f6_bytes(B * T, Cc):
-        raise ValueError("Qx6 is too small")
-    bc = torch.empty((B * T, KB), dtype=torch.float32, device=X.device) if want_clip else None
-    rc = lib().tdq_quantize_act_blocks_chw_f6(X.data_ptr(), _dt(X), B, Cc, T, ld_c, ld_b, C.byref(p),
-                                              Qx6.data_ptr(), bs.data_ptr(), _ptr(bc), bs.stride(0),
-                                              _stream())
-    _check(rc, "tdq_quantize_act_blocks_chw_f6")
-    return Qx6, bs, bc
-
-
 def tdq_tokenize_chw(X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """X[B, C, H, W] (or [B, C, T]) with contiguous spatial axes -> Xt[B, H*W, C]."""
-    if X.dim() == 4:
-        if X.stride(3) != 1 or X.stride(2) != X.shape[3]:
-            raise ValueError("the spatial axes of X must be contiguous")
-        B, Cc, T = X.shape[0], X.shape[1], X.shape[2] * X.shape[3]
-    elif X.dim() == 3 and X.stride(2) == 1:
-        B, Cc, T = X.shape
-    else:
-        raise ValueError("X must be [B, C, H, W] or [B, C, T] with contiguous tokens")
-    ld_c = X.stride(1) if Cc > 1 else T
-    ld_b = X.stride(0) if B > 1 else max((Cc - 1) * ld_c + T, 1)
+    B, Cc, T, ld_c, ld_b = _bct(X)
     if out is None:
         out = torch.empty((B, T, Cc), dtype=X.dtype, device=X.device)
     rc = lib().tdq_tokenize_chw(X.data_ptr(), _dt(X), B, Cc, T, ld_c, ld_b, out.data_ptr(),

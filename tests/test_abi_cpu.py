@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported():
             "tdq_calibrate_quantize_fused", "tdq_range_disparity",
             "tdq_calibrate_groups_chw", "tdq_calibrate_groups_static", "tdq_w4a4_linear_f6", "tdq_quantize_act_f6",
             "tdq_pack_codes_f6", "tdq_f6_bytes", "tdq_w4a4_linear_blocks_f6",
-            "tdq_quantize_act_blocks_f6", "tdq_quantize_act_blocks_chw_f6",
+            "tdq_quantize_act_blocks_f6",
             "tdq_quantize_weight", "tdq_workspace_bytes", "tdq_version",
             "tdq_status_string", "tdq_default_params"} <= set(names)
     L = tdq.lib()
@@ -64,6 +64,8 @@ def test_workspace_bytes():
     assert tdq.workspace_bytes(32, 4096, 1024, tdq.TDQ_F16, tdq.default_params(32)) > \
         tdq.workspace_bytes(1, 4096, 1024, tdq.TDQ_F16, tdq.default_params(32))
     assert tdq.workspace_bytes(0, 10, 10, tdq.TDQ_F16, p) == 0
+    assert tdq.workspace_bytes(65536, 10, 10, tdq.TDQ_F16, p) == 0
+    assert tdq.workspace_bytes(65535, 10, 10, tdq.TDQ_F16, p) > 0
     assert tdq.workspace_bytes(1, 10, 10, 7, p) == 0
     bad = tdq.default_params(n_groups=0)
     assert tdq.workspace_bytes(1, 10, 10, tdq.TDQ_F16, bad) == 0
@@ -85,6 +87,7 @@ def test_calibrate_rejects_bad_arguments():
     assert _calib(p, ws=None) == tdq.ERR_NULL
     assert _calib(p, dt=5) == tdq.ERR_DTYPE
     assert _calib(p, B=0) == tdq.ERR_SHAPE
+    assert _calib(p, B=65536) == tdq.ERR_SHAPE          # images index a 16-bit grid axis
     assert _calib(p, ld=7) == tdq.ERR_SHAPE
     assert _calib(p, wsb=16) == tdq.ERR_WORKSPACE
     assert _calib(p, ws=FAKE + 8) == tdq.ERR_WORKSPACE
@@ -358,14 +361,6 @@ def test_f6_entries_reject_bad_arguments():
     assert qb(FAKE, 0, 1, 8, 64, 64, C.byref(pb), FAKE + 8, FAKE, None, 2, None) == tdq.ERR_ALIGN
     assert qb(FAKE, 5, 1, 8, 64, 64, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_DTYPE
     assert qb(FAKE, 0, 1, 8, 64, 64, C.byref(p), FAKE, FAKE, None, 2, None) == tdq.ERR_UNSUPPORTED   # chan_group 0: the token-set path
-    qc = L.tdq_quantize_act_blocks_chw_f6
-    assert qc(None, 0, 1, 64, 8, 8, 512, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_NULL
-    assert qc(FAKE, 0, 1, 64, 8, 8, 512, C.byref(pb), None, FAKE, None, 2, None) == tdq.ERR_NULL
-    assert qc(FAKE, 0, 1, 64, 8, 7, 512, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_SHAPE   # ld_c < T
-    assert qc(FAKE, 0, 1, 64, 8, 8, 100, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_SHAPE   # ld_b too small
-    assert qc(FAKE, 0, 1, 64, 8, 8, 512, C.byref(pb), FAKE, FAKE, None, 1, None) == tdq.ERR_SHAPE   # two blocks
-    assert qc(FAKE, 0, 1, 64, 8, 8, 512, C.byref(pb), FAKE + 4, FAKE, None, 2, None) == tdq.ERR_ALIGN
-    assert qc(FAKE, 0, 70000, 64, 8, 8, 512, C.byref(pb), FAKE, FAKE, None, 2, None) == tdq.ERR_SHAPE
     gb = L.tdq_w4a4_linear_blocks_f6
     okb = dict(Qx=FAKE, ds=FAKE, ld_s=2, M=8, K=64, N=8, Qw=FAKE, ws=FAKE, bias=None, Y=FAKE, ydt=1, ld_y=8)
 

@@ -171,33 +171,3 @@ def test_token_set_calibration_reads_conv_layout(B, C, H, W, dtype, G):
     exact = np.array_equal(g["scale"], osc) and np.array_equal(g["clip"], oc)
     U.assert_codes_match(U.unpack_device_codes(Q, C), q_ref, Xt_ref, oc[rows, og].reshape(-1),
                          osc[rows, og].reshape(-1), exact)
-
-
-@pytest.mark.parametrize("B,C,H,W,dtype,variant", [
-    (2, 96, 12, 12, np.float16, (3, 1.0, 0.2, 0.0)),      # T = 144: one full token tile and a ragged one
-    (2, 80, 127, 1, np.float16, (3, 1.0, 0.2, 0.0)),      # B T = 254: two padding rows, one token of slack
-    (3, 200, 5, 7, np.float16, (2, 1.0, 0.6, 0.0)),       # C = 200: blocks 7 of 8 real in the second channel tile
-    (1, 33, 9, 9, np.float16, (3, 1.0, 0.2, 0.9)),        # odd C
-    (2, 128, 16, 16, np.float16, (3, 1.0, 0.2, 0.0)),     # whole tiles
-    (2, 72, 10, 9, np.float32, (3, 2.0, 0.1, 0.0)),
-    (1, 260, 8, 8, np.float32, (1, 0.3, 0.2, 0.0)),
-])
-def test_quantize_blocks_chw_f6_equals_the_other_routes(B, C, H, W, dtype, variant):
-    """tdq_quantize_act_blocks_chw_f6: steps and radii of tdq_quantize_act_blocks_chw bit
-    for bit, and the fragments tdq_quantize_act_blocks_f6 writes for the tokenized map
-    (every byte, the zero padding included)."""
-    flags, tau, zr, base_pct = variant
-    _say(f"[chw-f6] B={B} C={C} H={H} W={W} dtype={dtype.__name__} variant={variant}")
-    X = _feature_map(B, C, H, W, dtype, 7)
-    p = tdq.block_params(tau, zr, flags, base_pct)
-    Xd = torch.from_numpy(X).to(U.dev())
-    T = H * W
-    Q, bs, bc = tdq.tdq_quantize_act_blocks_chw(Xd, p, want_clip=True)
-    F = torch.full((tdq.f6_bytes(B * T, C),), 0xA5, dtype=torch.uint8, device=U.dev())   # all must be written
-    bs6 = torch.full_like(bs, float("nan"))
-    F, bs6, bc6 = tdq.tdq_quantize_act_blocks_chw_f6(Xd, p, want_clip=True, out=(F, bs6))
-    Ft, bst, _ = tdq.tdq_quantize_act_blocks_f6(tdq.tdq_tokenize_chw(Xd), p)
-    torch.cuda.synchronize()
-    assert torch.equal(bs6, bs) and torch.equal(bc6, bc) and torch.equal(bst, bs)
-    assert torch.equal(F, tdq.tdq_pack_codes_f6(Q, C))
-    assert torch.equal(F, Ft)

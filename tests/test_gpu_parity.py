@@ -476,6 +476,21 @@ def test_rank_select_shapes(T, C, G):
     U.assert_calibration_matches(g, X, p)
 
 
+@pytest.mark.parametrize("G,exact", [(128, 0), (129, 0), (200, 0), (256, 0), (256, 256)])
+def test_radix_levels_many_sets_f32(G, exact):
+    """binary32 input with more than 128 sets per image: 2^5 bins per set are all the LDS
+    histogram holds, so the 31-bit key takes seven radix levels (six up to 128 sets).
+    Orders of magnitude between tokens, so that the digits of every level matter."""
+    _say(f"[radix-levels] G={G} exact={exact}")
+    rng = np.random.Generator(np.random.PCG64(900 + G))
+    X = (rng.laplace(0, 1, (2, 1200, 40)) * rng.lognormal(0, 2.5, (2, 1200, 1))).astype(np.float32)
+    p = tdq.default_params(G)
+    p.flags |= exact
+    g = U.gpu_calibrate(X, p)
+    assert g["status"] == 0
+    U.assert_calibration_matches(g, X, p)
+
+
 # ------------------------------------------------- percentile base radius Q_p
 @pytest.mark.parametrize("case,pct,flags,extra", [("cfg2_fc2", 0.99, 3, 0), ("cfg2_qkv", 0.5, 0, 0),
                                                   ("cfg0", 0.99, 3, 0), ("cfg0", 0.9, 0, 0),
