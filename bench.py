@@ -31,13 +31,13 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
 # Vector lane operations per second.  The published fp32 vector peak, 157.3 TFLOP/s, is
 # 256 CUs x 4 SIMDs x 32 lanes x 2 flops x 2.4 GHz: 32 binary32 lane-operations per clock
-# and SIMD.  The `probes` leg measures what unpacked v_fma_f32 reaches on this device (two
-# wavefronts per SIMD come close to it, one wavefront per SIMD issues at well under half).
+# and SIMD.  The `probes` leg measures what unpacked v_fma_f32 reaches on this device (four
+# wavefronts per SIMD reach about 0.7 of it, two about 0.5, one about 0.27).
 PEAK_VALU_TLOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # HBM bytes per launch of the fc1 contraction on the default workload: NOT measured by this
 # run but imported from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command (scaled on the 1 GiB copy of the probes leg), profiles/bench_cfg4_hbm_traffic_pmc.txt
-GEMM_FC1_TRAFFIC_BYTES = 1182249898
+GEMM_FC1_TRAFFIC_BYTES = 1159614736
 GEMM_FC1_TRAFFIC_SOURCE = "profiles/bench_cfg4_hbm_traffic_pmc.txt"
 
 

@@ -61,8 +61,11 @@ typedef enum {
 
 #define TDQ_MAX_GROUPS 256
 /* Largest K of the whole-K contraction: its int32 accumulator holds 256 * acc (the codes
- * enter the matrix instruction as 16 * code), and |acc| <= 64 K, so 2^14 K < 2^31. */
+ * enter the matrix instruction as 16 * code), and |acc| <= 64 K, so 2^14 K < 2^31:
+ * tdq_w4a4_linear refuses more with TDQ_ERR_SHAPE.  (The block-scaled and the f6 entry
+ * points accumulate per block or in binary32 and take K up to 131072.) */
 #define TDQ_MAX_K 131071
+/* Largest B: images index a 16-bit grid axis of several kernels. */
 #define TDQ_MAX_IMAGES 65535
 #define TDQ_FUSED_MAX_GROUPS 64 /* most token sets per image of tdq_calibrate_quantize_fused */
 #define TDQ_BLOCK 32 /* channel block g of the per-(token, block) entry points (Sec. 5 setup) */

@@ -119,6 +119,16 @@ def test_block_quantizer_variants(flags, tau, zr, base_pct, dtype):
     _check_block_quantizer(X, tdq.block_params(tau, zr, flags, base_pct))
 
 
+@pytest.mark.parametrize("dtype,ratio", [("f16", 10.0), ("f16", 100.0), ("f16", 1000.0),
+                                         ("f32", 10.0), ("f32", 1000.0)])
+def test_block_quantizer_on_offset_data(dtype, ratio):
+    """Blocks far from zero mean (mean / sigma up to 1000) with C1 only: every step is
+    tau * sigma of its 32 values (Eq. tau_constraint), so the block dispersion must hold
+    the 1e-6 bar where a one-pass variance in binary32 would not."""
+    X = I.offset_activations(2, 70, 200, dtype, ratio, seed=11 + int(ratio), token_jitter=0.05)
+    _check_block_quantizer(X, tdq.block_params(1.0, 0.2, tdq.FLAG_C1, 0.0), ld_pad=8)
+
+
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
 def test_block_quantizer_degenerate_blocks(dtype):
     """All-zero blocks (eps floors), constant blocks (sigma = eps_std), ties at the rank,
