@@ -1044,24 +1044,22 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_roll(
       nxtA = Qx + (long long)tile_m0(it + 1) * ld_q;
       nxtB = Qw + (long long)tile_n0(it + 1) * ld_w;
     }
-    // The next tile's scalars, fetched after EVERY stage barrier (no branch inside the
-    // stream): ids and column entries, and the row scales for the ids that the stage before
-    // delivered -- the last stage's fetches are the ones that count, and they land before
-    // the next tile's first stage barrier, long before its output phase.  After the last
-    // tile they re-fetch its own.
+    // The next tile's scalars are fetched in this tile's last two stages (straight-line
+    // code: the stages before and inside the loop simply carry no fetch) and land before the
+    // next tile's first stage barrier, long before its output phase.  After the last tile
+    // they re-fetch its own.
     const int set = it & 1;
     const int nm0 = tile_m0(more ? it + 1 : it), nn0 = tile_n0(more ? it + 1 : it);
-    auto fetch_next = [&]() {
-      fetch_row_scales(set ^ 1, nm0);
-      fetch_ids_cols(set ^ 1, nm0, nn0);
-    };
-
-    TDQ_RSTAGE(0, 0, 1, true, fetch_next());
-    TDQ_RSTAGE(1, 1, 0, false, fetch_next());
-    for (int kt = 2; kt < k_tiles; kt += 2) {
-      TDQ_RSTAGE(kt, 0, 1, false, fetch_next());
-      TDQ_RSTAGE(kt + 1, 1, 0, false, fetch_next());
+    TDQ_RSTAGE(0, 0, 1, true, (void)0);
+    TDQ_RSTAGE(1, 1, 0, false, (void)0);
+    for (int kt = 2; kt < k_tiles - 2; kt += 2) {
+      TDQ_RSTAGE(kt, 0, 1, false, (void)0);
+      TDQ_RSTAGE(kt + 1, 1, 0, false, (void)0);
     }
+    // the tile's last two stages carry the fetches: ids and column entries first, one stage
+    // (and its barrier's wait for every load) later the row scales that read the ids
+    TDQ_RSTAGE(k_tiles - 2, 0, 1, false, fetch_ids_cols(set ^ 1, nm0, nn0));
+    TDQ_RSTAGE(k_tiles - 1, 1, 0, false, fetch_row_scales(set ^ 1, nm0));
     // Output phase of this tile (whole tiles only).  The lane index is made opaque per
     // tile: everything the output phase derives from it would otherwise be hoisted out of
     // the tile loop and live in (spilled) registers throughout the matrix stream.
@@ -1155,7 +1153,7 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
   // Whole tiles only, an even number of 256-code stages, rows of tiles in multiples of the
   // 8 XCDs, and at least 8 tiles for each of one persistent workgroup per CU: the rolling
   // kernel.  (One workgroup fits a CU, so more workgroups than CUs would run in turns.)
-  if (!acc_dump && M % 256 == 0 && N % 256 == 0 && K % 512 == 0 && (M / 256) % XCDS == 0 &&
+  if (!acc_dump && M % 256 == 0 && N % 256 == 0 && K % 512 == 0 && K >= 1024 && (M / 256) % XCDS == 0 &&
       256ll * ld_q < (1ll << 32) && 256ll * ld_w < (1ll << 32)) {
     const int wgs = (compute_units() / XCDS) * XCDS;
     if (wgs >= XCDS && big_tiles >= 8ll * wgs) {

@@ -669,7 +669,8 @@ def test_quotient_at_rounding_boundaries_f16():
 
 
 # ------------------------- persistent (rolling) contraction, sampled checks
-@pytest.mark.parametrize("K,out_dtype,with_bias,T,G,ld_pad", [(512, torch.float32, False, 128, 8, 0),
+@pytest.mark.parametrize("K,out_dtype,with_bias,T,G,ld_pad", [(1024, torch.float32, False, 128, 8, 0),
+                                                              (3072, torch.float16, True, 4096, 1, 0),
                                                               (512, torch.float16, True, 4096, 1, 0),
                                                               (1024, torch.float16, False, 2048, 32, 8),
                                                               (1536, torch.float32, True, 256, 5, 4),
@@ -677,8 +678,9 @@ def test_quotient_at_rounding_boundaries_f16():
 def test_rolling_contraction_sampled(K, out_dtype, with_bias, T, G, ld_pad):
     """Shapes of whole 256 x 256 tiles, at least eight for every CU, an even number of
     256-code stages: the persistent kernel whose stage stream runs across tile boundaries
-    (2, 4, 6 and 8 stages per tile; several images per tile and several tiles per image;
-    one token set without an id array).  Sampled rows of every kind of tile position
+    (4, 6, 8 and 12 stages per tile; several images per tile and several tiles per image;
+    one token set without an id array; K = 512, two stages, is below the kernel's smallest K
+    and takes the non-persistent kernel).  Sampled rows of every kind of tile position
     against the oracle, bit for bit; Y's padding untouched."""
     M, N = 16384, 8192
     _say(f"[gemm-roll] M={M} K={K} N={N} out={out_dtype} bias={with_bias} T={T} G={G} ld_pad={ld_pad}")
