@@ -432,12 +432,7 @@ __device__ __forceinline__ void dma4s(const float* sbase, unsigned voff, unsigne
 // (row 8*(r/4) + 4*(l/32) + r%4, column l%32).  Every address is a wavefront-uniform row
 // pointer plus one per-lane 32-bit offset.  wtile = &Y[first row][first column] of the
 // wavefront's part.
-// RAW_ROW: sRow holds the plain row scales and the factor 2^-8 that takes the 256 out of the
-// int8 accumulators is applied here (exact).  FENCED: the instruction scheduler may not
-// move code across the pairs of rows, which keeps the registers this function needs at
-// any one time to a few dozen (for a caller that has many values of its own to keep).
-template <typename OUT, int MT, int NT, typename ACC, bool BIAS, bool RAW_ROW = false,
-          bool FENCED = false>
+template <typename OUT, int MT, int NT, typename ACC, bool BIAS>
 __device__ __forceinline__ void tile_store_fast(ACC (&acc)[MT][NT], const float* sRow,
                                                 const float* sCol, const float* sBias, int lane,
                                                 int wm, int wn, OUT* __restrict__ wtile,
@@ -456,8 +451,7 @@ __device__ __forceinline__ void tile_store_fast(ACC (&acc)[MT][NT], const float*
     for (int q = 0; q < 4; ++q) {
       const float4 rs4 =
           *reinterpret_cast<const float4*>(&sRow[wm * 32 * MT + i * 32 + q * 8 + rquad]);
-      const float f8 = RAW_ROW ? 0.00390625f : 1.0f;
-      const float rsv[4] = {rs4.x * f8, rs4.y * f8, rs4.z * f8, rs4.w * f8};
+      const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
       // Two rows at a time.  The NT column blocks of one row are stored back to back:
       // together they cover whole cache lines of Y, written within a few instructions of
       // each other.
@@ -468,13 +462,7 @@ __device__ __forceinline__ void tile_store_fast(ACC (&acc)[MT][NT], const float*
         float y0[NT], y1[NT];
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-          auto a0 = acc[i][j][4 * q + t], a1 = acc[i][j][4 * q + t + 1];
-          if (FENCED) {
-            // the accumulators are read where they are used (the compiler would otherwise
-            // copy whole 16-register fragments out of the accumulation registers up front)
-            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[i][j][4 * q + t]));
-            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[i][j][4 * q + t + 1]));
-          }
+          const auto a0 = acc[i][j][4 * q + t], a1 = acc[i][j][4 * q + t + 1];
           y0[j] = ((float)a0 * rsv[t]) * ws[j];
           y1[j] = ((float)a1 * rsv[t + 1]) * ws[j];
           if (BIAS) {
@@ -497,7 +485,61 @@ __device__ __forceinline__ void tile_store_fast(ACC (&acc)[MT][NT], const float*
 #pragma unroll
           for (int j = 0; j < NT; ++j) store_out<OUT>(row1 + j * 32, y1[j]);
         }
-        if (FENCED) __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+}
+
+// Output phase of the persistent kernel.  Its weight rows are dealt to the column blocks so
+// that column block j of a wavefront holds output columns 4 c + j (c = lane % 32): the four
+// accumulators acc[i][0..3][r] of a lane are then four ADJACENT outputs of one row, and a lane
+// stores them with one instruction (8 bytes of binary16, 16 of binary32) -- 64 stores per
+// wavefront and tile instead of 256, each completing 256 or 512 contiguous bytes of two rows.
+// y = (float(acc) * row scale) * (column scale * 2^-8) (+ bias): the 2^-8 that takes the 256
+// out of the int8 accumulators rides on the column scale (a power of two: the same bits).
+// The accumulators are read where they are used and the scheduler may not move code across
+// rows, which keeps the registers this needs at any one time to a few dozen.  The stores are
+// the compiler's own (non-temporal, see store_out): a 16-byte store reads its data registers
+// over several cycles and the compiler, not inline assembly, knows how long to keep them.
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+template <typename OUT, bool BIAS>
+__device__ __forceinline__ void tile_store_cols4(v16i (&acc)[4][4], const float* sRow, const float* sCol,
+                                                 const float* sBias, int lane, int wm, int wn,
+                                                 const OUT* __restrict__ wtile, long long ld_y) {
+  const int ccol = lane & 31, rquad = (lane >> 5) * 4;
+  const unsigned lane_off = (unsigned)(rquad * (int)ld_y + 4 * ccol);      // elements
+  const float4 w4 = *reinterpret_cast<const float4*>(&sCol[wn * 128 + 4 * ccol]);
+  const float4 b4 = *reinterpret_cast<const float4*>(&sBias[wn * 128 + 4 * ccol]);
+  const float ws[4] = {w4.x * 0.00390625f, w4.y * 0.00390625f, w4.z * 0.00390625f, w4.w * 0.00390625f};
+  const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 rs4 = *reinterpret_cast<const float4*>(&sRow[wm * 128 + i * 32 + q * 8 + rquad]);
+      const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const OUT* row = wtile + (long long)(i * 32 + q * 8 + t) * ld_y;     // wavefront-uniform
+        float y[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int a;
+          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][4 * q + t]));
+          y[j] = ((float)a * rsv[t]) * ws[j];
+          if (BIAS) y[j] = y[j] + bs[j];
+        }
+        if constexpr (sizeof(OUT) == 2) {
+          // packed conversions round pairs of binary32 results to binary16
+          const u2v v = {__builtin_bit_cast(unsigned, round_pair_to_half(y[0], y[1])),
+                         __builtin_bit_cast(unsigned, round_pair_to_half(y[2], y[3]))};
+          __builtin_nontemporal_store(v, reinterpret_cast<u2v*>(const_cast<OUT*>(row) + lane_off));
+        } else {
+          const f4v v = {y[0], y[1], y[2], y[3]};
+          __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(const_cast<OUT*>(row) + lane_off));
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -913,8 +955,16 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_roll(
     const int c = (lane & 7) ^ ((rl0 >> 1) & 7);      // logical piece stored at position l & 7
 #pragma unroll
     for (int i = 0; i < 2 * MT; ++i) offA[i] = (unsigned)((32 * i + rl0) * ld_q + c * 16);
+    // Weight rows are dealt to the column blocks: LDS row 128 wn + 32 j + c' of the B part
+    // (column block j of wavefront column wn, matrix column c') holds weight row
+    // 128 wn + 4 c' + j, so that a lane's four column blocks are four adjacent outputs
+    // (tile_store_cols4).  The swizzle goes by the LDS row, as for A.
 #pragma unroll
-    for (int i = 0; i < 2 * NT; ++i) offB[i] = (unsigned)((32 * i + rl0) * ld_w + c * 16);
+    for (int i = 0; i < 2 * NT; ++i) {
+      const int lrow = 32 * i + rl0;                                   // LDS row, 0 .. 255
+      const int wrow = (lrow & 128) + 4 * (lrow & 31) + ((lrow >> 5) & 3);
+      offB[i] = (unsigned)(wrow * ld_w + c * 16);
+    }
   }
   const unsigned ring_base =
       (unsigned)(size_t)(__attribute__((address_space(3))) uint8_t*)ring;
@@ -1068,11 +1118,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_roll(
       asm volatile("" : "+v"(lane_o));
       OUT* wtile = Y + (long long)(m0 + wm * 128) * ld_y + (n0 + wn * 128);
       if (bias)
-        tile_store_fast<OUT, MT, NT, v16i, true, true, true>(acc, sRow[set], sCol[set], sBias[set], lane_o,
-                                                       wm, wn, wtile, ld_y);
+        tile_store_cols4<OUT, true>(acc, sRow[set], sCol[set], sBias[set], lane_o, wm, wn, wtile, ld_y);
       else
-        tile_store_fast<OUT, MT, NT, v16i, false, true, true>(acc, sRow[set], sCol[set], sBias[set], lane_o,
-                                                        wm, wn, wtile, ld_y);
+        tile_store_cols4<OUT, false>(acc, sRow[set], sCol[set], sBias[set], lane_o, wm, wn, wtile, ld_y);
     }
     curA = nxtA;
     curB = nxtB;
@@ -1154,7 +1202,8 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
   // 8 XCDs, and at least 8 tiles for each of one persistent workgroup per CU: the rolling
   // kernel.  (One workgroup fits a CU, so more workgroups than CUs would run in turns.)
   if (!acc_dump && M % 256 == 0 && N % 256 == 0 && K % 512 == 0 && K >= 1024 && (M / 256) % XCDS == 0 &&
-      256ll * ld_q < (1ll << 32) && 256ll * ld_w < (1ll << 32)) {
+      256ll * ld_q < (1ll << 32) && 256ll * ld_w < (1ll << 32) && ld_y < (1ll << 27) && ld_y % 4 == 0 &&
+      reinterpret_cast<uintptr_t>(Y) % (y_dt == TDQ_F32 ? 16 : 8) == 0) {
     const int wgs = (compute_units() / XCDS) * XCDS;
     if (wgs >= XCDS && big_tiles >= 8ll * wgs) {
       if (y_dt == TDQ_F32)

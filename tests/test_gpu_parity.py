@@ -673,6 +673,7 @@ def test_quotient_at_rounding_boundaries_f16():
                                                               (3072, torch.float16, True, 4096, 1, 0),
                                                               (512, torch.float16, True, 4096, 1, 0),
                                                               (1024, torch.float16, False, 2048, 32, 8),
+                                                              (1024, torch.float16, True, 2048, 4, 2),
                                                               (1536, torch.float32, True, 256, 5, 4),
                                                               (2048, torch.float16, True, 16384, 3, 0)])
 def test_rolling_contraction_sampled(K, out_dtype, with_bias, T, G, ld_pad):
@@ -680,7 +681,8 @@ def test_rolling_contraction_sampled(K, out_dtype, with_bias, T, G, ld_pad):
     256-code stages: the persistent kernel whose stage stream runs across tile boundaries
     (4, 6, 8 and 12 stages per tile; several images per tile and several tiles per image;
     one token set without an id array; K = 512, two stages, is below the kernel's smallest K
-    and takes the non-persistent kernel).  Sampled rows of every kind of tile position
+    and takes the non-persistent kernel, and so does a leading dimension of Y that is not a
+    multiple of 4: the persistent kernel stores four adjacent outputs per lane).  Sampled rows of every kind of tile position
     against the oracle, bit for bit; Y's padding untouched."""
     M, N = 16384, 8192
     _say(f"[gemm-roll] M={M} K={K} N={N} out={out_dtype} bias={with_bias} T={T} G={G} ld_pad={ld_pad}")
