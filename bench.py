@@ -125,20 +125,25 @@ def main():
     seg_names = ["calibrate", "quantize", "linear"]
 
     def step(events=None):
-        for li, L in enumerate(layers):
+        """One pass of the hot path.  `events`: 3 * len(layers) + 1 HIP events, one at every
+        boundary between entry points (the end of one segment is the start of the next, and
+        the last event of a step is the first of the following one)."""
+        k = 0
+        for L in layers:
             lc = L.lc
-            if events is not None:
-                events[li][0].record()
+            if events is not None and k == 0 and events[0] is not None:
+                events[0].record()
             tdq.tdq_calibrate_groups(L.X, L.p, L.ws, out=(L.gid, L.clip, L.scale))
             if events is not None:
-                events[li][1].record()
+                events[k + 1].record()
             tdq.tdq_quantize_act(L.X, L.p, L.gid, L.clip, L.scale, out=L.Q)
             if events is not None:
-                events[li][2].record()
+                events[k + 2].record()
             tdq.tdq_w4a4_linear(L.Q, L.gid, L.scale, lc.B, lc.T, lc.C, L.Qw, L.w_scale, None,
                                 out=L.Y)
             if events is not None:
-                events[li][3].record()
+                events[k + 3].record()
+            k += 3
 
     for _ in range(args.preroll):           # the run's own clock pre-roll, then the asked-for warm-up
         step()
@@ -146,21 +151,25 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    all_events = [[[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in layers]
-                  for _ in range(args.steps)]
+    nseg = 3 * len(layers)
+    flat = [torch.cuda.Event(enable_timing=True) for _ in range(nseg * args.steps + 1)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for k in range(args.steps):
-        step(all_events[k])
+        ev = flat[k * nseg:(k + 1) * nseg + 1]
+        if k > 0:
+            ev = [None] + ev[1:]          # already recorded as the previous step's last event
+        step(ev)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
 
     seg_ms = np.zeros((len(layers), 3))
-    for ev in all_events:
+    for k in range(args.steps):
         for li in range(len(layers)):
-            for s in range(3):
-                seg_ms[li, s] += ev[li][s].elapsed_time(ev[li][s + 1])
+            for sgm in range(3):
+                i = k * nseg + 3 * li + sgm
+                seg_ms[li, sgm] += flat[i].elapsed_time(flat[i + 1])
     seg_ms /= args.steps
 
     act_ms = seg_ms[:, 0].sum() + seg_ms[:, 1].sum()
