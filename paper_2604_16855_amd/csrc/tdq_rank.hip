@@ -41,7 +41,7 @@ constexpr int kSweepThreads = 1024;
 // k_bracket
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kSampleThreads) void k_bracket(
-    const u16* __restrict__ X, long long ld, int T, int C, int G, int W,
+    const u16* __restrict__ X, long long ld, int T, int C, int G, int W, int vec,
     const int* __restrict__ gid, const SetAcc* __restrict__ part, int S, Scalars sc, int pass,
     int keep_base, GroupWork* __restrict__ grp, Bracket* __restrict__ br,
     u32* __restrict__ bhist) {
@@ -55,6 +55,15 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   const int b = idx / G, j = idx - b * G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // the set ids of the first batch of tokens are on their way while the records are merged
+  constexpr int kRankBatch = 16;
+  const int* gb = gid + (long long)b * T;
+  int gv[kRankBatch];
+#pragma unroll
+  for (int u = 0; u < kRankBatch; ++u) {
+    const int t = u * kSampleThreads + tid;
+    gv[u] = t < T ? gb[t] : -1;
+  }
   // every thread merges the assignment's partial records of this set (same loads, same
   // order, same result); one of them stores the working record for the later kernels
   GroupWork w = merge_partials(part, b, j, S, G, C, sc, pass);
@@ -89,45 +98,51 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   const int n_runs = n_sel * rpt;                           // <= kSampleRuns
   const long long m = (long long)n_sel * cw;                // sample size, <= kSampleMax
 
-  // rank of every token inside its set -> the drawn tokens' indices.  The set ids
-  // are fetched kRankBatch rounds at a time so that the loads' latencies overlap.
-  constexpr int kRankBatch = 8;
-  const int* gb = gid + (long long)b * T;
+  // Rank of every token inside its set -> the drawn tokens' indices.  Tokens are taken
+  // kRankBatch rounds of kSampleThreads at a time: all set ids of a batch are loaded
+  // together, every wavefront counts its matches of every round (ballot), the counts meet
+  // in LDS once, and every thread turns them into the rank offsets of its own wavefront --
+  // two barriers per batch instead of two per round.
+  __shared__ u32 wcnt[kRankBatch * kSampleWaves];
   u32 base = 0;
   for (int t0 = 0; t0 < T; t0 += kRankBatch * kSampleThreads) {
-    int gv[kRankBatch];
+    if (t0 > 0) {
 #pragma unroll
-    for (int u = 0; u < kRankBatch; ++u) {
-      const int t = t0 + u * kSampleThreads + tid;
-      gv[u] = t < T ? gb[t] : -1;
+      for (int u = 0; u < kRankBatch; ++u) {
+        const int t = t0 + u * kSampleThreads + tid;
+        gv[u] = t < T ? gb[t] : -1;
+      }
     }
+    u32 within[kRankBatch];
 #pragma unroll
     for (int u = 0; u < kRankBatch; ++u) {
-      if (t0 + u * kSampleThreads >= T) break;               // uniform
-      const int t = t0 + u * kSampleThreads + tid;
-      const bool match = gv[u] == j;
-      const unsigned long long mask = __ballot(match);
-      const u32 within = (u32)__popcll(mask & ((1ull << lane) - 1ull));
-      if (lane == 0) wtot[wave] = (u32)__popcll(mask);
-      __syncthreads();
-      u32 before = 0, total = 0;
+      const unsigned long long mask = __ballot(gv[u] == j);
+      within[u] = (u32)__popcll(mask & ((1ull << lane) - 1ull));
+      if (lane == 0) wcnt[u * kSampleWaves + wave] = (u32)__popcll(mask);
+    }
+    __syncthreads();
+    u32 run = base;
+#pragma unroll
+    for (int u = 0; u < kRankBatch; ++u) {
+      u32 mine = 0;
 #pragma unroll
       for (int w2 = 0; w2 < kSampleWaves; ++w2) {
-        const u32 v = wtot[w2];
-        before += w2 < wave ? v : 0u;
-        total += v;
+        const u32 v = wcnt[u * kSampleWaves + w2];
+        mine = w2 == wave ? run : mine;
+        run += v;
       }
-      if (match) {
-        const u32 rank = base + before + within;
+      if (gv[u] == j) {
+        const int t = t0 + u * kSampleThreads + tid;
+        const u32 rank = mine + within[u];
         const u32 stratum = rank / (u32)stride, first = stratum * (u32)stride;
         const u32 len = (u32)tokens - first < (u32)stride ? (u32)tokens - first : (u32)stride;
         const u32 pick =
             first + (((stratum + 1u) * 2246822519u + (u32)idx * 3266489917u) >> 12) % len;
         if (rank == pick) sel[stratum] = t;
       }
-      base += total;
-      __syncthreads();
     }
+    base = run;
+    __syncthreads();                     // wcnt is rewritten by the next batch; sel is read below
   }
   // table of runs, so that the load loop below has no division in it
   for (int q = tid; q < kSampleRuns; q += kSampleThreads) {
@@ -136,7 +151,10 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
     if (q < n_runs) {
       const int slot = q / rpt, run = q - slot * rpt;
       const int t = sel[slot];
-      const u32 off = ((u32)t * 2654435761u >> 8) % (u32)(C - cw + 1);
+      // (whole 16-byte pieces when the rows allow 16-byte loads: C, cw and the offset are
+      // then multiples of 8 channels)
+      const u32 off = vec ? (((u32)t * 2654435761u >> 8) % (u32)((C - cw) / 8 + 1)) * 8u
+                          : ((u32)t * 2654435761u >> 8) % (u32)(C - cw + 1);
       rb = ((long long)b * T + t) * ld + off + run * kRunLen;
       rl = cw - run * kRunLen;
       rl = rl < kRunLen ? rl : kRunLen;
@@ -148,25 +166,52 @@ __global__ __launch_bounds__(kSampleThreads) void k_bracket(
   }
   __syncthreads();
 
-  // The sample: element e of lane l of wavefront w is channel l % 32 of run
-  // 8 e + 2 w + l / 32.  Loads are issued unconditionally (clamped channel) so that
-  // they overlap; every live key then adds one to an LDS histogram of its top
-  // kSampleBits bits.
+  // The sample.  Every live key adds one to an LDS histogram of its top kSampleBits bits.
+  // Loads are issued unconditionally (from a clamped, valid address) so that they overlap.
   for (int i = tid; i < (1 << kSampleBits); i += kSampleThreads) shist[i] = 0;
-  u32 key[kSamplePerThread];
-  const int half = lane >> 5, cl = lane & 31;
+  if (vec) {
+    // 16-byte pieces of 8 channels: piece p = 256 e + tid is part p % 4 of run p / 4, so a
+    // wavefront's load instruction fetches 16 whole runs of 64 bytes; a run's pieces are
+    // all live or (runs past the end of the table) all dead.
+    constexpr int kPieces = kSampleMax / 8 / kSampleThreads;      // 8 per thread
+    uint4 v[kPieces];
+    bool live[kPieces];
 #pragma unroll
-  for (int e = 0; e < kSamplePerThread; ++e) {
-    const int q = e * (2 * kSampleWaves) + 2 * wave + half;
-    const int rl = run_len[q];
-    const int ch = cl < rl ? cl : (rl > 0 ? rl - 1 : 0);
-    const u32 x = X[run_base[q] + ch];
-    key[e] = cl < rl ? (x & 0x7FFFu) : 0xFFFFu;
+    for (int e = 0; e < kPieces; ++e) {
+      const int p = e * kSampleThreads + tid;
+      const int q = p >> 2, part = p & 3;
+      live[e] = part * 8 < run_len[q];
+      v[e] = *reinterpret_cast<const uint4*>(X + run_base[q] + (live[e] ? part * 8 : 0));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kPieces; ++e) {
+      if (live[e]) {
+        const u32 wd[4] = {v[e].x, v[e].y, v[e].z, v[e].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          atomicAdd(&shist[(wd[i] & 0x7FFFu) >> (15 - kSampleBits)], 1u);
+          atomicAdd(&shist[((wd[i] >> 16) & 0x7FFFu) >> (15 - kSampleBits)], 1u);
+        }
+      }
+    }
+  } else {
+    // element e of lane l of wavefront w is channel l % 32 of run 8 e + 2 w + l / 32
+    u32 key[kSamplePerThread];
+    const int half = lane >> 5, cl = lane & 31;
+#pragma unroll
+    for (int e = 0; e < kSamplePerThread; ++e) {
+      const int q = e * (2 * kSampleWaves) + 2 * wave + half;
+      const int rl = run_len[q];
+      const int ch = cl < rl ? cl : (rl > 0 ? rl - 1 : 0);
+      const u32 x = X[run_base[q] + ch];
+      key[e] = cl < rl ? (x & 0x7FFFu) : 0xFFFFu;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kSamplePerThread; ++e)
+      if (key[e] != 0xFFFFu) atomicAdd(&shist[key[e] >> (15 - kSampleBits)], 1u);
   }
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < kSamplePerThread; ++e)
-    if (key[e] != 0xFFFFu) atomicAdd(&shist[key[e] >> (15 - kSampleBits)], 1u);
   __syncthreads();
 
   // Sample rank that corresponds to rank k of the set, and the histogram bin that
@@ -220,8 +265,10 @@ hipError_t launch_bracket(const void* X, int B, int T, int C, long long ld, int 
                           const int* gid, const void* part, const Scalars& sc, int pass,
                           bool keep_base, GroupWork* grp, Bracket* br, unsigned* bhist,
                           hipStream_t st) {
+  // 16-byte sample loads need rows of whole, aligned 16-byte pieces
+  const int vec = ((reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0 && C % 8 == 0) ? 1 : 0;
   hipLaunchKernelGGL(k_bracket, dim3(B * G), dim3(kSampleThreads), 0, st,
-                     static_cast<const u16*>(X), ld, T, C, G, W, gid,
+                     static_cast<const u16*>(X), ld, T, C, G, W, vec, gid,
                      static_cast<const SetAcc*>(part), assign_split(T), sc, pass,
                      keep_base ? 1 : 0, grp, br, bhist);
   return hipGetLastError();
