@@ -900,14 +900,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_wide(
 
 // ---------------------------------------------------------------------------
 // Rolling variant of the wide-stage kernel for shapes of many whole tiles (M and N
-// multiples of 256, an even number of 256-code stages): a workgroup is persistent and
-// walks its share of the tiles, and the stream of stages never drains between tiles --
-// the loads of the next tile's first two stages are issued during the current tile's last
-// two, like any other stage's, and the next tile's token-set ids and scales are fetched
-// during those two stages into registers.  What a tile boundary
-// still costs is the output phase itself (the matrix pipe idles while a single wavefront
-// per SIMD converts and stores 256 results per lane); the workgroup launch, the two
-// dependent loads of the scales and the first stage's load latency are gone.
+// multiples of 256, an even number, at least four, of 256-code stages): a workgroup is
+// persistent and walks its share of the tiles, and the stream of stages never drains
+// between tiles -- the loads of the next tile's first two stages are issued during the
+// current tile's last two, like any other stage's, and the next tile's token-set ids and
+// scales are fetched during those two stages by direct loads into LDS.  What a tile
+// boundary still costs is the output phase itself (the matrix pipe idles while a single
+// wavefront per SIMD converts and stores 256 results per lane, tile_store_cols4); the
+// workgroup launch, the two dependent loads of the scales and the first stage's load
+// latency are gone.
 //
 // Operand addresses are a uniform 64-bit base (tile, stage) plus a 32-bit per-lane offset
 // that does not depend on the tile, so changing tile costs no vector work.
@@ -1025,8 +1026,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void k_w4a4_gemm_roll(
   // travel global -> LDS by direct loads as well, so no register holds them while the
   // matrix stream runs: `ids` and the column entries first; one stage later (the ids have
   // landed) the row scales that depend on them.  Image of a row: floor((m + 1/2) / T) in
-  // binary64, exact for m, T < 2^31.  An id read from LDS before the first fetch has landed
-  // is clamped into range (its row scale is overwritten before anyone uses it).
+  // binary64, exact for m, T < 2^31.  The id is clamped into range before it indexes the
+  // scales.
   const unsigned lds_of_wave = (unsigned)(wave * 256);
   auto lds_addr = [&](const void* ptr) {
     return __builtin_amdgcn_readfirstlane(
