@@ -36,7 +36,7 @@
 extern "C" {
 #endif
 
-#define TDQ_VERSION 100
+#define TDQ_VERSION 110
 
 typedef enum { TDQ_F16 = 0, TDQ_F32 = 1 } tdq_dtype;
 

@@ -42,7 +42,7 @@ def test_every_declared_entry_point_has_a_binding_of_the_same_name():
 
 
 def test_version_and_strings():
-    assert tdq.version() == 100
+    assert tdq.version() == 110
     assert tdq.status_string(0) == "ok"
     for s in range(-8, 0):
         assert tdq.status_string(s) != "unknown status"
