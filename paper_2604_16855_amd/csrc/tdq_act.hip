@@ -284,7 +284,8 @@ hipError_t launch_token_stats(const void* X, tdq_dtype dt, int M, int C, long lo
 //   key_t = bits(r_t); hi = max key; lo = max(min key, hi - 24 octaves);
 //   gid_t = key_t <= lo ? 0 : (key_t - lo) * G / (hi - lo + 1)      (64-bit integers)
 // then per token set: token count, c_base = max r_t, and the tokens' moments merged about
-// the image's pivot -> sigma = sqrt(S2/n - (S1/n)^2) + eps_std in binary64, rank k = ceil(zr n).
+// a pivot from inside the set (setacc_add) -> sigma = sqrt(S2/n - (S1/n)^2) + eps_std in
+// binary64, rank k = ceil(zr n).
 // Also clears this image's histogram slices and records whether the image holds
 // a non-finite value (its largest range key is Inf/NaN).
 // ---------------------------------------------------------------------------
@@ -314,14 +315,8 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign(
   }
   for (int g = tid; g < G; g += blockDim.x) {      // merge the wavefronts in a fixed order
     SetAcc m;
-    m.s1 = 0.0; m.s2 = 0.0; m.cnt = 0; m.kmax = 0;
-    for (int w = 0; w < NW; ++w) {
-      const SetAcc a = wacc[w * G + g];
-      m.cnt += a.cnt;
-      m.kmax = a.kmax > m.kmax ? a.kmax : m.kmax;
-      m.s1 += a.s1;
-      m.s2 += a.s2;
-    }
+    m.s1 = 0.0; m.s2 = 0.0; m.piv = 0.0; m.cnt = 0; m.kmax = 0;
+    for (int w = 0; w < NW; ++w) setacc_add(m, wacc[w * G + g], (double)C);
     part[((long long)b * S + sub) * G + g] = m;
   }
 }
@@ -349,7 +344,7 @@ int assign_split(int T) {
 hipError_t launch_assign(const float* r, const double* mean, const double* m2, int B, int T, int C,
                          int G, int* gid, void* part, unsigned* img_flag, unsigned* status,
                          hipStream_t st) {
-  int nw = 2048 / G;                       // keep the per-wavefront accumulators under 48 KiB
+  int nw = 1536 / G;                       // keep the per-wavefront accumulators under 48 KiB
   nw = nw > kAssignThreads / 64 ? kAssignThreads / 64 : (nw < 1 ? 1 : nw);
   const size_t lds = (size_t)nw * G * sizeof(SetAcc);
   hipLaunchKernelGGL(k_assign, dim3(assign_split(T), B), dim3(nw * 64), lds, st, r, mean, m2, T, C,

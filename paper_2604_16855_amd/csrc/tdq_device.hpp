@@ -178,28 +178,46 @@ __device__ __forceinline__ double row_pivot(const float* __restrict__ xp, int, b
   return (double)xp[0];
 }
 
-// Partial sums of one token set over part of an image's tokens.
+// Partial sums of one token set over part of an image's tokens, taken about a pivot of the
+// record's own: the mean of the first token that went into it.
 struct SetAcc {
-  double s1, s2;      // sum (x - P_b), sum (x - P_b)^2 with P_b the image's pivot
+  double s1, s2;      // sum (x - piv), sum (x - piv)^2 over the elements of the record's tokens
+  double piv;
   u32 cnt, kmax;      // tokens, largest range key
 };
 
+// a += b (cn = elements per token): b's sums are re-centred on a's pivot,
+//   sum (x - Pa)^2 = sum (x - Pb)^2 + 2 d sum (x - Pb) + n d^2,  d = Pb - Pa.
+// Tokens with one and the same mean add exact zeros, so a set of identical values (the
+// all-zero tokens of a padded image, say) ends with a variance of exactly zero, as the
+// two-pass definition gives it -- sums about a pivot from outside the set would leave a
+// rounding residue of 1e-8 of the pivot's distance in sigma.
+__device__ inline void setacc_add(SetAcc& a, const SetAcc& b, double cn) {
+  if (b.cnt == 0) return;
+  const u32 km = a.kmax > b.kmax ? a.kmax : b.kmax;
+  if (a.cnt == 0) {
+    a = b;
+  } else {
+    const double d = b.piv - a.piv, nb = (double)b.cnt * cn;
+    a.s1 += b.s1 + nb * d;
+    a.s2 += b.s2 + 2.0 * d * b.s1 + nb * d * d;
+    a.cnt += b.cnt;
+  }
+  a.kmax = km;
+}
+
 // Merges the S partial records of set j of image b (in index order, so the result is
 // bitwise repeatable) into the set's working record: n, c_base (DSTG base radius,
-// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2; the records' sums are taken
-// about the image's pivot, which the variance does not depend on), and the rank this pass
-// looks for: k = ceil(zr n), or ceil(p n) in the base-radius pass.
+// Eq. DSTG_clip), sigma = population std + eps_std (Sec. 4.2; the sums are about a pivot,
+// which the variance does not depend on), and the rank this pass looks for: k = ceil(zr n),
+// or ceil(p n) in the base-radius pass.
 __device__ inline GroupWork merge_partials(const SetAcc* __restrict__ part, int b, int j, int S,
                                            int G, int C, const Scalars& sc, int pass) {
-  u32 cnt = 0, cmax = 0;
-  double S1 = 0.0, S2 = 0.0;
-  for (int s = 0; s < S; ++s) {
-    const SetAcc a = part[((long long)b * S + s) * G + j];
-    cnt += a.cnt;
-    cmax = a.kmax > cmax ? a.kmax : cmax;
-    S1 += a.s1;
-    S2 += a.s2;
-  }
+  SetAcc m;
+  m.s1 = 0.0; m.s2 = 0.0; m.piv = 0.0; m.cnt = 0; m.kmax = 0;
+  for (int s = 0; s < S; ++s) setacc_add(m, part[((long long)b * S + s) * G + j], (double)C);
+  const u32 cnt = m.cnt, cmax = m.kmax;
+  const double S1 = m.s1, S2 = m.s2;
   GroupWork w;
   w.tokens = cnt;
   w.n = (long long)cnt * (long long)C;
@@ -247,7 +265,7 @@ __device__ inline void assign_tokens(const float* __restrict__ rb, const double*
   const int NW = blockDim.x >> 6;
   for (int i = tid; i < NW * G; i += blockDim.x) {
     SetAcc z;
-    z.s1 = 0.0; z.s2 = 0.0; z.cnt = 0; z.kmax = 0;
+    z.s1 = 0.0; z.s2 = 0.0; z.piv = 0.0; z.cnt = 0; z.kmax = 0;
     wacc[i] = z;
   }
   u32 kmin = 0xFFFFFFFFu, kmax = 0;
@@ -274,16 +292,13 @@ __device__ inline void assign_tokens(const float* __restrict__ rb, const double*
   __syncthreads();
   const u32 lo = s_lohi[0], hi = s_lohi[1];
   const unsigned long long width = (unsigned long long)(hi - lo) + 1ull;
-  // the image's pivot: the mean of its first token (zero if that is not finite, in
-  // which case the image's results are undefined anyway and its flag is raised)
-  double pb = meanb[0];
-  pb = (pb - pb == 0.0) ? pb : 0.0;
   const double cn = (double)C;
 
   // Wavefront w of workgroup `sub` owns the token batches sub NW + w, + S NW, ... (64
-  // tokens each).  Inside a batch the tokens of one set are summed with a fixed tree and
-  // added to the wavefront's accumulator of that set, sets in order of first appearance:
-  // every floating-point sum has a fixed order, so the result is bitwise repeatable.
+  // tokens each).  Inside a batch the tokens of one set are summed with a fixed tree, about
+  // the mean of the first of them, and added to the wavefront's accumulator of that set
+  // (setacc_add), sets in order of first appearance: every floating-point sum has a fixed
+  // order, so the result is bitwise repeatable.
   SetAcc* mine = wacc + wave * G;
   const int n_batches = (T + 63) / 64;
   // the loads of the next batch are issued before the current one is reduced
@@ -300,8 +315,7 @@ __device__ inline void assign_tokens(const float* __restrict__ rb, const double*
     const int t = bt * 64 + lane;
     const bool live = t < T;
     const u32 k = nk;
-    const double dm = n1 - pb;
-    const double v1 = cn * dm, v2 = n2 + cn * dm * dm;   // the token's sums about the image's pivot
+    const double tmean = n1, tm2 = n2;
     {
       const int tn = t + bstep * 64;
       if (bt + bstep < n_batches && tn < T) {
@@ -323,16 +337,27 @@ __device__ inline void assign_tokens(const float* __restrict__ rb, const double*
       const int gg = __builtin_amdgcn_readlane(g, leader);
       const bool sel = g == gg;
       const unsigned long long m = __ballot(sel);
-      const double a1 = group_sum_f64<64>(sel ? v1 : 0.0);     // totals land in lane 63
-      const double a2 = group_sum_f64<64>(sel ? v2 : 0.0);
+      // pivot of this batch's part of the set: the mean of its first token (zero if that is
+      // not finite: the image's results are then undefined anyway and its flag is raised)
+      const unsigned long long mb = __builtin_bit_cast(unsigned long long, tmean);
+      double piv = __builtin_bit_cast(
+          double, (unsigned long long)(u32)__builtin_amdgcn_readlane((int)(u32)mb, leader) |
+                      ((unsigned long long)(u32)__builtin_amdgcn_readlane((int)(u32)(mb >> 32), leader) << 32));
+      piv = (piv - piv == 0.0) ? piv : 0.0;
+      const double dm = tmean - piv;
+      const double a1 = group_sum_f64<64>(sel ? cn * dm : 0.0);            // totals land in lane 63
+      const double a2 = group_sum_f64<64>(sel ? tm2 + cn * dm * dm : 0.0);
       const u32 km = group_max_u32<64>(sel ? k : 0u);
       if (lane == 63) {
-        SetAcc a = mine[gg];
-        a.s1 += a1;
-        a.s2 += a2;
-        a.cnt += (u32)__popcll(m);
-        a.kmax = km > a.kmax ? km : a.kmax;
-        mine[gg] = a;
+        SetAcc bsum;
+        bsum.s1 = a1; bsum.s2 = a2; bsum.piv = piv; bsum.cnt = (u32)__popcll(m); bsum.kmax = km;
+        if (bt == bt0) {                 // uniform: the wavefront's first batch finds its records empty
+          mine[gg] = bsum;
+        } else {
+          SetAcc a = mine[gg];
+          setacc_add(a, bsum, cn);
+          mine[gg] = a;
+        }
       }
       todo &= ~m;
     }

@@ -101,3 +101,50 @@ def test_sigma_on_offset_feature_maps(dtype, ratio, head, B, C, H, W, G):
     g = dict(gid=gid.cpu().numpy(), clip=clip.cpu().numpy(), scale=scale.cpu().numpy(),
              stats=tdq.stats_to_numpy(stats))
     U.assert_calibration_matches(g, Xt_ref, p)
+
+
+def _constant_sets_input(B, T, C, dtype):
+    """Images whose token sets include sets of IDENTICAL values away from everything else:
+    every other token all zero (the padding of a masked image), every fifth token a constant
+    row, the rest Laplace rows of growing scale; the first token, whatever pivot a kernel
+    might take from it, belongs to none of the constant sets."""
+    rng = np.random.Generator(np.random.PCG64(B * 1000 + T + C))
+    X = rng.laplace(0, 1, (B, T, C)) * (1.0 + 0.05 * np.arange(T))[None, :, None]
+    X[:, 0, :] += 3.0
+    X[:, 1::2, :] = 0.0
+    X[:, 5::10, :] = 40.0 * float(T)          # larger than anything else: the top set, constant
+    np.clip(X, -60000.0, 60000.0, out=X)
+    return X.astype(np.float16 if dtype == "f16" else np.float32)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("B,T,C,G", [(2, 64, 64, 8), (1, 300, 1024, 16), (2, 41, 4096, 4), (1, 2100, 40, 32)])
+def test_sets_of_identical_values_have_zero_dispersion(dtype, B, T, C, G):
+    """A set whose elements are all equal has a population standard deviation of exactly
+    zero (Sec. 4.2), so its sigma is eps_std and the projection ends at the eps floor
+    (Eq. dcrp with the supplementary numerical conventions): the merge of the per-token
+    moments must not leave a rounding residue there.  Through the multi-kernel path, the
+    single launch and the conv-layout sweep."""
+    X = _constant_sets_input(B, T, C, dtype)
+    p = tdq.default_params(G, flags=tdq.FLAG_C1 | tdq.FLAG_C2)
+    _say(f"[constant sets] {dtype} B={B} T={T} C={C} G={G}")
+    g = U.gpu_calibrate(X, p)
+    gid, clip, scale, st = U.assert_calibration_matches(g, X, p)
+    sig = g["stats"]["sigma"].reshape(B, G)
+    zero_sets = [(b, j) for b in range(B) for j in range(G) if st[b][j]["n"] and st[b][j]["sigma"] == np.float32(1e-12)]
+    assert len(zero_sets) >= B, "the input was meant to hold constant sets"
+    for b, j in zero_sets:
+        assert sig[b, j] == np.float32(1e-12), (b, j, sig[b, j])
+    if G <= 64 and T * C <= 400000:      # the single launch takes at most 64 sets; keep the image small
+        gid2, clip2, scale2, stats2, flags2, Q2, ws2 = tdq.tdq_calibrate_quantize_fused(U.to_device(X), p,
+                                                                                      want_stats=True)
+        torch.cuda.synchronize()
+        g2 = dict(gid=gid2.cpu().numpy(), clip=clip2.cpu().numpy(), scale=scale2.cpu().numpy(),
+                  stats=tdq.stats_to_numpy(stats2))
+        U.assert_calibration_matches(g2, X, p)
+    Xc = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 1)).reshape(B, C, T, 1)).to(U.dev())
+    Xt, gid3, clip3, scale3, stats3, ws3 = tdq.tdq_calibrate_groups_chw(Xc, p, want_stats=True)
+    torch.cuda.synchronize()
+    g3 = dict(gid=gid3.cpu().numpy(), clip=clip3.cpu().numpy(), scale=scale3.cpu().numpy(),
+              stats=tdq.stats_to_numpy(stats3))
+    U.assert_calibration_matches(g3, X, p)
