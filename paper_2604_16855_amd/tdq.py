@@ -165,10 +165,17 @@ def _check(rc: int, where: str) -> None:
 
 
 def _btc(X: torch.Tensor) -> Tuple[int, int, int, int]:
-    if (X.dim() != 3 or X.stride(2) != 1
-            or (X.shape[0] > 1 and X.stride(0) != X.shape[1] * X.stride(1))):
+    # the stride of an axis of extent 1 is never used to address anything, and torch is
+    # free to report any value for it
+    if X.dim() != 3 or (X.shape[2] > 1 and X.stride(2) != 1):
         raise ValueError("X must be [B, T, C] with contiguous channels and uniform row stride")
-    return X.shape[0], X.shape[1], X.shape[2], X.stride(1)
+    if X.shape[1] > 1:
+        ld = X.stride(1)
+    else:
+        ld = X.stride(0) if X.shape[0] > 1 else max(X.shape[2], 1)
+    if X.shape[0] > 1 and X.stride(0) != X.shape[1] * ld:
+        raise ValueError("X must be [B, T, C] with contiguous channels and uniform row stride")
+    return X.shape[0], X.shape[1], X.shape[2], ld
 
 
 def workspace_bytes(B: int, T: int, C_: int, dt: int, p: Params) -> int:
@@ -297,10 +304,10 @@ def _bct(X: torch.Tensor) -> Tuple[int, int, int, int, int]:
     """(B, C, T, ld_c, ld_b) of a feature map [B, C, H, W] or [B, C, T] with contiguous
     spatial axes."""
     if X.dim() == 4:
-        if X.stride(3) != 1 or X.stride(2) != X.shape[3]:
+        if (X.shape[3] > 1 and X.stride(3) != 1) or (X.shape[2] > 1 and X.stride(2) != X.shape[3]):
             raise ValueError("the spatial axes of X must be contiguous")
         B, Cc, T = X.shape[0], X.shape[1], X.shape[2] * X.shape[3]
-    elif X.dim() == 3 and X.stride(2) == 1:
+    elif X.dim() == 3 and (X.shape[2] == 1 or X.stride(2) == 1):
         B, Cc, T = X.shape
     else:
         raise ValueError("X must be [B, C, H, W] or [B, C, T] with contiguous tokens")

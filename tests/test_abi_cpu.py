@@ -377,6 +377,27 @@ def test_f6_entries_reject_bad_arguments():
     assert callb(ydt=3) == tdq.ERR_DTYPE
 
 
+def test_binding_shape_helpers_ignore_strides_of_unit_axes():
+    """The marshalling takes leading dimensions from strides; the stride of an axis of
+    extent 1 addresses nothing (torch and numpy report whatever is convenient for it), so
+    it must neither be rejected nor handed on as a leading dimension."""
+    import numpy as np
+    import torch
+    assert tdq._btc(torch.zeros(2, 5, 12)[:, :, :8]) == (2, 5, 8, 12)
+    assert tdq._btc(torch.zeros(3, 1, 10)[:, :, :8]) == (3, 1, 8, 10)       # one token per image
+    assert tdq._btc(torch.zeros(1, 1, 8)) == (1, 1, 8, 8)
+    assert tdq._btc(torch.zeros(4, 6, 3)[:, :, :1]) == (4, 6, 1, 3)         # one channel
+    with pytest.raises(ValueError):
+        tdq._btc(torch.zeros(2, 5, 12)[:, :, ::2])
+    with pytest.raises(ValueError):
+        tdq._btc(torch.zeros(3, 5, 8)[::2])
+    a = torch.from_numpy(np.ascontiguousarray(np.zeros((3, 1, 64, 8), np.float16).transpose(0, 2, 1, 3)))
+    assert a.shape == (3, 64, 1, 8) and tdq._bct(a) == (3, 64, 8, 8, 512)   # H = 1
+    assert tdq._bct(torch.zeros(2, 16, 7, 1)) == (2, 16, 7, 7, 112)         # W = 1
+    with pytest.raises(ValueError):
+        tdq._bct(torch.zeros(2, 16, 7, 4)[:, :, :, ::2])
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py runs on one GPU only and says so."""
     import subprocess
