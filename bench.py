@@ -37,7 +37,7 @@ PEAK_VALU_TLOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # HBM bytes per launch of the fc1 contraction on the default workload: NOT measured by this
 # run but imported from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command (scaled on the 1 GiB copy of the probes leg), profiles/bench_cfg4_hbm_traffic_pmc.txt
-GEMM_FC1_TRAFFIC_BYTES = 1159059064
+GEMM_FC1_TRAFFIC_BYTES = 1159039309
 GEMM_FC1_TRAFFIC_SOURCE = "profiles/bench_cfg4_hbm_traffic_pmc.txt"
 
 
@@ -269,8 +269,9 @@ def _time_events(torch, fn, iters, warm):
 def probes_leg(torch, tdq, dev):
     """What this device sustains in this run, from kernels inside libtdq (tdq_probe): a plain
     read and a plain copy of 1 GiB (the achievable-bandwidth denominators beside the 8 TB/s
-    peak), a register-only stream of the contraction's matrix instruction on all-zero and on
-    random operand bytes (the data-dependent ceiling beside the 5.0 POP/s peak), and
+    peak), a register-only stream of the contraction's matrix instruction in the contraction's
+    4 x 4 operand pattern on all-zero operands, on random bytes and on random int4 codes in
+    the kernels' operand encoding (the data-dependent ceilings beside the 5.0 POP/s peak), and
     register-only v_fma_f32 streams with one and with two wavefronts per SIMD (lanes per
     clock of the vector unit)."""
     res = {}
@@ -285,7 +286,7 @@ def probes_leg(torch, tdq, dev):
     res["copy_1gib"] = {"ms": round(ms, 4), "gbs_read_plus_write": round(2 * gib / (ms * 1e-3) / 1e9, 1)}
     del rd, cp
     grid, iters = 4 * cus, 4000
-    small = buf[:grid * 8192 + 4096]
+    small = buf[:grid * 32768 + 4096]
     ops = grid * 4 * iters * 16 * 65536
     ms = _time_events(torch, lambda: tdq.tdq_probe(tdq.PROBE_MFMA_I8, small, iters, grid), 5, 20)
     res["mfma_i8_zeros"] = {"ms": round(ms, 4), "tops": round(ops / (ms * 1e-3) / 1e12, 1),
@@ -294,6 +295,12 @@ def probes_leg(torch, tdq, dev):
     small.copy_(torch.randint(0, 256, (small.numel(),), dtype=torch.uint8, device=dev, generator=g))
     ms = _time_events(torch, lambda: tdq.tdq_probe(tdq.PROBE_MFMA_I8, small, iters, grid), 5, 20)
     res["mfma_i8_random_bytes"] = {"ms": round(ms, 4), "tops": round(ops / (ms * 1e-3) / 1e12, 1),
+                                   "frac_of_peak": round(ops / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)}
+    # uniformly random int4 codes as the contraction feeds them: the code in the high
+    # nibble of the byte (16 x code), low nibble zero
+    small.copy_(torch.randint(0, 16, (small.numel(),), dtype=torch.uint8, device=dev, generator=g) * 16)
+    ms = _time_events(torch, lambda: tdq.tdq_probe(tdq.PROBE_MFMA_I8, small, iters, grid), 5, 20)
+    res["mfma_i8_random_codes"] = {"ms": round(ms, 4), "tops": round(ops / (ms * 1e-3) / 1e12, 1),
                                    "frac_of_peak": round(ops / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)}
     fb = buf[:8192].view(torch.float32)
     fb[:64] = 0.999

@@ -374,9 +374,10 @@ int tdq_w4a4_linear_blocks_f6(const uint8_t* Qx6, const float* block_scale, int6
  *   TDQ_PROBE_COPY        copies the first half of buf to the second (bytes a multiple of
  *                         8192): bytes / 2 read and bytes / 2 written
  *   TDQ_PROBE_MFMA_I8     grid workgroups of 4 wavefronts, each issuing iters x 16
- *                         v_mfma_i32_32x32x32_i8 (65536 integer operations each) on
- *                         operands taken from buf (its contents choose the data: zeros,
- *                         random bytes); bytes >= 8192 grid + 4096
+ *                         v_mfma_i32_32x32x32_i8 (65536 integer operations each) on four A
+ *                         and four B operands taken from buf (accumulator (i, j) += A[i] B[j]
+ *                         as in the contraction; the contents of buf choose the data: zeros,
+ *                         random bytes, codes times 16); bytes >= 32768 grid + 4096
  *   TDQ_PROBE_FMA_1WAVE,  grid workgroups of 256 / 512 / 1024 threads (1 / 2 / 4 wavefronts
  *   _2WAVES, _4WAVES      per SIMD of a CU), every wavefront issuing iters x 16 independent
  *                         v_fma_f32; buf holds 128 floats (multiplier, addend per lane),

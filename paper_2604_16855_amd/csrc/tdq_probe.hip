@@ -25,31 +25,44 @@ __global__ __launch_bounds__(256) void k_probe_copy(const uint4* __restrict__ p,
   if (i < n) q[i] = p[i];
 }
 
-// Register-only stream of the int8 matrix instruction of the contraction: a wavefront
-// loads its two operands once (16 bytes per lane each, whatever the buffer holds: zeros
-// or random bytes) and issues iters x 16 independent v_mfma_i32_32x32x32_i8, one
-// wavefront per SIMD (256 accumulator registers).
+// Register-only stream of the int8 matrix instruction of the contraction, in the
+// contraction's own pattern: a wavefront loads four A and four B operands once (16 bytes
+// per lane each, whatever the buffer holds: zeros, random bytes, codes in the kernels'
+// operand encoding) and issues iters x 16 v_mfma_i32_32x32x32_i8, accumulator (i, j) +=
+// A[i] B[j], so that both operands change from one instruction to the next as they do in
+// the kernels; one wavefront per SIMD (256 accumulator registers).
 __global__ __launch_bounds__(256, 1) void k_probe_mfma_i8(const uint4* __restrict__ src, int iters,
                                                           int* __restrict__ sink) {
   const int tid = threadIdx.x;
-  const uint4 qa = src[(size_t)blockIdx.x * 512 + tid], qb = src[(size_t)blockIdx.x * 512 + 256 + tid];
-  const v4i a = {(int)qa.x, (int)qa.y, (int)qa.z, (int)qa.w};
-  const v4i b = {(int)qb.x, (int)qb.y, (int)qb.z, (int)qb.w};
-  v16i acc[16];
+  v4i a[4], b[4];
 #pragma unroll
-  for (int t = 0; t < 16; ++t)
+  for (int i = 0; i < 4; ++i) {
+    const uint4 qa = src[((size_t)blockIdx.x * 8 + i) * 256 + tid];
+    const uint4 qb = src[((size_t)blockIdx.x * 8 + 4 + i) * 256 + tid];
+    a[i] = v4i{(int)qa.x, (int)qa.y, (int)qa.z, (int)qa.w};
+    b[i] = v4i{(int)qb.x, (int)qb.y, (int)qb.z, (int)qb.w};
+  }
+  v16i acc[4][4];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[t][r] = 0;
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int t = 0; t < 16; ++t)
-      acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[t], 0, 0, 0);
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
   }
   int x = 0;
 #pragma unroll
-  for (int t = 0; t < 16; ++t)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) x ^= acc[t][r];
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x ^= acc[i][j][r];
   if (x == 0x5bd1e995 && iters < 0) sink[tid] = x;
 }
 
@@ -99,9 +112,9 @@ extern "C" int tdq_probe(int32_t kind, void* buf, size_t bytes, int32_t iters, i
       break;
     }
     case TDQ_PROBE_MFMA_I8: {
-      if (grid < 1 || iters < 1 || bytes < (size_t)grid * 8192 + 4096) return TDQ_ERR_SHAPE;
+      if (grid < 1 || iters < 1 || bytes < (size_t)grid * 32768 + 4096) return TDQ_ERR_SHAPE;
       hipLaunchKernelGGL(k_probe_mfma_i8, dim3(grid), dim3(256), 0, st, static_cast<const uint4*>(buf),
-                         iters, reinterpret_cast<int*>(static_cast<char*>(buf) + (size_t)grid * 8192));
+                         iters, reinterpret_cast<int*>(static_cast<char*>(buf) + (size_t)grid * 32768));
       break;
     }
     case TDQ_PROBE_FMA_1WAVE:

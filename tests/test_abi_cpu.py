@@ -170,7 +170,7 @@ def test_probe_rejects_bad_arguments():
     assert f(9, FAKE, 8192, 1, 1, None) == tdq.ERR_PARAM
     assert f(tdq.PROBE_READ, FAKE, 1000, 1, 1, None) == tdq.ERR_SHAPE
     assert f(tdq.PROBE_COPY, FAKE, 4096, 1, 1, None) == tdq.ERR_SHAPE
-    assert f(tdq.PROBE_MFMA_I8, FAKE, 8192, 1, 4, None) == tdq.ERR_SHAPE      # 4 workgroups need 36 KiB
+    assert f(tdq.PROBE_MFMA_I8, FAKE, 131072, 1, 4, None) == tdq.ERR_SHAPE    # 4 workgroups need 132 KiB
     assert f(tdq.PROBE_FMA_1WAVE, FAKE, 8192, 0, 1, None) == tdq.ERR_SHAPE
 
 
