@@ -508,39 +508,73 @@ __device__ __forceinline__ void tile_store_cols4(v16i (&acc)[4][4], const float*
                                                  const float* sBias, int lane, int wm, int wn,
                                                  const OUT* __restrict__ wtile, long long ld_y) {
   const int ccol = lane & 31, rquad = (lane >> 5) * 4;
-  const unsigned lane_off = (unsigned)(rquad * (int)ld_y + 4 * ccol);      // elements
+  // byte offset of the lane inside the wavefront's 128 rows; 132 rows of ld_y elements fit 32 bits (host)
+  const unsigned lane_off = (unsigned)(rquad * (int)ld_y + 4 * ccol) * (unsigned)sizeof(OUT);
   const float4 w4 = *reinterpret_cast<const float4*>(&sCol[wn * 128 + 4 * ccol]);
   const float4 b4 = *reinterpret_cast<const float4*>(&sBias[wn * 128 + 4 * ccol]);
   const float ws[4] = {w4.x * 0.00390625f, w4.y * 0.00390625f, w4.z * 0.00390625f, w4.w * 0.00390625f};
   const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
+  // Every instruction of a lone wavefront costs an issue slot here (nothing else runs on the
+  // SIMD during the output phase), so the store address costs one vector add per row: scalar
+  // base of the wavefront's part of the tile + a 32-bit lane offset that walks down the rows
+  // (rows 0-3, 8-11, ... of every 32: steps of one row and of five).
+  typedef __attribute__((address_space(1))) char gchar;
+  gchar* const base = reinterpret_cast<gchar*>(reinterpret_cast<unsigned long long>(wtile));
+  unsigned voff = lane_off;
+  const unsigned step1 = (unsigned)ld_y * (unsigned)sizeof(OUT), step5 = 5u * step1;
+  // The four row scales of a group of four rows are read from LDS one group ahead: a lone
+  // wavefront has nothing else to run while it waits for an LDS read.  The accumulators of a
+  // row are copied out of the accumulation registers one row ahead, between the previous
+  // row's last binary32 operation and its conversion / store: the instruction after an asm
+  // statement then never reads what the statement wrote, and no wait state is inserted.
+  const float* rs_src = sRow + wm * 128 + rquad;
+  float4 rs_next = *reinterpret_cast<const float4*>(rs_src);
+  int a_cur[4], a_nxt[4] = {0, 0, 0, 0};
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int j = 0; j < 4; ++j) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a_cur[j]) : "a"(acc[0][j][0]));
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 rs4 = *reinterpret_cast<const float4*>(&sRow[wm * 128 + i * 32 + q * 8 + rquad]);
-      const float rsv[4] = {rs4.x, rs4.y, rs4.z, rs4.w};
+  for (int g = 0; g < 16; ++g) {                   // row group g: rows 8 g .. 8 g + 3 (+ 4 for the upper lanes)
+    const float rsv[4] = {rs_next.x, rs_next.y, rs_next.z, rs_next.w};
+    if (g + 1 < 16) rs_next = *reinterpret_cast<const float4*>(rs_src + (g + 1) * 8);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const OUT* row = wtile + (long long)(i * 32 + q * 8 + t) * ld_y;     // wavefront-uniform
-        float y[4];
+    for (int t = 0; t < 4; ++t) {
+      float y[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          int a;
-          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][4 * q + t]));
-          y[j] = ((float)a * rsv[t]) * ws[j];
-          if (BIAS) y[j] = y[j] + bs[j];
-        }
-        if constexpr (sizeof(OUT) == 2) {
-          // packed conversions round pairs of binary32 results to binary16
-          const u2v v = {__builtin_bit_cast(unsigned, round_pair_to_half(y[0], y[1])),
-                         __builtin_bit_cast(unsigned, round_pair_to_half(y[2], y[3]))};
-          __builtin_nontemporal_store(v, reinterpret_cast<u2v*>(const_cast<OUT*>(row) + lane_off));
-        } else {
-          const f4v v = {y[0], y[1], y[2], y[3]};
-          __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(const_cast<OUT*>(row) + lane_off));
-        }
-        __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < 4; ++j) {
+        y[j] = ((float)a_cur[j] * rsv[t]) * ws[j];
+        if (BIAS) y[j] = y[j] + bs[j];
       }
+      __builtin_amdgcn_sched_barrier(0);
+      // (binary16) the empty asm keeps the last binary32 operations from being merged with
+      // the conversion into mixed-precision instructions that would round only once
+      if constexpr (sizeof(OUT) == 2) asm volatile("" : "+v"(y[0]), "+v"(y[1]), "+v"(y[2]), "+v"(y[3]));
+      {
+        const int r2 = 4 * g + t + 1;              // the next row's accumulators
+        if (r2 < 64) {
+          const int i2 = r2 >> 4, q2 = (r2 >> 2) & 3, t2 = r2 & 3;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a_nxt[j]) : "a"(acc[i2][j][4 * q2 + t2]));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      gchar* dst = base + voff;
+      if constexpr (sizeof(OUT) == 2) {
+        // packed conversions round pairs of binary32 results to binary16
+        typedef float f2v_ __attribute__((ext_vector_type(2)));
+        const f2v_ p0 = {y[0], y[1]}, p1 = {y[2], y[3]};
+        const u2v v = {__builtin_bit_cast(unsigned, __builtin_convertvector(p0, h2v)),
+                       __builtin_bit_cast(unsigned, __builtin_convertvector(p1, h2v))};
+        __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) u2v*>(dst));
+      } else {
+        const f4v v = {y[0], y[1], y[2], y[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) f4v*>(dst));
+      }
+      voff += t == 3 ? step5 : step1;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a_cur[j] = a_nxt[j];
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
@@ -1203,7 +1237,8 @@ hipError_t launch_w4a4_gemm(const uint8_t* Qx, long long ld_q, const int* gid, c
   // 8 XCDs, and at least 8 tiles for each of one persistent workgroup per CU: the rolling
   // kernel.  (One workgroup fits a CU, so more workgroups than CUs would run in turns.)
   if (!acc_dump && M % 256 == 0 && N % 256 == 0 && K % 512 == 0 && K >= 1024 && (M / 256) % XCDS == 0 &&
-      256ll * ld_q < (1ll << 32) && 256ll * ld_w < (1ll << 32) && ld_y < (1ll << 27) && ld_y % 4 == 0 &&
+      256ll * ld_q < (1ll << 32) && 256ll * ld_w < (1ll << 32) && ld_y % 4 == 0 &&
+      132ll * ld_y * (y_dt == TDQ_F32 ? 4 : 2) < (1ll << 32) &&      // 32-bit store offsets inside 128 rows
       reinterpret_cast<uintptr_t>(Y) % (y_dt == TDQ_F32 ? 16 : 8) == 0) {
     const int wgs = (compute_units() / XCDS) * XCDS;
     if (wgs >= XCDS && big_tiles >= 8ll * wgs) {
