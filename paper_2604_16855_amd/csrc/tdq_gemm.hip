@@ -546,32 +546,43 @@ __device__ __forceinline__ void tile_store_cols4(v16i (&acc)[4][4], const float*
         if (BIAS) y[j] = y[j] + bs[j];
       }
       __builtin_amdgcn_sched_barrier(0);
-      // (binary16) the empty asm keeps the last binary32 operations from being merged with
-      // the conversion into mixed-precision instructions that would round only once
-      if constexpr (sizeof(OUT) == 2) asm volatile("" : "+v"(y[0]), "+v"(y[1]), "+v"(y[2]), "+v"(y[3]));
-      {
-        const int r2 = 4 * g + t + 1;              // the next row's accumulators
+      const int r2 = 4 * g + t + 1;                // the next row's accumulators
+      const int i2 = (r2 >> 4) & 3, q2 = (r2 >> 2) & 3, t2 = r2 & 3;
+      if constexpr (sizeof(OUT) == 2) {
+        // One asm statement copies the next row's accumulators out and rounds this row's pairs
+        // of binary32 results to binary16 (packed conversion, to nearest even): the conversion
+        // cannot be merged with the multiplication before it into a mixed-precision
+        // instruction that would round only once, and the instruction after the statement --
+        // the next row's address -- reads nothing the statement wrote.
+        u2v v;
+        if (r2 < 64)
+          asm volatile(
+              "v_accvgpr_read_b32 %2, %10\n\tv_accvgpr_read_b32 %3, %11\n\t"
+              "v_accvgpr_read_b32 %4, %12\n\tv_accvgpr_read_b32 %5, %13\n\t"
+              "v_cvt_pk_f16_f32 %0, %6, %7\n\tv_cvt_pk_f16_f32 %1, %8, %9"
+              : "=&v"(v.x), "=&v"(v.y), "=&v"(a_nxt[0]), "=&v"(a_nxt[1]), "=&v"(a_nxt[2]), "=&v"(a_nxt[3])
+              : "v"(y[0]), "v"(y[1]), "v"(y[2]), "v"(y[3]), "a"(acc[i2][0][4 * q2 + t2]),
+                "a"(acc[i2][1][4 * q2 + t2]), "a"(acc[i2][2][4 * q2 + t2]), "a"(acc[i2][3][4 * q2 + t2]));
+        else
+          asm volatile("v_cvt_pk_f16_f32 %0, %2, %3\n\tv_cvt_pk_f16_f32 %1, %4, %5"
+                       : "=&v"(v.x), "=&v"(v.y)
+                       : "v"(y[0]), "v"(y[1]), "v"(y[2]), "v"(y[3]));
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned voff_next = voff + (t == 3 ? step5 : step1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) u2v*>(base + voff));
+        voff = voff_next;
+      } else {
         if (r2 < 64) {
-          const int i2 = r2 >> 4, q2 = (r2 >> 2) & 3, t2 = r2 & 3;
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a_nxt[j]) : "a"(acc[i2][j][4 * q2 + t2]));
         }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      gchar* dst = base + voff;
-      if constexpr (sizeof(OUT) == 2) {
-        // packed conversions round pairs of binary32 results to binary16
-        typedef float f2v_ __attribute__((ext_vector_type(2)));
-        const f2v_ p0 = {y[0], y[1]}, p1 = {y[2], y[3]};
-        const u2v v = {__builtin_bit_cast(unsigned, __builtin_convertvector(p0, h2v)),
-                       __builtin_bit_cast(unsigned, __builtin_convertvector(p1, h2v))};
-        __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) u2v*>(dst));
-      } else {
+        __builtin_amdgcn_sched_barrier(0);
         const f4v v = {y[0], y[1], y[2], y[3]};
-        __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) f4v*>(dst));
+        __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) f4v*>(base + voff));
+        voff += t == 3 ? step5 : step1;
       }
-      voff += t == 3 ? step5 : step1;
 #pragma unroll
       for (int j = 0; j < 4; ++j) a_cur[j] = a_nxt[j];
       __builtin_amdgcn_sched_barrier(0);
