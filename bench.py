@@ -37,7 +37,7 @@ PEAK_VALU_TLOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # HBM bytes per launch of the fc1 contraction on the default workload: NOT measured by this
 # run but imported from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command (scaled on the 1 GiB copy of the probes leg), profiles/bench_cfg4_hbm_traffic_pmc.txt
-GEMM_FC1_TRAFFIC_BYTES = 1159039309
+GEMM_FC1_TRAFFIC_BYTES = 1159044046
 GEMM_FC1_TRAFFIC_SOURCE = "profiles/bench_cfg4_hbm_traffic_pmc.txt"
 
 
